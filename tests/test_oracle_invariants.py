@@ -1,0 +1,202 @@
+"""Invariants of the oracle's verify/commit protocol and of the lazy cache policy (CPU only).
+
+Section 4.2 of arXiv 2408.15237 (MultiStep, Algorithm 2):
+  I1  multistep over k tokens equals k single steps,
+  I2  multistep from a cached state equals the matching slice of one full scan
+      over exactly the accepted tokens,
+  I3  rollback (partial accept) then re-verify of the same remaining tokens
+      reproduces the first verify's outputs and final state,
+  O3==O1  the lazy three-slot cache (snapshot h_j / h_k, replay of pending
+      tokens, conv ring) is observationally the eager definition,
+  and the integer bookkeeping obeys its invariants on every acceptance sequence.
+"""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workload import Workload, generate
+
+TINY = Workload("tiny", "scalar", batch=2, nheads=4, headdim=3, dstate=5, k=4, rounds=10, io="f32",
+                accept="uniform", ngroups=2, seed=3)
+TINY_DIAG = Workload("tinyd", "diag", batch=2, nheads=6, headdim=1, dstate=4, k=5, rounds=10, io="bf16",
+                     accept="geometric", conv_act="silu", seed=4)
+
+
+def _eager(wl, data, layer=0):
+    lp = data.layers[layer]
+    return oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.conv_act, wl.ngroups)
+
+
+def _lazy(wl, data, layer=0):
+    lp = data.layers[layer]
+    return oracle.LazyMirror(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.kmax_eff, wl.ring_len,
+                             wl.conv_act, wl.ngroups)
+
+
+@pytest.mark.parametrize("wl", [TINY, TINY_DIAG], ids=lambda w: w.name)
+def test_I1_multistep_equals_single_steps(wl):
+    data = generate(wl, rounds=1)
+    rd = data.rounds[0]
+    big = _eager(wl, data)
+    y, xc, snap = big.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
+    one = _eager(wl, data)
+    ones = np.ones(wl.batch, dtype=np.int32)
+    for t in range(wl.k):
+        y1, xc1, _ = one.verify(rd.x_raw[:, t:t + 1], rd.dt[0][:, t:t + 1], rd.B[0][:, t:t + 1], rd.C[0][:, t:t + 1])
+        one.commit(ones)
+        assert np.array_equal(y1[:, 0], y[:, t])
+        assert np.array_equal(xc1[:, 0], xc[:, t])
+        assert np.array_equal(one.h, snap[t + 1])
+
+
+@pytest.mark.parametrize("wl", [TINY, TINY_DIAG], ids=lambda w: w.name)
+def test_I2_schedule_equals_full_scan_of_accepted_tokens(wl):
+    """Re-drafting after a rejection: every round feeds fresh tokens; the committed stream is the accepted ones."""
+    data = generate(wl)
+    lp = data.layers[0]
+    eager = _eager(wl, data)
+    acc_x = [[] for _ in range(wl.batch)]
+    acc_dt = [[] for _ in range(wl.batch)]
+    acc_B = [[] for _ in range(wl.batch)]
+    acc_C = [[] for _ in range(wl.batch)]
+    acc_y = [[] for _ in range(wl.batch)]
+    for rd in data.rounds:
+        y, _, _ = eager.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
+        for b in range(wl.batch):
+            a = int(rd.accepted[b])
+            acc_x[b].append(rd.x_raw[b, :a]); acc_dt[b].append(rd.dt[0][b, :a])
+            acc_B[b].append(rd.B[0][b, :a]); acc_C[b].append(rd.C[0][b, :a]); acc_y[b].append(y[b, :a])
+        eager.commit(rd.accepted)
+    W, Cx = wl.conv_width, wl.conv_channels
+    for b in range(wl.batch):
+        xs = np.concatenate(acc_x[b]); dts = np.concatenate(acc_dt[b])
+        Bs = np.concatenate(acc_B[b]); Cs = np.concatenate(acc_C[b]); ys = np.concatenate(acc_y[b])
+        L = xs.shape[0]
+        assert L == eager.j[b] and L > 0
+        # one pass: library conv over the whole accepted stream, then one scan from h0
+        want_conv = torch.nn.functional.conv1d(
+            torch.from_numpy(xs.astype(np.float64)).T[None], torch.from_numpy(lp.conv_w.astype(np.float64))[:, None, :],
+            None if lp.conv_b is None else torch.from_numpy(lp.conv_b.astype(np.float64)), padding=W - 1, groups=Cx)[0, :, :L].T
+        if wl.conv_act == "silu":
+            want_conv = torch.nn.functional.silu(want_conv)
+        raw = np.concatenate([np.zeros((1, W - 1, Cx)), xs[None]], axis=1)
+        xc_full = oracle.conv_causal(raw, lp.conv_w, lp.conv_b, wl.conv_act, wl.io)
+        tol = 1e-2 if wl.io == "bf16" else 3e-7
+        assert np.allclose(xc_full[0], want_conv.numpy(), rtol=tol, atol=tol)
+        y_full, snap = oracle.scan_tokens(wl.a_mode, lp.h0[b:b + 1], xc_full, dts[None], Bs[None], Cs[None], lp.A, lp.D)
+        assert np.array_equal(y_full[0], ys)
+        assert np.array_equal(snap[L, 0], eager.h[b])
+
+
+@pytest.mark.parametrize("wl", [TINY, TINY_DIAG], ids=lambda w: w.name)
+def test_I3_rollback_then_reverify_reproduces(wl):
+    data = generate(wl, rounds=2)
+    r0, r1 = data.rounds
+    eager = _eager(wl, data)
+    eager.verify(r0.x_raw, r0.dt[0], r0.B[0], r0.C[0])
+    eager.commit(np.full(wl.batch, wl.k, dtype=np.int32))          # warm the conv history
+    y, _, snap = eager.verify(r1.x_raw, r1.dt[0], r1.B[0], r1.C[0])
+    for a in range(wl.k):
+        e2 = _eager(wl, data)
+        e2.verify(r0.x_raw, r0.dt[0], r0.B[0], r0.C[0]); e2.commit(np.full(wl.batch, wl.k, dtype=np.int32))
+        e2.verify(r1.x_raw, r1.dt[0], r1.B[0], r1.C[0]); e2.commit(np.full(wl.batch, a, dtype=np.int32))
+        assert np.array_equal(e2.h, snap[a])
+        y2, _, snap2 = e2.verify(r1.x_raw[:, a:], r1.dt[0][:, a:], r1.B[0][:, a:], r1.C[0][:, a:])
+        assert np.array_equal(y2, y[:, a:])
+        assert np.array_equal(snap2[-1], snap[-1])
+
+
+def _run_both(wl, data, accepted_per_round, ks=None):
+    eager, lazy = _eager(wl, data), _lazy(wl, data)
+    total = np.zeros(wl.batch, dtype=np.int64)
+    for i, rd in enumerate(data.rounds):
+        k = rd.x_raw.shape[1]
+        ye, xce, _ = eager.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
+        yl, xcl = lazy.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
+        assert np.array_equal(xce, xcl)
+        assert np.allclose(ye, yl, rtol=1e-12, atol=1e-13)
+        # verify is idempotent and leaves the bookkeeping alone
+        yl2, _ = lazy.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
+        assert np.array_equal(yl, yl2)
+        acc = np.asarray(accepted_per_round[i])
+        eager.commit(acc); lazy.commit(acc)
+        total += acc
+        bk = lazy.bk
+        assert np.allclose(lazy.materialize(), eager.h, rtol=1e-12, atol=1e-13)
+        for b in range(wl.batch):
+            assert bk.pos[b] + bk.pend[b] == total[b] == eager.j[b]
+            assert bk.cur[b] in (0, 1, 2) and 0 <= bk.pend[b] < k
+            assert bk.conv_head[b] == (wl.conv_width - 2 + total[b]) % wl.ring_len
+            assert bk.last_k[b] == 0
+        assert bk.win_par == (i + 1) % 2 and bk.err == 0
+    return eager, lazy
+
+
+@pytest.mark.parametrize("wl", [TINY, TINY_DIAG], ids=lambda w: w.name)
+def test_lazy_policy_equals_eager_on_random_schedule(wl):
+    data = generate(wl)
+    _run_both(wl, data, [rd.accepted for rd in data.rounds])
+
+
+def test_lazy_policy_with_varying_k_and_kmax():
+    wl = TINY.scaled(kmax=6, rounds=12, seed=9)
+    ks = [1, 6, 3, 6, 2, 5, 1, 1, 6, 4, 2, 6]
+    data = generate(wl, k_schedule=ks)
+    rng = np.random.default_rng(1)
+    acc = [rng.integers(0, k + 1, size=wl.batch) for k in ks]
+    _run_both(wl, data, acc)
+
+
+def test_lazy_policy_all_accept_and_all_reject_streaks():
+    wl = TINY.scaled(rounds=9)
+    data = generate(wl)
+    k = wl.k
+    acc = [[k, k], [k, k], [0, 0], [0, 0], [k, 0], [0, k], [k - 1, 1], [k, k], [0, 0]]
+    _run_both(wl, data, acc)
+
+
+def test_bruteforce_every_acceptance_sequence():
+    """All (k+1)^rounds acceptance sequences for k<=3 over 4 rounds: lazy state == eager state, ints consistent."""
+    for k in (1, 2, 3):
+        wl = Workload("bf", "scalar", batch=1, nheads=2, headdim=2, dstate=3, k=k, rounds=4, io="f32",
+                      accept="uniform", seed=20 + k)
+        data = generate(wl)
+        for seq in itertools.product(range(k + 1), repeat=wl.rounds):
+            _run_both(wl, data, [[a] for a in seq])
+
+
+def test_bookkeeping_slot_semantics_bruteforce():
+    """Track, per slot, which token position its content stands for; the live slot must always stand for `pos`."""
+    R = 8
+    for k in (1, 2, 3):
+        for seq in itertools.product(range(k + 1), repeat=5):
+            bk = oracle.BookkeepingModel(1, R, 4)
+            slot_pos = {0: 0}
+            total = 0
+            for a in seq:
+                cur, pend, pos = bk.cur[0], bk.pend[0], bk.pos[0]
+                bk.verify(k)
+                if pend > 0:
+                    slot_pos[(cur + 1) % 3] = pos + pend          # h_j written
+                slot_pos[(cur + 2) % 3] = pos + pend + k          # h_k written
+                assert (cur + 2) % 3 != cur and (cur + 1) % 3 != cur   # the source slot is never overwritten
+                bk.commit([a])
+                total += a
+                assert slot_pos[bk.cur[0]] == bk.pos[0]
+                assert bk.pos[0] + bk.pend[0] == total
+                assert 0 <= bk.pend[0] < k
+                assert bk.conv_head[0] == (2 + total) % R
+
+
+def test_bookkeeping_error_paths():
+    bk = oracle.BookkeepingModel(2, 8, 4)
+    bk.commit([0, 0])                               # commit without verify: no-op, sticky error
+    assert bk.err == 1 and bk.win_par == 0 and bk.cur == [0, 0]
+    bk = oracle.BookkeepingModel(2, 8, 4)
+    bk.verify(3)
+    bk.commit([7, -2])                              # out of range: clamped to [0, k], sticky error
+    assert bk.err == 1 and bk.pend == [0, 0] and bk.pos == [3, 0] and bk.cur == [2, 0]
+    assert bk.conv_head == [(2 + 3) % 8, 2]

@@ -1,0 +1,263 @@
+"""Pins of the CPU oracle against things other than itself.
+
+The paper (arXiv 2408.15237) prints no worked numeric example of the multi-step
+kernel, so the oracle is pinned to what the mathematics fixes:
+  * the closed form of the recurrence for a scalar (and, element-wise, a
+    diagonal) A  (Section 2.1 Eq. 1 with A_bar = exp(Delta*A), B_bar = Delta*B),
+  * the geometric series for constant inputs,
+  * the linear-attention special case A=0, Delta=1 (Section 2.1: the RNN form of
+    linearized attention; Section 2.2: "N'=1 and identity discretization"),
+  * a brute-force evaluation of Eq. 1 with explicit diagonal matrices,
+  * library routines: torch conv1d for the conv, torch's bf16 cast for rounding.
+Every pin is also run against deliberately wrong variants of the recurrence
+(planted on the CPU, in this file) to show that it would catch them.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+
+def _draw(seed, batch=2, H=4, P=3, N=5, G=2, k=6, mode="scalar"):
+    r = np.random.default_rng(seed)
+    d = dict(
+        h0=r.standard_normal((batch, H, P, N)) * 0.3,
+        x=r.standard_normal((batch, k, H * P)),
+        dt=np.logaddexp(0, r.standard_normal((batch, k, H)) - 1.0),
+        B=r.standard_normal((batch, k, G, N)),
+        C=r.standard_normal((batch, k, G, N)),
+        A=-np.exp(r.uniform(0, np.log(16), size=(H, N) if mode == "diag" else (H,))),
+        D=r.standard_normal(H),
+    )
+    return d
+
+
+def _oracle_scan(mode, d):
+    return oracle.scan_tokens(mode, d["h0"], d["x"], d["dt"], d["B"], d["C"], d["A"], d["D"])
+
+
+# ---- deliberately wrong recurrences (python loops; tiny sizes only) -----------------------------
+def _mutant_scan(kind):
+    def scan(mode, d):
+        h0, x, dt, Bm, Cm, A, D = (d[n] for n in ("h0", "x", "dt", "B", "C", "A", "D"))
+        batch, H, P, N = h0.shape
+        k, G = x.shape[1], Bm.shape[2]
+        snap = np.zeros((k + 1,) + h0.shape)
+        snap[0] = h0
+        y = np.zeros((batch, k, H * P))
+        for b in range(batch):
+            for hd in range(H):
+                g = hd * G // H
+                if kind == "group_modulo":
+                    g = hd % G
+                for t in range(k):
+                    for p in range(P):
+                        xv = x[b, t, hd * P + p]
+                        acc = 0.0
+                        for n in range(N):
+                            a = A[hd, n] if mode == "diag" else A[hd]
+                            dec = np.exp(dt[b, t, hd] * a)
+                            Bv, Cv = Bm[b, t, g, n], Cm[b, t, g, n]
+                            if kind == "sign_A":
+                                dec = np.exp(-dt[b, t, hd] * a)
+                            if kind == "swap_BC":
+                                Bv, Cv = Cv, Bv
+                            inp = dt[b, t, hd] * Bv * xv
+                            if kind == "no_dt_on_B":
+                                inp = Bv * xv
+                            hprev = snap[t, b, hd, p, n]
+                            hn = dec * hprev + inp
+                            if kind == "decay_input_too":
+                                hn = dec * (hprev + inp)
+                            snap[t + 1, b, hd, p, n] = hn
+                            acc += Cv * (hprev if kind == "y_from_old_state" else hn)
+                        y[b, t, hd * P + p] = acc + (0.0 if kind == "drop_D" else D[hd] * xv)
+        return y, snap
+    return scan
+
+
+MUTANTS = ["sign_A", "swap_BC", "no_dt_on_B", "decay_input_too", "y_from_old_state", "drop_D", "group_modulo"]
+
+
+# ---- pin 1: closed form -------------------------------------------------------------------------
+def _closed_form(mode, d):
+    h0, x, dt, Bm, Cm, A, D = (d[n] for n in ("h0", "x", "dt", "B", "C", "A", "D"))
+    batch, H, P, N = h0.shape
+    k, G = x.shape[1], Bm.shape[2]
+    rep = H // G
+    Bh = np.repeat(Bm, rep, axis=2)                      # [b,k,H,N]: head hd -> group hd // (H/G)
+    Ch = np.repeat(Cm, rep, axis=2)
+    xh = x.reshape(batch, k, H, P)
+    Acoef = A[None, None, :, :] if mode == "diag" else A[None, None, :, None]   # [1,1,H,N|1]
+    S = np.cumsum(dt, axis=1)                            # [b,k,H]
+    ys, hs = [], []
+    for T in range(k):
+        # h_T = e^{A S_T} h0 + sum_{t<=T} e^{A (S_T - S_t)} dt_t x_t (x) B_t
+        decay0 = np.exp(Acoef[:, 0] * S[:, T, :, None])                       # [b,H,N|1]
+        hT = decay0[:, :, None, :] * h0
+        w = np.exp(Acoef * (S[:, T:T + 1, :] - S[:, :T + 1, :])[..., None])   # [b,T+1,H,N|1]
+        hT = hT + np.einsum("bthn,bthp->bhpn", w * dt[:, :T + 1, :, None] * Bh[:, :T + 1], xh[:, :T + 1])
+        yT = np.einsum("bhn,bhpn->bhp", Ch[:, T], hT) + D[None, :, None] * xh[:, T]
+        hs.append(hT)
+        ys.append(yT.reshape(batch, H * P))
+    return np.stack(ys, axis=1), np.stack([h0] + hs, axis=0)
+
+
+def _agrees(got, want, rtol=1e-11):
+    (y, s), (y2, s2) = got, want
+    return bool(np.allclose(y, y2, rtol=rtol, atol=1e-12) and np.allclose(s, s2, rtol=rtol, atol=1e-12))
+
+
+@pytest.mark.parametrize("mode", ["scalar", "diag"])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_closed_form(mode, seed):
+    d = _draw(seed, mode=mode)
+    assert _agrees(_oracle_scan(mode, d), _closed_form(mode, d))
+
+
+@pytest.mark.parametrize("kind", MUTANTS)
+def test_closed_form_catches_planted_mistakes(kind):
+    d = _draw(3, mode="scalar")
+    assert _agrees(_mutant_scan("none")("scalar", d), _closed_form("scalar", d))      # the harness itself is sound
+    assert not _agrees(_mutant_scan(kind)("scalar", d), _closed_form("scalar", d))
+
+
+# ---- pin 2: constant input -> geometric series ---------------------------------------------------
+@pytest.mark.parametrize("mode", ["scalar", "diag"])
+def test_constant_input_geometric_series(mode):
+    batch, H, P, N, k = 1, 2, 2, 3, 40
+    r = np.random.default_rng(5)
+    delta = 0.07
+    x1 = r.standard_normal(H * P)
+    B1 = r.standard_normal((1, N))
+    C1 = r.standard_normal((1, N))
+    A = -np.exp(r.uniform(0, 2, size=(H, N) if mode == "diag" else (H,)))
+    D = r.standard_normal(H)
+    h0 = r.standard_normal((batch, H, P, N))
+    d = dict(h0=h0, x=np.tile(x1, (batch, k, 1)), dt=np.full((batch, k, H), delta),
+             B=np.tile(B1, (batch, k, 1, 1)), C=np.tile(C1, (batch, k, 1, 1)), A=A, D=D)
+    y, snap = _oracle_scan(mode, d)
+    a = np.exp(delta * (A if mode == "diag" else A[:, None]))           # [H,N|1]
+    T = k
+    drive = delta * B1[0][None, None, :] * x1.reshape(H, P)[:, :, None]  # [H,P,N]
+    want = a[:, None, :] ** T * h0[0] + drive * (1 - a[:, None, :] ** T) / (1 - a[:, None, :])
+    assert np.allclose(snap[T, 0], want, rtol=1e-10, atol=1e-13)
+    y_want = np.einsum("n,hpn->hp", C1[0], want) + D[:, None] * x1.reshape(H, P)
+    assert np.allclose(y[0, T - 1], y_want.reshape(-1), rtol=1e-10, atol=1e-13)
+
+
+# ---- pin 3: linear attention special case -------------------------------------------------------
+def _linear_attention(d):
+    x, Bm, Cm = d["x"], d["B"], d["C"]
+    batch, k, G, N = Bm.shape
+    H = d["D"].shape[0]
+    P = x.shape[2] // H
+    out = np.zeros_like(x)
+    for b in range(batch):
+        for hd in range(H):
+            g = hd * G // H
+            scores = np.tril(Cm[b, :, g] @ Bm[b, :, g].T)               # [k,k], causal
+            out[b, :, hd * P:(hd + 1) * P] = scores @ x[b, :, hd * P:(hd + 1) * P]
+    return out
+
+
+def _linatt_inputs(seed):
+    d = _draw(seed, batch=2, H=4, P=3, N=5, G=2, k=7)
+    d["A"] = np.zeros_like(d["A"])
+    d["dt"] = np.ones_like(d["dt"])
+    d["D"] = np.zeros_like(d["D"])
+    d["h0"] = np.zeros_like(d["h0"])
+    return d
+
+
+def test_linear_attention_special_case():
+    d = _linatt_inputs(7)
+    y, _ = _oracle_scan("scalar", d)
+    assert np.allclose(y, _linear_attention(d), rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("kind", ["swap_BC", "y_from_old_state", "group_modulo"])
+def test_linear_attention_catches_planted_mistakes(kind):
+    d = _linatt_inputs(7)
+    y, _ = _mutant_scan(kind)("scalar", d)
+    assert not np.allclose(y, _linear_attention(d), rtol=1e-9, atol=1e-9)
+
+
+# ---- pin 4: brute force of Eq. 1 with explicit matrices ------------------------------------------
+@pytest.mark.parametrize("mode", ["scalar", "diag"])
+def test_bruteforce_matrix_form(mode):
+    d = _draw(11, batch=1, H=2, P=2, N=3, G=1, k=4, mode=mode)
+    y, snap = _oracle_scan(mode, d)
+    for hd in range(2):
+        for p in range(2):
+            h = d["h0"][0, hd, p].copy()                                  # state vector in R^N
+            for t in range(4):
+                dt = d["dt"][0, t, hd]
+                a = d["A"][hd] if mode == "diag" else np.full(3, d["A"][hd])
+                Abar = np.diag(np.exp(dt * a))                           # discrete A as a diagonal matrix
+                Bbar = dt * d["B"][0, t, 0]
+                xv = d["x"][0, t, hd * 2 + p]
+                h = Abar @ h + Bbar * xv
+                assert np.allclose(snap[t + 1, 0, hd, p], h, rtol=1e-12, atol=1e-14)
+                assert np.isclose(y[0, t, hd * 2 + p], d["C"][0, t, 0] @ h + d["D"][hd] * xv, rtol=1e-12, atol=1e-14)
+
+
+# ---- pin 5: conv against the library routine ----------------------------------------------------
+@pytest.mark.parametrize("act", ["none", "silu"])
+@pytest.mark.parametrize("use_bias", [True, False])
+def test_conv_matches_torch_conv1d(act, use_bias):
+    r = np.random.default_rng(13)
+    batch, L, Cx, W = 2, 9, 6, 4
+    seq = r.standard_normal((batch, L, Cx))
+    wgt = r.standard_normal((Cx, W))
+    bias = r.standard_normal(Cx) if use_bias else None
+    raw = np.concatenate([np.zeros((batch, W - 1, Cx)), seq], axis=1)
+    got = oracle.conv_causal(raw, wgt, bias, act, "f32")
+    xt = torch.from_numpy(seq).permute(0, 2, 1)                           # [b,C,L]
+    want = torch.nn.functional.conv1d(xt, torch.from_numpy(wgt)[:, None, :],
+                                      None if bias is None else torch.from_numpy(bias),
+                                      padding=W - 1, groups=Cx)[..., :L]
+    if act == "silu":
+        want = torch.nn.functional.silu(want)
+    want = want.permute(0, 2, 1).to(torch.float32).to(torch.float64).numpy()
+    assert np.allclose(got, want, rtol=3e-7, atol=1e-7)
+
+
+def test_conv_tap_order_is_pinned():
+    # one-hot weights: tap w of a width-4 causal conv selects the input 3-w steps back
+    batch, Cx, W, k = 1, 1, 4, 5
+    seq = np.arange(1.0, 1.0 + W - 1 + k).reshape(1, -1, 1)               # raw[i] = i+1
+    for w in range(W):
+        wgt = np.zeros((Cx, W))
+        wgt[0, w] = 1.0
+        got = oracle.conv_causal(seq, wgt, None, "none", "f32")[0, :, 0]
+        assert np.array_equal(got, seq[0, w:w + k, 0])
+
+
+# ---- pin 6: rounding against the library cast ----------------------------------------------------
+def test_bf16_rounding_matches_torch_cast():
+    r = np.random.default_rng(17)
+    v = np.concatenate([
+        r.standard_normal(20000).astype(np.float32),
+        (r.standard_normal(2000) * 1e-30).astype(np.float32),
+        (r.standard_normal(2000) * 1e30).astype(np.float32),
+        np.float32([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -1.0 - 2.0 ** -8, 0.0, 2.0 ** -133, 2.0 ** -134,
+                    3 * 2.0 ** -134, 1e-40, -1e-40, 3.38e38]),
+    ])
+    want = torch.from_numpy(v).to(torch.bfloat16).to(torch.float64).numpy()
+    got = oracle.round_io(v.astype(np.float64), "bf16")
+    assert np.array_equal(got, want)
+
+
+def test_bf16_rounding_is_single_step():
+    # 1 + 2^-8 + 2^-30 lies just above a tie: one rounding goes up; rounding via fp32 first would tie to even (down)
+    x = 1.0 + 2.0 ** -8 + 2.0 ** -30
+    assert oracle.round_io(np.array([x]), "bf16")[0] == 1.0 + 2.0 ** -7
+    assert oracle.round_io(np.array([x]), "f32")[0] == np.float64(np.float32(x))
+
+
+def test_first_conflict_examples():
+    draft = np.array([[1, 2, 3, 4], [1, 2, 3, 4], [9, 2, 3, 4], [1, 2, 3, 4]])
+    target = np.array([[1, 2, 3, 4], [1, 2, 7, 4], [1, 2, 3, 4], [1, 2, 3, 5]])
+    assert oracle.first_conflict(draft, target).tolist() == [4, 2, 0, 3]
