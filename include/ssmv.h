@@ -1,0 +1,182 @@
+/*
+ * ssmv.h - C ABI of the MI355X (gfx950) library for multi-step speculative
+ * verification through a selective state-space (Mamba / Mamba-2) layer.
+ *
+ * The operations follow arXiv 2408.15237:
+ *   Section 2.1, Eq. 1      h_t = A_t h_{t-1} + B_t x_t ,  y_t = C_t^T h_t
+ *   Section 2.2             diagonal A, per-step sampling interval Delta_t; the
+ *                           discrete parameters are rebuilt on the fly as
+ *                           A_bar = exp(Delta_t * A), B_bar = Delta_t * B_t and
+ *                           never stored
+ *   Section 4.2, MultiStep  y_{j:k}, h_j, h_k <- MultiStep(h_i, ., i, j, k; A,B,C,Delta)
+ *   Section 4.2, Alg. 2     Verify keeps ONE cached state and returns h_k when
+ *                           every draft is accepted, else h_j; FirstConflict
+ *   Section 4.3             recomputation of old steps, multi-step decoding of
+ *                           the drafts and caching in ONE kernel; the conv part
+ *                           of the block as a circular buffer
+ *
+ * Conventions
+ *   - Every pointer inside ssmv_cache and every tensor argument is DEVICE memory
+ *     owned by the CALLER (for instance torch tensors).  The library allocates
+ *     and frees no device memory.  Pointers must be 16-byte aligned and stay
+ *     valid until the stream has executed the call.  ssmv_dims and ssmv_cache are
+ *     HOST structs, read during the call only.
+ *   - All calls are asynchronous on `hip_stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) except ssmv_check, which waits for the stream.
+ *   - Arguments are validated on the host before any HIP call is made, so the
+ *     error paths can be exercised without a GPU.  Every function returns an
+ *     ssmv_status; ssmv_last_error() gives the text of the calling thread's
+ *     last failure.
+ *   - h_t is the state AFTER token t.  Per sequence, `pos` tokens are folded
+ *     into the live state slot and `pend` more tokens are accepted but not yet
+ *     folded (they sit in the current half of the pending-token window and are
+ *     replayed by the next verify): the cache is advanced lazily.
+ *   - One cache must not be used from two streams at once.  Per round the calls
+ *     go conv1d_state_update -> ssm_verify_multistep -> ssm_commit_rollback.
+ *     Verify changes neither the live slot nor any integer except last_k, so
+ *     repeating it is legal and gives the same result.
+ */
+#ifndef SSMV_H
+#define SSMV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SSMV_OK = 0,
+    SSMV_EINVAL = -1,        /* null pointer, size or enum out of range                 */
+    SSMV_EUNSUPPORTED = -2,  /* valid request that no compiled kernel covers            */
+    SSMV_EALIGN = -3,        /* a device pointer is not 16-byte aligned                 */
+    SSMV_ESEQUENCE = -4,     /* ssmv_check: the device saw a bad accepted[] / ordering  */
+    SSMV_EHIP = -5           /* a HIP runtime call failed                               */
+} ssmv_status;
+
+enum { SSMV_F32 = 0, SSMV_BF16 = 1 };           /* io_dtype: storage type of tokens, y, conv ring, windows */
+enum { SSMV_A_SCALAR = 0, SSMV_A_DIAG = 1 };    /* a_mode: A[H] (one decay per head) or A[H][N], headdim 1  */
+enum { SSMV_ACT_NONE = 0, SSMV_ACT_SILU = 1 };  /* conv_act                                                */
+
+#define SSMV_KMAX_LIMIT 16      /* largest supported kmax                   */
+#define SSMV_CONV_WIDTH 4       /* the only supported conv width            */
+#define SSMV_CACHE_NPTR 15      /* number of pointers in ssmv_cache         */
+
+typedef struct {
+    int32_t batch;          /* sequences                                                          */
+    int32_t nheads;         /* H  (diag mode: the number of channels)                             */
+    int32_t headdim;        /* P  (diag mode: must be 1)                                          */
+    int32_t dstate;         /* N  in {4, 8, 16, 32, 64, 128, 256}                                 */
+    int32_t ngroups;        /* G  B/C groups; H % G == 0; head hd uses group hd*G/H               */
+    int32_t conv_width;     /* W  must be SSMV_CONV_WIDTH                                         */
+    int32_t conv_channels;  /* Cx must equal H*P                                                  */
+    int32_t kmax;           /* largest k ever passed, 1..SSMV_KMAX_LIMIT                          */
+    int32_t ring_len;       /* R  power of two >= W-1+kmax                                        */
+    int32_t io_dtype;       /* SSMV_F32 | SSMV_BF16                                               */
+    int32_t a_mode;         /* SSMV_A_SCALAR | SSMV_A_DIAG                                        */
+    int32_t conv_act;       /* SSMV_ACT_NONE | SSMV_ACT_SILU                                      */
+} ssmv_dims;
+
+/* The per-layer cache (Section 4.2: one cached state per sequence, advanced lazily;
+ * Section 4.3 footnote: the conv inputs as a circular buffer). */
+typedef struct {
+    float   *state;        /* [3][batch][H][P][N] fp32, N fastest: three slots per sequence         */
+    void    *conv_ring;    /* [batch][R][Cx] io_dtype, channel fastest: raw conv inputs             */
+    void    *win_xc[2];    /* [batch][kmax][Cx]   io_dtype: conv outputs of a round (ping-pong)     */
+    void    *win_dt[2];    /* [batch][kmax][H]    io_dtype                                          */
+    void    *win_B[2];     /* [batch][kmax][G][N] io_dtype                                          */
+    int32_t *cur_slot;     /* [batch] in {0,1,2}: the live slot, holds the state at `pos`           */
+    int32_t *pend;         /* [batch] in [0,kmax): accepted tokens not yet folded into the slot     */
+    int64_t *pos;          /* [batch] tokens folded into state[cur_slot]                            */
+    int32_t *conv_head;    /* [batch] ring index of the newest COMMITTED raw input                  */
+    int32_t *last_k;       /* [batch] k of the verify that has not been committed yet, else 0       */
+    int32_t *win_par;      /* [1] which half of win_* holds the pending tokens                      */
+    int32_t *err_flag;     /* [1] sticky; set by the device on a bad accepted[] or a stray commit   */
+} ssmv_cache;
+
+/* Bytes the caller must allocate for each pointer of ssmv_cache, in declaration
+ * order: state, conv_ring, win_xc[0], win_xc[1], win_dt[0], win_dt[1], win_B[0],
+ * win_B[1], cur_slot, pend, pos, conv_head, last_k, win_par, err_flag. */
+int ssmv_cache_sizes(const ssmv_dims *dims, size_t out_bytes[SSMV_CACHE_NPTR]);
+
+/* Start a cache: slot 0 <- h0 ([batch][H][P][N] fp32 device, NULL = zeros), the
+ * ring's first W-1 entries <- conv_init ([batch][W-1][Cx] io_dtype device, NULL
+ * = zeros: an empty history), conv_head = W-2, every other integer 0
+ * (Algorithm 2, Speculate: h_cache <- h_0, j <- 0). */
+int ssmv_cache_reset(const ssmv_dims *dims, const ssmv_cache *cache, const float *h0,
+                     const void *conv_init, void *hip_stream);
+
+/* Conv roll (Section 4.3 footnote).  Appends the k raw inputs of this round to
+ * the ring after conv_head[b] (older committed entries are kept, entries of a
+ * rejected suffix are simply overwritten by the next round) and writes
+ *   xc[b][t][c] = act(bias[c] + sum_{w<W} wgt[c][w] * raw_b[j_b+1+t-(W-1)+w][c]),
+ * a causal depthwise cross-correlation over the committed inputs followed by
+ * the new ones, accumulated in fp32 and rounded to io_dtype.
+ *   x_raw [batch][k][Cx], wgt [Cx][W], bias [Cx] or NULL, xc_out [batch][k][Cx]:
+ *   all io_dtype, device.  1 <= k <= kmax.  Integers of the cache are not changed. */
+int conv1d_state_update(const ssmv_dims *dims, const ssmv_cache *cache, const void *x_raw,
+                        const void *wgt, const void *bias, int32_t k, void *xc_out,
+                        void *hip_stream);
+
+/* MultiStep of Section 4.2 fused as Section 4.3 asks: in ONE kernel launch, per
+ * sequence, (i) load the live state h_pos and replay the pend[b] pending tokens
+ * from the window, (ii) if pend[b] > 0 store that state h_j into slot
+ * (cur+1)%3, (iii) run the k draft tokens
+ *   h <- exp(dt_t*A) * h + (dt_t * x_t) (x) B_t ,   y_t = C_t . h + D * x_t
+ * (Eq. 1; fp32 state and arithmetic), (iv) store h_k into slot (cur+2)%3 and
+ * this round's (xc, dt, B) into the other half of the window.  Intermediate
+ * states and the discrete parameters live in registers/LDS only.
+ *   xc [batch][k][H*P], dt [batch][k][H], Bm, Cm [batch][k][G][N]: io_dtype, device;
+ *   dt is the final positive step size; A [H] or [H][N] (negative reals) and D [H]:
+ *   fp32, device; y_out [batch][k][H*P] io_dtype.  1 <= k <= kmax.
+ * Sets last_k[b] = k; changes no other integer and not the live slot. */
+int ssm_verify_multistep(const ssmv_dims *dims, const ssmv_cache *cache, const void *xc,
+                         const void *dt, const void *Bm, const void *Cm, const float *A,
+                         const float *D, int32_t k, void *y_out, void *hip_stream);
+
+/* Algorithm 2, "return h_k if k' = k else h_j", as integer bookkeeping.  Per
+ * sequence with a = accepted[b] (device int32 [batch]; values outside
+ * [0,last_k] are clamped and set err_flag):
+ *   a == last_k : cur <- (cur+2)%3, pos <- pos+pend+a, pend <- 0
+ *   pend > 0    : cur <- (cur+1)%3, pos <- pos+pend,   pend <- a
+ *   otherwise   :                                      pend <- a
+ *   always      : conv_head <- (conv_head+a) & (R-1), last_k <- 0
+ * and win_par flips once.  A commit with no verify pending changes nothing and
+ * sets err_flag. */
+int ssm_commit_rollback(const ssmv_dims *dims, const ssmv_cache *cache, const int32_t *accepted,
+                        void *hip_stream);
+
+/* State at pos+pend (live slot with the pending tokens folded in), written to
+ * h_out [batch][H][P][N] fp32 device; the cache is not changed.  For tests and
+ * for handing the state to another engine. */
+int ssmv_materialize(const ssmv_dims *dims, const ssmv_cache *cache, const float *A, float *h_out,
+                     void *hip_stream);
+
+/* FirstConflict of Algorithm 2: accepted[b] = length of the longest prefix on
+ * which draft[b][.] and target[b][.] agree.  draft, target [batch][k] and
+ * accepted [batch]: int32, device. */
+int ssmv_first_conflict(const int32_t *draft, const int32_t *target, int32_t batch, int32_t k,
+                        int32_t *accepted, void *hip_stream);
+
+/* Waits for the stream and returns SSMV_ESEQUENCE if err_flag is set, else SSMV_OK. */
+int ssmv_check(const ssmv_cache *cache, void *hip_stream);
+
+/* Launch shape of the verify kernel.  rows_per_lane in {0 = choose from the
+ * problem size, 1, 2, 4, 8}; waves_per_group in {0 = choose, 1, 2, 4}.  Process-wide;
+ * for tuning and for tests that want to cover every shape. */
+int ssmv_set_tuning(int32_t rows_per_lane, int32_t waves_per_group);
+
+/* Plain device copy kernel used to calibrate bandwidth counters and the
+ * achievable HBM ceiling: reads n_bytes from src, writes them to dst0 and, if
+ * dst1 is not NULL, to dst1 as well (the verify kernel's read-S / write-2S
+ * pattern).  n_bytes must be a multiple of 16. */
+int ssmv_copy_probe(const void *src, void *dst0, void *dst1, size_t n_bytes, void *hip_stream);
+
+const char *ssmv_last_error(void);
+const char *ssmv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSMV_H */

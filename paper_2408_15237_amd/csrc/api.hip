@@ -1,0 +1,321 @@
+// The C ABI of libssmv: argument validation on the host (before any HIP call, so the error
+// paths run without a GPU), choice of the launch shape, and kernel launches.
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "ssmv_internal.h"
+
+using namespace ssmv;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(int hip_code, const char *what)
+{
+    return fail(SSMV_EHIP, "%s: %s", what, hipGetErrorString((hipError_t)hip_code));
+}
+
+std::atomic<int> g_tune_rows{0};
+std::atomic<int> g_tune_waves{0};
+
+bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+size_t io_bytes(int io) { return io == SSMV_BF16 ? 2 : 4; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_dims(const ssmv_dims *d)
+{
+    if (!d) return fail(SSMV_EINVAL, "dims is NULL");
+    if (d->batch < 1 || d->nheads < 1 || d->headdim < 1 || d->dstate < 1 || d->ngroups < 1)
+        return fail(SSMV_EINVAL, "batch/nheads/headdim/dstate/ngroups must be >= 1");
+    if (d->io_dtype != SSMV_F32 && d->io_dtype != SSMV_BF16) return fail(SSMV_EINVAL, "io_dtype %d unknown", d->io_dtype);
+    if (d->a_mode != SSMV_A_SCALAR && d->a_mode != SSMV_A_DIAG) return fail(SSMV_EINVAL, "a_mode %d unknown", d->a_mode);
+    if (d->conv_act != SSMV_ACT_NONE && d->conv_act != SSMV_ACT_SILU) return fail(SSMV_EINVAL, "conv_act %d unknown", d->conv_act);
+    if (d->nheads % d->ngroups != 0) return fail(SSMV_EINVAL, "nheads %d not a multiple of ngroups %d", d->nheads, d->ngroups);
+    if ((long)d->conv_channels != (long)d->nheads * d->headdim)
+        return fail(SSMV_EINVAL, "conv_channels %d != nheads*headdim %ld", d->conv_channels, (long)d->nheads * d->headdim);
+    if (d->kmax < 1) return fail(SSMV_EINVAL, "kmax %d < 1", d->kmax);
+    if (d->kmax > SSMV_KMAX_LIMIT) return fail(SSMV_EUNSUPPORTED, "kmax %d > %d", d->kmax, SSMV_KMAX_LIMIT);
+    if (d->conv_width != SSMV_CONV_WIDTH) return fail(SSMV_EUNSUPPORTED, "conv_width %d (only %d)", d->conv_width, SSMV_CONV_WIDTH);
+    if (!is_pow2(d->ring_len) || d->ring_len < d->conv_width - 1 + d->kmax)
+        return fail(SSMV_EINVAL, "ring_len %d must be a power of two >= conv_width-1+kmax = %d", d->ring_len,
+                    d->conv_width - 1 + d->kmax);
+    if (d->dstate != 16 && d->dstate != 32 && d->dstate != 64 && d->dstate != 128 && d->dstate != 256)
+        return fail(SSMV_EUNSUPPORTED, "dstate %d (supported: 16, 32, 64, 128, 256)", d->dstate);
+    if (d->a_mode == SSMV_A_DIAG) {
+        if (d->headdim != 1) return fail(SSMV_EINVAL, "diag mode needs headdim 1 (got %d)", d->headdim);
+        if (d->ngroups != 1) return fail(SSMV_EUNSUPPORTED, "diag mode needs ngroups 1 (got %d)", d->ngroups);
+        if (d->dstate > 64) return fail(SSMV_EUNSUPPORTED, "diag mode supports dstate <= 64 (got %d)", d->dstate);
+    }
+    const double slot = (double)d->batch * d->nheads * d->headdim * d->dstate;
+    if (slot * 3 > 2.0e10) return fail(SSMV_EUNSUPPORTED, "state of %.3g elements is beyond what one cache may hold", slot * 3);
+    if ((double)d->batch * d->nheads * d->headdim > 2.0e9) return fail(SSMV_EUNSUPPORTED, "too many state rows");
+    return SSMV_OK;
+}
+
+int check_ptr(const void *p, const char *name)
+{
+    if (!p) return fail(SSMV_EINVAL, "%s is NULL", name);
+    if (!aligned16(p)) return fail(SSMV_EALIGN, "%s (%p) is not 16-byte aligned", name, p);
+    return SSMV_OK;
+}
+
+int check_cache(const ssmv_cache *c)
+{
+    if (!c) return fail(SSMV_EINVAL, "cache is NULL");
+    int rc;
+#define CK(field) if ((rc = check_ptr(c->field, "cache." #field)) != SSMV_OK) return rc
+    CK(state); CK(conv_ring);
+    CK(win_xc[0]); CK(win_xc[1]); CK(win_dt[0]); CK(win_dt[1]); CK(win_B[0]); CK(win_B[1]);
+    CK(cur_slot); CK(pend); CK(pos); CK(conv_head); CK(last_k); CK(win_par); CK(err_flag);
+#undef CK
+    return SSMV_OK;
+}
+
+int check_k(const ssmv_dims *d, int k)
+{
+    if (k < 1 || k > d->kmax) return fail(SSMV_EINVAL, "k %d outside [1, kmax=%d]", k, d->kmax);
+    return SSMV_OK;
+}
+
+// rows per lane and waves per workgroup for the verify kernel
+int choose_shape(const ssmv_dims *d, int lds_tokens, int k, VerifyShape *out, int *rows_wg, int *tiles)
+{
+    const bool diag = d->a_mode == SSMV_A_DIAG;
+    const int N = d->dstate;
+    const int rpi = rows_per_instr(N);
+    const int dom = diag ? d->nheads : d->headdim;          // rows of the tiled domain
+    const long domains = diag ? d->batch : (long)d->batch * d->nheads;
+    int R = g_tune_rows.load(), waves = g_tune_waves.load();
+    if (R != 0 && !verify_shape_supported(N, R, diag)) return fail(SSMV_EUNSUPPORTED, "rows_per_lane %d not built for dstate %d", R, N);
+    const bool autoR = R == 0, autoW = waves == 0;
+    auto fits = [&](int r, int w) {
+        VerifyParams q{};
+        q.lds_tokens = lds_tokens; q.k = k; q.N = N; q.rows_wg = w * rpi * r;
+        return verify_lds_bytes(q, diag) <= 64 * 1024;
+    };
+    if (autoR || autoW) {
+        // Largest tile that still leaves >= 1024 workgroups (4 per compute unit) and does not
+        // exceed the domain; otherwise the smallest tile, to spread a small problem over the chip.
+        int bestR = -1, bestW = -1;
+        long best_rows = -1;
+        for (int r = 8; r >= 1; r /= 2) {
+            if (!autoR && r != R) continue;
+            if (!verify_shape_supported(N, r, diag)) continue;
+            for (int w = 4; w >= 1; w /= 2) {
+                if (!autoW && w != waves) continue;
+                if (!fits(r, w)) continue;
+                const int rw = w * rpi * r;
+                const long t = (dom + rw - 1) / rw;
+                const long groups = domains * t;
+                const bool wasteful = rw > dom && rw > rpi;     // tile larger than the domain
+                long score;
+                if (groups >= 1024 && !wasteful) score = 1000000L + rw;      // big tiles first
+                else score = wasteful ? -rw : 500000L - rw;                   // else the more groups the better
+                if (score > best_rows) { best_rows = score; bestR = r; bestW = w; }
+            }
+        }
+        if (bestR < 0) return fail(SSMV_EUNSUPPORTED, "no launch shape fits (dstate %d, tokens %d)", N, lds_tokens);
+        R = bestR; waves = bestW;
+    } else if (!fits(R, waves)) {
+        return fail(SSMV_EUNSUPPORTED, "LDS need of the requested shape exceeds 64 KiB");
+    }
+    if (waves != 1 && waves != 2 && waves != 4) return fail(SSMV_EINVAL, "waves_per_group %d not in {1,2,4}", waves);
+    out->rows_per_lane = R;
+    out->waves = waves;
+    *rows_wg = waves * rpi * R;
+    *tiles = (dom + *rows_wg - 1) / *rows_wg;
+    return SSMV_OK;
+}
+
+void fill_verify(VerifyParams &p, const ssmv_dims *d, const ssmv_cache *c)
+{
+    p.batch = d->batch; p.H = d->nheads; p.P = d->headdim; p.N = d->dstate; p.G = d->ngroups; p.kmax = d->kmax;
+    p.io = d->io_dtype;
+    p.state = c->state;
+    p.slot_stride = (size_t)d->batch * d->nheads * d->headdim * d->dstate;
+    for (int i = 0; i < 2; ++i) { p.win_xc[i] = c->win_xc[i]; p.win_dt[i] = c->win_dt[i]; p.win_B[i] = c->win_B[i]; }
+    p.cur_slot = c->cur_slot; p.pend = c->pend; p.last_k = c->last_k; p.win_par = c->win_par;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ssmv_last_error(void) { return g_err; }
+const char *ssmv_version(void) { return "ssmv 0.1 (gfx950)"; }
+
+int ssmv_set_tuning(int32_t rows_per_lane, int32_t waves_per_group)
+{
+    if (rows_per_lane != 0 && rows_per_lane != 1 && rows_per_lane != 2 && rows_per_lane != 4 && rows_per_lane != 8)
+        return fail(SSMV_EINVAL, "rows_per_lane %d not in {0,1,2,4,8}", rows_per_lane);
+    if (waves_per_group != 0 && waves_per_group != 1 && waves_per_group != 2 && waves_per_group != 4)
+        return fail(SSMV_EINVAL, "waves_per_group %d not in {0,1,2,4}", waves_per_group);
+    g_tune_rows.store(rows_per_lane);
+    g_tune_waves.store(waves_per_group);
+    return SSMV_OK;
+}
+
+int ssmv_cache_sizes(const ssmv_dims *d, size_t out_bytes[SSMV_CACHE_NPTR])
+{
+    int rc = check_dims(d);
+    if (rc != SSMV_OK) return rc;
+    if (!out_bytes) return fail(SSMV_EINVAL, "out_bytes is NULL");
+    const size_t e = io_bytes(d->io_dtype);
+    const size_t B = d->batch, H = d->nheads, P = d->headdim, N = d->dstate, G = d->ngroups, K = d->kmax, Cx = d->conv_channels;
+    size_t *o = out_bytes;
+    o[0] = 3 * B * H * P * N * sizeof(float);
+    o[1] = B * d->ring_len * Cx * e;
+    o[2] = o[3] = B * K * Cx * e;
+    o[4] = o[5] = B * K * H * e;
+    o[6] = o[7] = B * K * G * N * e;
+    o[8] = B * sizeof(int32_t);   // cur_slot
+    o[9] = B * sizeof(int32_t);   // pend
+    o[10] = B * sizeof(int64_t);  // pos
+    o[11] = B * sizeof(int32_t);  // conv_head
+    o[12] = B * sizeof(int32_t);  // last_k
+    o[13] = sizeof(int32_t);      // win_par
+    o[14] = sizeof(int32_t);      // err_flag
+    return SSMV_OK;
+}
+
+int ssmv_cache_reset(const ssmv_dims *d, const ssmv_cache *c, const float *h0, const void *conv_init, void *hip_stream)
+{
+    int rc;
+    if ((rc = check_dims(d)) != SSMV_OK) return rc;
+    if ((rc = check_cache(c)) != SSMV_OK) return rc;
+    if (h0 && !aligned16(h0)) return fail(SSMV_EALIGN, "h0 is not 16-byte aligned");
+    if (conv_init && !aligned16(conv_init)) return fail(SSMV_EALIGN, "conv_init is not 16-byte aligned");
+    ResetParams p{};
+    p.batch = d->batch; p.Cx = d->conv_channels; p.R = d->ring_len; p.W = d->conv_width; p.io = d->io_dtype;
+    p.state_elems = (size_t)d->batch * d->nheads * d->headdim * d->dstate;
+    p.state = c->state; p.h0 = h0; p.ring = c->conv_ring; p.conv_init = conv_init;
+    p.cur_slot = c->cur_slot; p.pend = c->pend; p.conv_head = c->conv_head; p.last_k = c->last_k;
+    p.win_par = c->win_par; p.err_flag = c->err_flag; p.pos = c->pos;
+    const int hc = launch_reset(p, (hipStream_t)hip_stream);
+    return hc == 0 ? SSMV_OK : hip_fail(hc, "ssmv_cache_reset");
+}
+
+int conv1d_state_update(const ssmv_dims *d, const ssmv_cache *c, const void *x_raw, const void *wgt, const void *bias,
+                        int32_t k, void *xc_out, void *hip_stream)
+{
+    int rc;
+    if ((rc = check_dims(d)) != SSMV_OK) return rc;
+    if ((rc = check_cache(c)) != SSMV_OK) return rc;
+    if ((rc = check_k(d, k)) != SSMV_OK) return rc;
+    if ((rc = check_ptr(x_raw, "x_raw")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(wgt, "wgt")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(xc_out, "xc_out")) != SSMV_OK) return rc;
+    if (bias && !aligned16(bias)) return fail(SSMV_EALIGN, "bias is not 16-byte aligned");
+    ConvParams p{};
+    p.batch = d->batch; p.Cx = d->conv_channels; p.k = k; p.R = d->ring_len; p.io = d->io_dtype; p.act = d->conv_act;
+    p.ring = c->conv_ring; p.conv_head = c->conv_head; p.x_raw = x_raw; p.wgt = wgt; p.bias = bias; p.xc = xc_out;
+    const int hc = launch_conv(p, (hipStream_t)hip_stream);
+    return hc == 0 ? SSMV_OK : hip_fail(hc, "conv1d_state_update");
+}
+
+int ssm_verify_multistep(const ssmv_dims *d, const ssmv_cache *c, const void *xc, const void *dt, const void *Bm,
+                         const void *Cm, const float *A, const float *D, int32_t k, void *y_out, void *hip_stream)
+{
+    int rc;
+    if ((rc = check_dims(d)) != SSMV_OK) return rc;
+    if ((rc = check_cache(c)) != SSMV_OK) return rc;
+    if ((rc = check_k(d, k)) != SSMV_OK) return rc;
+    if ((rc = check_ptr(xc, "xc")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(dt, "dt")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(Bm, "Bm")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(Cm, "Cm")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(A, "A")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(D, "D")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(y_out, "y_out")) != SSMV_OK) return rc;
+    VerifyParams p{};
+    fill_verify(p, d, c);
+    p.k = k;
+    p.lds_tokens = d->kmax - 1 + k;
+    p.xc = xc; p.dt = dt; p.Bm = Bm; p.Cm = Cm; p.A = A; p.D = D; p.y = y_out; p.h_out = nullptr;
+    VerifyShape shape;
+    if ((rc = choose_shape(d, p.lds_tokens, k, &shape, &p.rows_wg, &p.tiles)) != SSMV_OK) return rc;
+    const int hc = d->a_mode == SSMV_A_DIAG ? launch_verify_diag(p, shape, (hipStream_t)hip_stream)
+                                             : launch_verify_scalar(p, shape, (hipStream_t)hip_stream);
+    return hc == 0 ? SSMV_OK : hip_fail(hc, "ssm_verify_multistep");
+}
+
+int ssmv_materialize(const ssmv_dims *d, const ssmv_cache *c, const float *A, float *h_out, void *hip_stream)
+{
+    int rc;
+    if ((rc = check_dims(d)) != SSMV_OK) return rc;
+    if ((rc = check_cache(c)) != SSMV_OK) return rc;
+    if ((rc = check_ptr(A, "A")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(h_out, "h_out")) != SSMV_OK) return rc;
+    VerifyParams p{};
+    fill_verify(p, d, c);
+    p.k = 0;
+    p.lds_tokens = d->kmax - 1 > 0 ? d->kmax - 1 : 1;
+    p.A = A; p.D = A;   // D is not read when k == 0
+    p.h_out = h_out;
+    VerifyShape shape;
+    if ((rc = choose_shape(d, p.lds_tokens, 0, &shape, &p.rows_wg, &p.tiles)) != SSMV_OK) return rc;
+    const int hc = d->a_mode == SSMV_A_DIAG ? launch_verify_diag(p, shape, (hipStream_t)hip_stream)
+                                             : launch_verify_scalar(p, shape, (hipStream_t)hip_stream);
+    return hc == 0 ? SSMV_OK : hip_fail(hc, "ssmv_materialize");
+}
+
+int ssm_commit_rollback(const ssmv_dims *d, const ssmv_cache *c, const int32_t *accepted, void *hip_stream)
+{
+    int rc;
+    if ((rc = check_dims(d)) != SSMV_OK) return rc;
+    if ((rc = check_cache(c)) != SSMV_OK) return rc;
+    if (!accepted) return fail(SSMV_EINVAL, "accepted is NULL");
+    if ((reinterpret_cast<uintptr_t>(accepted) & 3u) != 0) return fail(SSMV_EALIGN, "accepted is not 4-byte aligned");
+    CommitParams p{};
+    p.batch = d->batch; p.R = d->ring_len;
+    p.cur_slot = c->cur_slot; p.pend = c->pend; p.conv_head = c->conv_head; p.last_k = c->last_k;
+    p.win_par = c->win_par; p.err_flag = c->err_flag; p.pos = c->pos; p.accepted = accepted;
+    const int hc = launch_commit(p, (hipStream_t)hip_stream);
+    return hc == 0 ? SSMV_OK : hip_fail(hc, "ssm_commit_rollback");
+}
+
+int ssmv_first_conflict(const int32_t *draft, const int32_t *target, int32_t batch, int32_t k, int32_t *accepted,
+                        void *hip_stream)
+{
+    if (!draft || !target || !accepted) return fail(SSMV_EINVAL, "draft/target/accepted is NULL");
+    if (batch < 1 || k < 1) return fail(SSMV_EINVAL, "batch %d and k %d must be >= 1", batch, k);
+    const int hc = launch_first_conflict(draft, target, batch, k, accepted, (hipStream_t)hip_stream);
+    return hc == 0 ? SSMV_OK : hip_fail(hc, "ssmv_first_conflict");
+}
+
+int ssmv_check(const ssmv_cache *c, void *hip_stream)
+{
+    if (!c || !c->err_flag) return fail(SSMV_EINVAL, "cache or cache.err_flag is NULL");
+    int32_t flag = 0;
+    hipError_t e = hipMemcpyAsync(&flag, c->err_flag, sizeof(flag), hipMemcpyDeviceToHost, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail((int)e, "ssmv_check copy");
+    e = hipStreamSynchronize((hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail((int)e, "ssmv_check sync");
+    if (flag != 0) return fail(SSMV_ESEQUENCE, "device flagged a bad accepted[] value or a commit without a verify");
+    return SSMV_OK;
+}
+
+int ssmv_copy_probe(const void *src, void *dst0, void *dst1, size_t n_bytes, void *hip_stream)
+{
+    int rc;
+    if ((rc = check_ptr(src, "src")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(dst0, "dst0")) != SSMV_OK) return rc;
+    if (dst1 && !aligned16(dst1)) return fail(SSMV_EALIGN, "dst1 is not 16-byte aligned");
+    if (n_bytes == 0 || (n_bytes & 15u) != 0) return fail(SSMV_EINVAL, "n_bytes %zu must be a positive multiple of 16", n_bytes);
+    const int hc = launch_copy_probe(src, dst0, dst1, n_bytes, (hipStream_t)hip_stream);
+    return hc == 0 ? SSMV_OK : hip_fail(hc, "ssmv_copy_probe");
+}
+
+}  // extern "C"

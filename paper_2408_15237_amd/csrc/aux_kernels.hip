@@ -1,0 +1,267 @@
+// Small kernels around the fused verification kernel: the conv roll over the circular buffer
+// (Section 4.3 footnote of arXiv 2408.15237), the integer commit/rollback of Algorithm 2,
+// FirstConflict, cache reset, and a plain copy kernel for bandwidth calibration.
+#include "ssmv_internal.h"
+
+namespace ssmv {
+
+// ---- 16-byte vector access in the I/O storage type ------------------------------------------------
+
+template <int IO, int VEC>
+struct IoVec;
+
+template <>
+struct IoVec<SSMV_F32, 4> {
+    static __device__ __forceinline__ void load(const void *base, size_t idx, float (&v)[4])
+    {
+        const float4 t = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(base) + idx);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    }
+    static __device__ __forceinline__ void store(void *base, size_t idx, const float (&v)[4])
+    {
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(base) + idx) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+
+template <>
+struct IoVec<SSMV_BF16, 8> {
+    static __device__ __forceinline__ void load(const void *base, size_t idx, float (&v)[8])
+    {
+        const uint4 t = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(base) + idx);
+        const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ void store(void *base, size_t idx, const float (&v)[8])
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16_bits(v[2 * i]) | ((uint32_t)f32_to_bf16_bits(v[2 * i + 1]) << 16);
+        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(base) + idx) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+
+template <int IO>
+struct IoVec<IO, 1> {
+    static __device__ __forceinline__ void load(const void *base, size_t idx, float (&v)[1]) { v[0] = load_io(base, idx, IO); }
+    static __device__ __forceinline__ void store(void *base, size_t idx, const float (&v)[1]) { store_io(base, idx, v[0], IO); }
+};
+
+// round a value to the storage type and back, so that what is fed on matches what is stored
+template <int IO>
+__device__ __forceinline__ float round_io(float v)
+{
+    if (IO == SSMV_BF16) return bf16_bits_to_f32(f32_to_bf16_bits(v));
+    return v;
+}
+
+// ---- conv roll -----------------------------------------------------------------------------------
+// One thread owns VEC adjacent channels of one sequence for all k tokens: it reads the W-1 newest
+// committed ring entries, then per new token appends the raw input to the ring and emits the
+// width-4 causal dot product.  Ring slots written are head+1..head+k, slots read are
+// head-2..head, disjoint because R >= W-1+kmax.
+template <int IO, int VEC>
+__global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
+{
+    constexpr int W = SSMV_CONV_WIDTH;
+    const int chunks = p.Cx / VEC;
+    const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= (long)p.batch * chunks) return;
+    const int b = (int)(gid / chunks);
+    const int c0 = (int)(gid - (long)b * chunks) * VEC;
+    const int head = p.conv_head[b];
+    const int mask = p.R - 1;
+
+    float hist[W - 1][VEC];
+#pragma unroll
+    for (int i = 0; i < W - 1; ++i)
+        IoVec<IO, VEC>::load(p.ring, ((size_t)b * p.R + ((head - (W - 2) + i) & mask)) * p.Cx + c0, hist[i]);
+
+    float w[VEC][W];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c)
+#pragma unroll
+        for (int i = 0; i < W; ++i) w[c][i] = load_io(p.wgt, (size_t)(c0 + c) * W + i, IO);
+    float bias[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) bias[c] = p.bias ? load_io(p.bias, c0 + c, IO) : 0.f;
+
+    for (int t = 0; t < p.k; ++t) {
+        float x[VEC], out[VEC];
+        IoVec<IO, VEC>::load(p.x_raw, ((size_t)b * p.k + t) * p.Cx + c0, x);
+        IoVec<IO, VEC>::store(p.ring, ((size_t)b * p.R + ((head + 1 + t) & mask)) * p.Cx + c0, x);
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            float s = bias[c];
+            s = fmaf(w[c][0], hist[0][c], s);
+            s = fmaf(w[c][1], hist[1][c], s);
+            s = fmaf(w[c][2], hist[2][c], s);
+            s = fmaf(w[c][3], x[c], s);
+            if (p.act == SSMV_ACT_SILU) s = s / (1.f + expf(-s));
+            out[c] = s;
+            hist[0][c] = hist[1][c];
+            hist[1][c] = hist[2][c];
+            hist[2][c] = x[c];
+        }
+        IoVec<IO, VEC>::store(p.xc, ((size_t)b * p.k + t) * p.Cx + c0, out);
+    }
+}
+
+int launch_conv(const ConvParams &p, hipStream_t stream)
+{
+    const int vec = p.io == SSMV_BF16 ? 8 : 4;
+    const bool vec_ok = (p.Cx % vec) == 0;
+    const long threads = (long)p.batch * (vec_ok ? p.Cx / vec : p.Cx);
+    const int block = 256;
+    const unsigned grid = (unsigned)((threads + block - 1) / block);
+    if (p.io == SSMV_BF16) {
+        if (vec_ok) hipLaunchKernelGGL((conv_kernel<SSMV_BF16, 8>), dim3(grid), dim3(block), 0, stream, p);
+        else hipLaunchKernelGGL((conv_kernel<SSMV_BF16, 1>), dim3(grid), dim3(block), 0, stream, p);
+    } else {
+        if (vec_ok) hipLaunchKernelGGL((conv_kernel<SSMV_F32, 4>), dim3(grid), dim3(block), 0, stream, p);
+        else hipLaunchKernelGGL((conv_kernel<SSMV_F32, 1>), dim3(grid), dim3(block), 0, stream, p);
+    }
+    return (int)hipGetLastError();
+}
+
+// ---- commit / rollback (Algorithm 2: "return h_k if k'=k else h_j", lazily advanced cache) -----------
+__global__ __launch_bounds__(256) void commit_kernel(const CommitParams p)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= p.batch) return;
+    const int lk = p.last_k[b];
+    if (lk == 0) {                       // nothing was verified: leave everything, flag it
+        *p.err_flag = 1;
+        return;
+    }
+    int a = p.accepted[b];
+    if (a < 0 || a > lk) {
+        *p.err_flag = 1;
+        a = a < 0 ? 0 : lk;
+    }
+    const int cur = p.cur_slot[b];
+    const int pd = p.pend[b];
+    if (a == lk) {                       // every draft accepted: h_k becomes the live state
+        p.cur_slot[b] = (cur + 2) % 3;
+        p.pos[b] += pd + a;
+        p.pend[b] = 0;
+    } else if (pd > 0) {                 // rejection: fall back to h_j, the accepted prefix stays pending
+        p.cur_slot[b] = (cur + 1) % 3;
+        p.pos[b] += pd;
+        p.pend[b] = a;
+    } else {                             // rejection with nothing pending: the live slot already is h_j
+        p.pend[b] = a;
+    }
+    p.conv_head[b] = (p.conv_head[b] + a) & (p.R - 1);
+    p.last_k[b] = 0;
+    if (b == 0) *p.win_par ^= 1;
+}
+
+int launch_commit(const CommitParams &p, hipStream_t stream)
+{
+    const int block = 256;
+    hipLaunchKernelGGL(commit_kernel, dim3((p.batch + block - 1) / block), dim3(block), 0, stream, p);
+    return (int)hipGetLastError();
+}
+
+// ---- FirstConflict ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void first_conflict_kernel(const int32_t *draft, const int32_t *target, int batch, int k,
+                                                             int32_t *accepted)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= batch) return;
+    int n = 0;
+    while (n < k && draft[(size_t)b * k + n] == target[(size_t)b * k + n]) ++n;
+    accepted[b] = n;
+}
+
+int launch_first_conflict(const int32_t *draft, const int32_t *target, int batch, int k, int32_t *accepted, hipStream_t stream)
+{
+    const int block = 256;
+    hipLaunchKernelGGL(first_conflict_kernel, dim3((batch + block - 1) / block), dim3(block), 0, stream, draft, target, batch, k,
+                       accepted);
+    return (int)hipGetLastError();
+}
+
+// ---- reset (fill kernels, so that a caller may capture it in a graph) -----------------------------------
+__global__ __launch_bounds__(256) void reset_state_kernel(const ResetParams p)
+{
+    const size_t n4 = p.state_elems / 4;       // N is a multiple of 4, so is the slot size
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (p.h0) v = reinterpret_cast<const float4 *>(p.h0)[i];
+        reinterpret_cast<float4 *>(p.state)[i] = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void reset_ring_kernel(const ResetParams p)
+{
+    const size_t n = (size_t)p.batch * p.R * p.Cx;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const int c = (int)(i % p.Cx);
+        const size_t br = i / p.Cx;
+        const int slot = (int)(br % p.R);
+        const int b = (int)(br / p.R);
+        float v = 0.f;
+        if (p.conv_init && slot < p.W - 1) v = load_io(p.conv_init, ((size_t)b * (p.W - 1) + slot) * p.Cx + c, p.io);
+        store_io(p.ring, i, v, p.io);
+    }
+    const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (size_t b = gid; b < (size_t)p.batch; b += stride) {
+        p.cur_slot[b] = 0;
+        p.pend[b] = 0;
+        p.pos[b] = 0;
+        p.conv_head[b] = p.W - 2;
+        p.last_k[b] = 0;
+    }
+    if (gid == 0) {
+        *p.win_par = 0;
+        *p.err_flag = 0;
+    }
+}
+
+int launch_reset(const ResetParams &p, hipStream_t stream)
+{
+    const int block = 256;
+    size_t n4 = p.state_elems / 4;
+    unsigned g1 = (unsigned)((n4 + block - 1) / block);
+    if (g1 > 8192) g1 = 8192;
+    if (g1 == 0) g1 = 1;
+    hipLaunchKernelGGL(reset_state_kernel, dim3(g1), dim3(block), 0, stream, p);
+    size_t n = (size_t)p.batch * p.R * p.Cx;
+    unsigned g2 = (unsigned)((n + block - 1) / block);
+    if (g2 > 8192) g2 = 8192;
+    if (g2 == 0) g2 = 1;
+    hipLaunchKernelGGL(reset_ring_kernel, dim3(g2), dim3(block), 0, stream, p);
+    return (int)hipGetLastError();
+}
+
+// ---- plain copy: read n bytes, write them once or twice ----------------------------------------------
+__global__ __launch_bounds__(256) void copy_probe_kernel(const float4 *__restrict__ src, float4 *__restrict__ dst0,
+                                                         float4 *__restrict__ dst1, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+        const float4 v = src[i];
+        dst0[i] = v;
+        if (dst1) dst1[i] = v;
+    }
+}
+
+int launch_copy_probe(const void *src, void *dst0, void *dst1, size_t n_bytes, hipStream_t stream)
+{
+    const size_t n16 = n_bytes / 16;
+    const int block = 256;
+    size_t want = (n16 + block - 1) / block;
+    unsigned grid = (unsigned)(want > 256 * 16 ? 256 * 16 : (want ? want : 1));
+    hipLaunchKernelGGL(copy_probe_kernel, dim3(grid), dim3(block), 0, stream, reinterpret_cast<const float4 *>(src),
+                       reinterpret_cast<float4 *>(dst0), reinterpret_cast<float4 *>(dst1), n16);
+    return (int)hipGetLastError();
+}
+
+}  // namespace ssmv

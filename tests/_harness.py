@@ -1,0 +1,148 @@
+"""Shared helpers of the GPU parity tests: run a seeded workload through the HIP library (C ABI)
+and through the fp64 oracle, round by round, and compare.
+
+Error metric (per tensor): max_i |g_i - r_i| / max(|r_i|, rms(r)).  The rms floor keeps
+near-cancelled dot products from dividing by ~0.  Bounds: 1e-5 for fp32 I/O, 2e-2 for bf16 I/O
+with fp32 state.  Integers (slot, pending count, position, ring head, parity) must be equal.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2408_15237_amd as ssmv
+from workload import Workload, WorkloadData
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+TORCH_IO = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def rel_err(got, ref) -> float:
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    floor = np.sqrt(np.mean(ref * ref))
+    den = np.maximum(np.abs(ref), max(floor, 1e-30))
+    return float(np.max(np.abs(got - ref) / den))
+
+
+def to_dev(a, io: str):
+    """float32 container holding io-representable values -> device tensor of the io type (exact)."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda").to(TORCH_IO[io]).contiguous()
+
+
+def to_host(t) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def dims_of(wl: Workload):
+    return ssmv.make_dims(wl.batch, wl.nheads, wl.headdim, wl.dstate, ngroups=wl.ngroups, kmax=wl.kmax_eff,
+                          ring_len=wl.ring_len, io=wl.io, a_mode=wl.a_mode, conv_act=wl.conv_act)
+
+
+class HipLayer:
+    """One layer of the HIP path: device parameters, its cache, and the three calls of a round."""
+
+    def __init__(self, wl: Workload, lp, conv_init=None):
+        self.wl = wl
+        self.dims = dims_of(wl)
+        self.cache = ssmv.LayerCache.allocate(self.dims)
+        self.A = torch.from_numpy(lp.A).to("cuda").contiguous()
+        self.D = torch.from_numpy(lp.D).to("cuda").contiguous()
+        self.conv_w = to_dev(lp.conv_w, wl.io)
+        self.conv_b = None if lp.conv_b is None else to_dev(lp.conv_b, wl.io)
+        self.h0 = torch.from_numpy(lp.h0).to("cuda").contiguous()
+        self.conv_init = None if conv_init is None else to_dev(conv_init, wl.io)
+        self.reset()
+
+    def reset(self):
+        ssmv.ssmv_cache_reset(self.dims, self.cache.c, self.h0, self.conv_init)
+
+    def conv(self, x_raw):
+        k = x_raw.shape[1]
+        xc = torch.empty_like(x_raw)
+        ssmv.conv1d_state_update(self.dims, self.cache.c, x_raw, self.conv_w, self.conv_b, k, xc)
+        return xc
+
+    def verify(self, xc, dt, Bm, Cm):
+        k = xc.shape[1]
+        y = torch.empty_like(xc)
+        ssmv.ssm_verify_multistep(self.dims, self.cache.c, xc, dt, Bm, Cm, self.A, self.D, k, y)
+        return y
+
+    def commit(self, accepted_dev):
+        ssmv.ssm_commit_rollback(self.dims, self.cache.c, accepted_dev)
+
+    def materialize(self):
+        wl = self.wl
+        h = torch.empty((wl.batch, wl.nheads, wl.headdim, wl.dstate), dtype=torch.float32, device="cuda")
+        ssmv.ssmv_materialize(self.dims, self.cache.c, self.A, h)
+        return h
+
+
+def eager_oracle(wl: Workload, lp, conv_init=None):
+    return oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.conv_act, wl.ngroups,
+                              conv_init=conv_init)
+
+
+def run_parity(wl: Workload, data: WorkloadData, layer: int = 0, x_override=None, check_state_every: int = 1,
+               conv_init=None, reverify: bool = False):
+    """Full parity of one layer over all rounds of `data`.  Returns the worst errors seen."""
+    lp = data.layers[layer]
+    tol = TOL[wl.io]
+    hip = HipLayer(wl, lp, conv_init=conv_init)
+    ora = eager_oracle(wl, lp, conv_init=conv_init)
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
+    worst = {"y": 0.0, "xc": 0.0, "h": 0.0}
+    for i, rd in enumerate(data.rounds):
+        x_raw = rd.x_raw if x_override is None else x_override[i]
+        k = x_raw.shape[1]
+        y_ref, xc_ref, _ = ora.verify(x_raw, rd.dt[layer], rd.B[layer], rd.C[layer])
+        d_x, d_dt = to_dev(x_raw, wl.io), to_dev(rd.dt[layer], wl.io)
+        d_B, d_C = to_dev(rd.B[layer], wl.io), to_dev(rd.C[layer], wl.io)
+        xc = hip.conv(d_x)
+        y = hip.verify(xc, d_dt, d_B, d_C)
+        if reverify:                                   # verify twice: must be idempotent
+            y2 = hip.verify(xc, d_dt, d_B, d_C)
+            assert torch.equal(y, y2), "verify is not idempotent (round %d)" % i
+        bk.verify(k)
+        e_xc, e_y = rel_err(to_host(xc), xc_ref), rel_err(to_host(y), y_ref)
+        assert e_xc <= tol, "round %d: conv output error %.3g > %.3g" % (i, e_xc, tol)
+        assert e_y <= tol, "round %d: y error %.3g > %.3g" % (i, e_y, tol)
+        acc = rd.accepted
+        hip.commit(torch.from_numpy(acc.astype(np.int32)).to("cuda"))
+        ora.commit(acc)
+        bk.commit(acc)
+        ints = hip.cache.ints()
+        assert ints["cur_slot"].tolist() == bk.cur, "round %d: cur_slot" % i
+        assert ints["pend"].tolist() == bk.pend, "round %d: pend" % i
+        assert ints["pos"].tolist() == bk.pos, "round %d: pos" % i
+        assert ints["conv_head"].tolist() == bk.conv_head, "round %d: conv_head" % i
+        assert ints["last_k"].tolist() == bk.last_k, "round %d: last_k" % i
+        assert ints["win_par"] == bk.win_par and ints["err_flag"] == bk.err == 0, "round %d: parity/err" % i
+        if check_state_every and (i % check_state_every == 0 or i == len(data.rounds) - 1):
+            e_h = rel_err(to_host(hip.materialize()), ora.h)
+            assert e_h <= tol, "round %d: state error %.3g > %.3g" % (i, e_h, tol)
+            worst["h"] = max(worst["h"], e_h)
+        worst["y"], worst["xc"] = max(worst["y"], e_y), max(worst["xc"], e_xc)
+    ssmv.ssmv_check(hip.cache.c)
+    return worst
+
+
+def slice_workload(wl: Workload, data: WorkloadData, seqs, heads, layer: int = 0):
+    """The sub-problem made of the given sequences and heads (independent recurrences), for the oracle."""
+    assert wl.ngroups == 1
+    P = wl.headdim
+    ch = np.concatenate([np.arange(h * P, (h + 1) * P) for h in heads])
+    lp = data.layers[layer]
+    from workload.generate import LayerParams, RoundInputs
+    sub_lp = LayerParams(A=lp.A[heads], D=lp.D[heads], conv_w=lp.conv_w[ch],
+                         conv_b=None if lp.conv_b is None else lp.conv_b[ch], h0=lp.h0[seqs][:, heads])
+    sub_wl = wl.scaled(batch=len(seqs), nheads=len(heads), layers=1)
+    rounds = []
+    for rd in data.rounds:
+        rounds.append(RoundInputs(x_raw=rd.x_raw[seqs][:, :, ch], dt=[rd.dt[layer][seqs][:, :, heads]],
+                                  B=[rd.B[layer][seqs]], C=[rd.C[layer][seqs]], accepted=rd.accepted[seqs]))
+    return sub_wl, WorkloadData(wl=sub_wl, layers=[sub_lp], rounds=rounds), ch

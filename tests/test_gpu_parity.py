@@ -1,0 +1,215 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle, element by element.
+
+Sizes are chosen so that the oracle finishes in seconds while the kernels still see several
+workgroup tiles and ragged tails; the full benchmark shapes are covered in test_gpu_fullsize.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2408_15237_amd as ssmv
+from workload import CONFIGS, Workload, generate
+
+from _harness import HipLayer, TOL, dims_of, rel_err, run_parity, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _auto_tuning():
+    ssmv.ssmv_set_tuning(0, 0)
+    yield
+    ssmv.ssmv_set_tuning(0, 0)
+
+
+def test_cfg0_tiny_fp32():
+    wl = CONFIGS["cfg0"]
+    worst = run_parity(wl, generate(wl), reverify=True)
+    print("cfg0 worst errors", worst)
+
+
+def test_cfg1_shape_reduced_batch_bf16():
+    wl = CONFIGS["cfg1"].scaled(nheads=4, rounds=16)
+    run_parity(wl, generate(wl), reverify=True)
+
+
+def test_cfg1_shape_reduced_fp32():
+    wl = CONFIGS["cfg1"].scaled(nheads=3, rounds=16, io="f32", batch=2)
+    run_parity(wl, generate(wl))
+
+
+@pytest.mark.parametrize("rows,waves", [(r, w) for r in (1, 2, 4, 8) for w in (1, 2, 4)])
+def test_every_launch_shape_scalar(rows, waves):
+    ssmv.ssmv_set_tuning(rows, waves)
+    wl = Workload("shape", "scalar", batch=3, nheads=3, headdim=72, dstate=64, k=4, rounds=8, io="f32",
+                  accept="uniform", seed=rows * 10 + waves)
+    run_parity(wl, generate(wl))
+
+
+@pytest.mark.parametrize("rows,waves", [(r, w) for r in (1, 2, 4) for w in (1, 2, 4)])
+def test_every_launch_shape_diag(rows, waves):
+    ssmv.ssmv_set_tuning(rows, waves)
+    wl = Workload("shaped", "diag", batch=2, nheads=203, headdim=1, dstate=16, k=5, rounds=8, io="f32",
+                  accept="geometric", seed=rows * 10 + waves)
+    run_parity(wl, generate(wl))
+
+
+@pytest.mark.parametrize("N,P,G,io", [(16, 24, 1, "f32"), (32, 20, 2, "bf16"), (64, 40, 2, "f32"),
+                                      (128, 12, 1, "f32"), (256, 6, 4, "bf16"), (64, 1, 1, "f32"), (16, 100, 4, "bf16")])
+def test_state_sizes_groups_and_ragged_tiles(N, P, G, io):
+    wl = Workload("sz", "scalar", batch=2, nheads=4, headdim=P, dstate=N, k=3, rounds=10, io=io, accept="uniform",
+                  ngroups=G, kmax=5, seed=N + P)
+    run_parity(wl, generate(wl))
+
+
+@pytest.mark.parametrize("N,io", [(16, "bf16"), (32, "f32"), (64, "bf16")])
+def test_diag_mode(N, io):
+    wl = CONFIGS["cfg2"].scaled(nheads=1000, dstate=N, rounds=12, io=io, batch=2)
+    run_parity(wl, generate(wl), reverify=True)
+
+
+@pytest.mark.parametrize("act,bias", [("silu", True), ("none", False), ("silu", False)])
+def test_conv_variants_and_initial_history(act, bias):
+    wl = Workload("conv", "scalar", batch=2, nheads=2, headdim=36, dstate=16, k=4, rounds=8, io="bf16",
+                  accept="uniform", conv_act=act, conv_bias=bias, seed=5)
+    data = generate(wl)
+    init = np.random.default_rng(1).standard_normal((wl.batch, wl.conv_width - 1, wl.conv_channels)).astype(np.float32)
+    from workload import round_to_io
+    run_parity(wl, data, conv_init=round_to_io(init, wl.io))
+
+
+def test_conv_scalar_channel_path():
+    # channel count that is no multiple of the 16-byte vector: the one-channel-per-thread kernel
+    wl = Workload("convs", "scalar", batch=2, nheads=3, headdim=7, dstate=16, k=4, rounds=6, io="bf16",
+                  accept="uniform", seed=6)
+    run_parity(wl, generate(wl))
+
+
+def test_varying_k_up_to_the_limit():
+    ks = [1, 16, 7, 16, 2, 9, 1, 1, 16, 4]
+    wl = Workload("kmax", "scalar", batch=3, nheads=2, headdim=32, dstate=64, k=4, kmax=16, rounds=len(ks), io="f32",
+                  accept="uniform", seed=8)
+    run_parity(wl, generate(wl, k_schedule=ks))
+
+
+def test_varying_k_diag():
+    ks = [3, 16, 1, 12, 16, 5]
+    wl = Workload("kmaxd", "diag", batch=2, nheads=70, headdim=1, dstate=16, k=4, kmax=16, rounds=len(ks), io="bf16",
+                  accept="uniform", seed=9)
+    run_parity(wl, generate(wl, k_schedule=ks))
+
+
+@pytest.mark.parametrize("accept", ["all", "none"])
+def test_accept_streaks(accept):
+    wl = Workload("streak", "scalar", batch=2, nheads=2, headdim=64, dstate=64, k=4, rounds=7, io="bf16",
+                  accept=accept, seed=10)
+    run_parity(wl, generate(wl))
+
+
+def test_mixed_pending_counts_in_one_batch():
+    wl = Workload("mixed", "scalar", batch=9, nheads=2, headdim=64, dstate=64, k=6, rounds=12, io="f32",
+                  accept="uniform", seed=11)
+    data = generate(wl)
+    # force every pend value 0..k-1 to occur together in one launch
+    data.rounds[0].accepted[:] = [0, 1, 2, 3, 4, 5, 6, 3, 0]
+    run_parity(wl, data)
+
+
+def test_k1_single_step_rounds():
+    wl = Workload("k1", "scalar", batch=2, nheads=2, headdim=64, dstate=64, k=1, rounds=10, io="f32",
+                  accept="uniform", seed=12)
+    run_parity(wl, generate(wl))
+
+
+def test_multistep_equals_single_steps_on_gpu():
+    """I1 on the device: one k-token verify + full accept == k single-token rounds (same kernels, tolerance)."""
+    wl = Workload("i1", "scalar", batch=2, nheads=2, headdim=64, dstate=64, k=4, rounds=1, io="f32",
+                  accept="all", seed=13)
+    data = generate(wl)
+    rd, lp = data.rounds[0], data.layers[0]
+    big, one = HipLayer(wl, lp), HipLayer(wl, lp)
+    dx, ddt, dB, dC = (to_dev(a, wl.io) for a in (rd.x_raw, rd.dt[0], rd.B[0], rd.C[0]))
+    y = big.verify(big.conv(dx), ddt, dB, dC)
+    big.commit(torch.full((wl.batch,), wl.k, dtype=torch.int32, device="cuda"))
+    ones = torch.ones(wl.batch, dtype=torch.int32, device="cuda")
+    for t in range(wl.k):
+        sl = slice(t, t + 1)
+        yt = one.verify(one.conv(dx[:, sl].contiguous()), ddt[:, sl].contiguous(), dB[:, sl].contiguous(), dC[:, sl].contiguous())
+        one.commit(ones)
+        assert rel_err(to_host(yt[:, 0]), to_host(y[:, t])) <= 1e-5
+    assert rel_err(to_host(one.materialize()), to_host(big.materialize())) <= 1e-5
+
+
+def test_materialize_and_verify_do_not_mutate_the_cache():
+    wl = Workload("mut", "scalar", batch=2, nheads=2, headdim=64, dstate=64, k=4, rounds=2, io="f32",
+                  accept="uniform", seed=14)
+    data = generate(wl)
+    data.rounds[0].accepted[:] = [2, 1]                       # leave tokens pending
+    lp = data.layers[0]
+    hip = HipLayer(wl, lp)
+    r0, r1 = data.rounds
+    xc = hip.conv(to_dev(r0.x_raw, wl.io))
+    hip.verify(xc, to_dev(r0.dt[0], wl.io), to_dev(r0.B[0], wl.io), to_dev(r0.C[0], wl.io))
+    hip.commit(torch.from_numpy(r0.accepted).to("cuda"))
+    ints0 = hip.cache.ints()
+    live0 = hip.cache.state_view()[torch.from_numpy(ints0["cur_slot"]).long(), torch.arange(wl.batch)].clone()
+    h_a = hip.materialize()
+    xc = hip.conv(to_dev(r1.x_raw, wl.io))
+    hip.verify(xc, to_dev(r1.dt[0], wl.io), to_dev(r1.B[0], wl.io), to_dev(r1.C[0], wl.io))
+    h_b = hip.materialize()
+    ints1 = hip.cache.ints()
+    live1 = hip.cache.state_view()[torch.from_numpy(ints1["cur_slot"]).long(), torch.arange(wl.batch)]
+    assert torch.equal(h_a, h_b) and torch.equal(live0, live1)
+    for name in ("cur_slot", "pend", "pos", "conv_head"):
+        assert np.array_equal(ints0[name], ints1[name])
+    assert ints1["last_k"].tolist() == [wl.k] * wl.batch and ints1["win_par"] == ints0["win_par"]
+
+
+def test_device_error_flag_paths():
+    wl = Workload("err", "scalar", batch=3, nheads=1, headdim=16, dstate=16, k=3, rounds=1, io="f32",
+                  accept="uniform", seed=15)
+    data = generate(wl)
+    lp, rd = data.layers[0], data.rounds[0]
+    hip = HipLayer(wl, lp)
+    # commit without verify: nothing changes, sticky flag
+    hip.commit(torch.zeros(wl.batch, dtype=torch.int32, device="cuda"))
+    with pytest.raises(ssmv.SsmvError) as ei:
+        ssmv.ssmv_check(hip.cache.c)
+    assert ei.value.code == ssmv.SSMV_ESEQUENCE
+    ints = hip.cache.ints()
+    assert ints["win_par"] == 0 and ints["cur_slot"].tolist() == [0, 0, 0] and ints["pos"].tolist() == [0, 0, 0]
+    # out-of-range accepted: clamped exactly like the integer model, sticky flag
+    hip.reset()
+    ssmv.ssmv_check(hip.cache.c)
+    xc = hip.conv(to_dev(rd.x_raw, wl.io))
+    hip.verify(xc, to_dev(rd.dt[0], wl.io), to_dev(rd.B[0], wl.io), to_dev(rd.C[0], wl.io))
+    bad = np.array([7, -2, 1], dtype=np.int32)
+    hip.commit(torch.from_numpy(bad).to("cuda"))
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
+    bk.verify(wl.k)
+    bk.commit(bad)
+    ints = hip.cache.ints()
+    assert ints["cur_slot"].tolist() == bk.cur and ints["pend"].tolist() == bk.pend and ints["pos"].tolist() == bk.pos
+    assert ints["conv_head"].tolist() == bk.conv_head and ints["err_flag"] == bk.err == 1
+
+
+def test_first_conflict_bit_exact():
+    rng = np.random.default_rng(16)
+    for batch, k in [(1, 1), (7, 4), (300, 8), (1025, 16)]:
+        draft = rng.integers(0, 3, size=(batch, k)).astype(np.int32)
+        target = rng.integers(0, 3, size=(batch, k)).astype(np.int32)
+        target[: batch // 3] = draft[: batch // 3]                      # some full matches
+        out = torch.empty(batch, dtype=torch.int32, device="cuda")
+        ssmv.ssmv_first_conflict(torch.from_numpy(draft).to("cuda"), torch.from_numpy(target).to("cuda"), batch, k, out)
+        assert np.array_equal(out.cpu().numpy(), oracle.first_conflict(draft, target))
+
+
+def test_copy_probe_copies():
+    src = torch.randn(1 << 20, device="cuda")
+    d0, d1 = torch.zeros_like(src), torch.zeros_like(src)
+    ssmv.ssmv_copy_probe(src, d0, d1, src.numel() * 4)
+    assert torch.equal(src, d0) and torch.equal(src, d1)
+    d0.zero_()
+    ssmv.ssmv_copy_probe(src, d0, None, src.numel() * 4)
+    assert torch.equal(src, d0)
