@@ -1,0 +1,341 @@
+#!/usr/bin/env python3
+"""Benchmark of the multi-step SSM verification path on one MI355X.
+
+A step is one verify round of one layer over one batch: conv1d_state_update ->
+ssm_verify_multistep -> ssm_commit_rollback, inputs already resident in HBM.  Steps rotate
+round-robin over enough independent caches that a cache's state has left the last-level cache
+before it is touched again (the "cold" protocol: a real decoder streams the model's weights
+between two visits to a layer's state).  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] ...
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (0: one pass over all caches and rounds)")
+    ap.add_argument("--warmup", type=int, default=-1, help="untimed steps (-1: one per cache, at least 3)")
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--footprint-gib", type=float, default=2.0, help="total size of the rotating caches (cold protocol)")
+    ap.add_argument("--instances", type=int, default=0, help="number of rotating caches (0: from --footprint-gib)")
+    ap.add_argument("--no-graph", action="store_true", help="launch every step from Python instead of one HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle baseline")
+    ap.add_argument("--rows", type=int, default=0, help="verify kernel: state rows per lane (0 = auto)")
+    ap.add_argument("--waves", type=int, default=0, help="verify kernel: waves per workgroup (0 = auto)")
+    ap.add_argument("--kernel-only", action="store_true", help="only the verify-kernel loop (for rocprofv3 runs)")
+    ap.add_argument("--split", action="store_true",
+                    help="three launches per step (conv1d_state_update, ssm_verify_multistep, ssm_commit_rollback) instead of "
+                         "the fused conv+verify launch and one commit launch per round over all caches")
+    return ap.parse_args()
+
+
+def pend_after(accepted_rounds, k_rounds):
+    """Host-side accounting of the pending-token count per sequence before each round (for byte counts only)."""
+    import numpy as np
+    pend = np.zeros_like(accepted_rounds[0])
+    out = []
+    for acc, k in zip(accepted_rounds, k_rounds):
+        out.append(pend.copy())
+        pend = np.where(acc == k, 0, acc)
+    return out
+
+
+def verify_bytes(wl, pend, k, fused):
+    """Algorithmic HBM bytes of one verify launch: state read once, h_k written, h_j written where
+    tokens were pending, token inputs read, y and the stash written, pending tokens re-read; with the
+    conv roll fused in: the raw inputs instead of xc, the ring append, 3 history rows, weights and bias."""
+    e = 2 if wl.io == "bf16" else 4
+    S = wl.state_elems * 4
+    Cx, H, GN = wl.conv_channels, wl.nheads, wl.ngroups * wl.dstate
+    total = 0
+    for pd in pend:
+        total += S * (2 + (1 if pd > 0 else 0))
+        total += k * (Cx + H + 2 * GN) * e          # xc (or x_raw), dt, B, C in
+        total += k * Cx * e                         # y out
+        total += k * (Cx + H + GN) * e              # stash out
+        total += int(pd) * (Cx + H + GN) * e        # pending tokens in
+        if fused:
+            total += (k * Cx + 3 * Cx + 5 * Cx) * e # ring append, ring history, conv weights + bias
+    return int(total)
+
+
+def round_bytes(wl, pend, k, fused):
+    """Whole round.  Split path: the verify launch plus the conv launch (x_raw in, ring append, xc out, 3
+    history rows and weights in).  Fused path: the one launch."""
+    e = 2 if wl.io == "bf16" else 4
+    if fused:
+        return verify_bytes(wl, pend, k, True)
+    conv = len(pend) * (k * wl.conv_channels * 3 + 3 * wl.conv_channels + 5 * wl.conv_channels) * e
+    return verify_bytes(wl, pend, k, False) + conv
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU (the path shards over sequences/heads with no exchange step); "
+              "--gpus %d is not supported, run with --gpus 1" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2408_15237_amd as ssmv
+    from workload import CONFIGS, generate
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    ssmv.load_library()
+    ssmv.ssmv_set_tuning(args.rows, args.waves)
+
+    wl = CONFIGS[args.workload]
+    if wl.layers != 1:
+        wl = wl.scaled(layers=1)           # the metric is per SSM layer; the stack is covered by the parity tests
+    data = generate(wl)
+    lp = data.layers[0]
+    io_t = torch.bfloat16 if wl.io == "bf16" else torch.float32
+    dev = "cuda"
+
+    def up(a):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).to(io_t).contiguous()
+
+    dims = ssmv.make_dims(wl.batch, wl.nheads, wl.headdim, wl.dstate, ngroups=wl.ngroups, kmax=wl.kmax_eff,
+                          ring_len=wl.ring_len, io=wl.io, a_mode=wl.a_mode, conv_act=wl.conv_act)
+    sizes = ssmv.ssmv_cache_sizes(dims)
+    cache_bytes = sum(sizes)
+    n_inst = args.instances or max(1, math.ceil(args.footprint_gib * 2 ** 30 / cache_bytes))
+    caches = [ssmv.LayerCache.allocate(dims) for _ in range(n_inst)]
+    A = torch.from_numpy(lp.A).to(dev)
+    D = torch.from_numpy(lp.D).to(dev)
+    conv_w, conv_b = up(lp.conv_w), (None if lp.conv_b is None else up(lp.conv_b))
+    h0 = torch.from_numpy(lp.h0).to(dev)
+    rounds = [dict(x=up(r.x_raw), dt=up(r.dt[0]), B=up(r.B[0]), C=up(r.C[0]),
+                   acc=torch.from_numpy(r.accepted).to(dev)) for r in data.rounds]
+    n_rounds = len(rounds)
+    k = wl.k
+    xc_buf = torch.empty_like(rounds[0]["x"])
+    y_buf = torch.empty_like(rounds[0]["x"])
+    for c in caches:
+        ssmv.ssmv_cache_reset(dims, c.c, h0, None)
+    torch.cuda.synchronize()
+
+    fused = not args.split
+    all_caches = (ssmv.ssmv_cache * n_inst)(*[c.c for c in caches])
+
+    # The rotating caches play the SSM layers of one model: a round verifies layer after layer, then the
+    # accepted lengths are known and every layer commits.  Step s = (layer s % n_inst, round s // n_inst).
+    def step(s):
+        i = s % n_inst
+        c = caches[i].c
+        r = rounds[(s // n_inst) % n_rounds]
+        if fused:
+            ssmv.ssm_conv_verify_multistep(dims, c, r["x"], conv_w, conv_b, r["dt"], r["B"], r["C"], A, D, k, y_buf)
+            if i == n_inst - 1:
+                ssmv.ssm_commit_rollback_multi(dims, all_caches, r["acc"])
+        else:
+            ssmv.conv1d_state_update(dims, c, r["x"], conv_w, conv_b, k, xc_buf)
+            ssmv.ssm_verify_multistep(dims, c, xc_buf, r["dt"], r["B"], r["C"], A, D, k, y_buf)
+            ssmv.ssm_commit_rollback(dims, c, r["acc"])
+
+    def finish(s_end):
+        """Commit the layers of a round that the timed region cut short (fused path only)."""
+        done = s_end % n_inst
+        if fused and done:
+            part = (ssmv.ssmv_cache * done)(*[c.c for c in caches[:done]])
+            ssmv.ssm_commit_rollback_multi(dims, part, rounds[(s_end // n_inst) % n_rounds]["acc"])
+
+    K = args.steps if args.steps > 0 else n_inst * n_rounds
+    W = args.warmup if args.warmup >= 0 else max(3, n_inst)
+    rounds_run = (W + K + n_inst - 1) // n_inst + 1
+    pend_sched = pend_after([data.rounds[i % n_rounds].accepted for i in range(rounds_run)], [k] * rounds_run)
+
+    result = {}
+    if args.kernel_only:
+        # three untimed rounds through every cache, so that the pending counts have their workload mix
+        for s in range(3 * n_inst):
+            step(s)
+        torch.cuda.synchronize()
+    if not args.kernel_only:
+        for s in range(W):
+            step(s)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if args.no_graph:
+            torch.cuda.synchronize()
+            ev0.record()
+            for s in range(W, W + K):
+                step(s)
+            finish(W + K)
+            ev1.record()
+            torch.cuda.synchronize()
+        else:
+            # the K timed steps as one HIP graph (kernel nodes only): no launch gaps from Python
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                graph.capture_begin()
+                for s in range(W, W + K):
+                    step(s)
+                finish(W + K)
+                graph.capture_end()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            ev0.record()
+            graph.replay()
+            ev1.record()
+            torch.cuda.synchronize()
+        total_ms = ev0.elapsed_time(ev1)
+        for c in caches:
+            ssmv.ssmv_check(c.c)
+        # algorithmic bytes of exactly the timed steps
+        tot_bytes = 0
+        for s in range(W, W + K):
+            tot_bytes += round_bytes(wl, pend_sched[s // n_inst], k, fused)
+        tokens = wl.batch * k * K
+        result.update(
+            value=tokens / (total_ms * 1e-3),
+            ms_per_step=total_ms / K,
+            step_hbm_gbps=tot_bytes / (total_ms * 1e-3) / 1e9,
+        )
+
+    # ---- the dominant kernel alone: n_meas back-to-back launches (one HIP graph, kernel nodes only) rotating
+    # over the caches, bracketed by HIP events on the launch stream.  The average therefore includes the gap
+    # between two kernels of one stream; rocprofv3's per-dispatch duration excludes it and reads lower.
+    torch.cuda.synchronize()
+    n_meas = max(64, min(512, 4 * n_inst))
+    pend_now = [c.ints()["pend"] for c in caches]
+    r0 = rounds[0]
+
+    def dominant(c):
+        if fused:
+            ssmv.ssm_conv_verify_multistep(dims, c, r0["x"], conv_w, conv_b, r0["dt"], r0["B"], r0["C"], A, D, k, y_buf)
+        else:
+            ssmv.ssm_verify_multistep(dims, c, r0["x"], r0["dt"], r0["B"], r0["C"], A, D, k, y_buf)
+
+    for i in range(n_inst):
+        dominant(caches[i].c)
+    torch.cuda.synchronize()
+    kbytes = sum(verify_bytes(wl, pend_now[i % n_inst], k, fused) for i in range(n_meas))
+    side2 = torch.cuda.Stream()
+    side2.wait_stream(torch.cuda.current_stream())
+    kgraph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side2):
+        kgraph.capture_begin()
+        for i in range(n_meas):
+            dominant(caches[i % n_inst].c)
+        kgraph.capture_end()
+    torch.cuda.current_stream().wait_stream(side2)
+    torch.cuda.synchronize()
+    durs = []
+    for rep in range(5):
+        ka, kb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ka.record()
+        kgraph.replay()
+        kb.record()
+        torch.cuda.synchronize()
+        durs.append(ka.elapsed_time(kb) / n_meas)
+    durs.sort()
+    avg_ms = sum(durs) / len(durs)
+    achieved = (kbytes / n_meas) / (avg_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "verify_kernel_%s_pmc.txt" % wl.name)
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                "frac": round(achieved / PEAK_HBM_GBPS, 4), "traffic": traffic,
+                "kernel": "verify_kernel (conv roll fused)" if fused else "verify_kernel", "avg_launch_us": round(avg_ms * 1e3, 3),
+                "median_launch_us": round(durs[len(durs) // 2] * 1e3, 3),
+                "algorithmic_bytes_per_launch": kbytes // n_meas, "launches_timed": n_meas * len(durs)}
+
+    # ---- achievable ceiling: plain copy, read S / write 2S, same footprint --------------------------
+    nbytes = (sizes[0] // 3) // 16 * 16
+    ce0, ce1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(2 * n_inst, 16)
+    for i in range(min(4, n_inst)):
+        st = caches[i % n_inst].buffers["state"]
+        base = st.data_ptr()
+        ssmv.ssmv_copy_probe(base, base + nbytes, base + 2 * nbytes, nbytes)
+    torch.cuda.synchronize()
+    ce0.record()
+    for i in range(reps):
+        base = caches[i % n_inst].buffers["state"].data_ptr()
+        ssmv.ssmv_copy_probe(base, base + nbytes, base + 2 * nbytes, nbytes)
+    ce1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 3 * nbytes * reps / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
+
+    if args.kernel_only:
+        print(json.dumps({"kernel_only": True, "roofline": roofline, "copy_r1w2_gbps": round(copy_gbps, 1)}))
+        return
+
+    # ---- the oracle on the host cores, bounded sample ------------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle                      # cpu_baseline leg only
+        ora = oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.conv_act, wl.ngroups)
+        t0 = time.perf_counter()
+        done = 0
+        while done < n_rounds:
+            r = data.rounds[done]
+            ora.verify(r.x_raw, r.dt[0], r.B[0], r.C[0])
+            ora.commit(r.accepted)
+            done += 1
+            el = time.perf_counter() - t0
+            if el >= args.cpu_seconds or (done >= 2 and el / done * (done + 1) > 2.5 * args.cpu_seconds):
+                break
+        el = time.perf_counter() - t0
+        cpu = {"value": round(wl.batch * k * done / el, 1), "unit": "tokens/s", "cores": oracle.oracle_threads(),
+               "kind": "oracle", "sample": "first %d of %d rounds of %s, all %d sequences (fp64, eager, %.1f s)"
+               % (done, n_rounds, wl.name, wl.batch, el)}
+
+    out = {
+        "metric": "verified draft tokens/sec per SSM layer",
+        "value": round(result["value"], 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(result["ms_per_step"], 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s-A layer, batch %d, %d heads x headdim %d x d_state %d, k=%d, %s I/O + fp32 state, "
+                               "%s acceptance, %d rounds, cold protocol over %d rotating caches (%.2f GiB)"
+                               % (wl.name, wl.a_mode, wl.batch, wl.nheads, wl.headdim, wl.dstate, k, wl.io, wl.accept,
+                                  n_rounds, n_inst, n_inst * cache_bytes / 2 ** 30),
+                   "batch": wl.batch, "k": k, "rounds": n_rounds, "instances": n_inst,
+                   "launch": "hip-graph" if not args.no_graph else "eager",
+                   "path": "fused conv+verify launch per layer, one commit launch per round over all caches" if fused
+                           else "conv, verify and commit launches per layer"},
+        "hbm_gbps_whole_step": round(result["step_hbm_gbps"], 1),
+        "copy_r1w2_gbps": round(copy_gbps, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

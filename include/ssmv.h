@@ -67,7 +67,7 @@ typedef struct {
     int32_t batch;          /* sequences                                                          */
     int32_t nheads;         /* H  (diag mode: the number of channels)                             */
     int32_t headdim;        /* P  (diag mode: must be 1)                                          */
-    int32_t dstate;         /* N  in {4, 8, 16, 32, 64, 128, 256}                                 */
+    int32_t dstate;         /* N  in {16, 32, 64, 128, 256} (diag mode: <= 64)                     */
     int32_t ngroups;        /* G  B/C groups; H % G == 0; head hd uses group hd*G/H               */
     int32_t conv_width;     /* W  must be SSMV_CONV_WIDTH                                         */
     int32_t conv_channels;  /* Cx must equal H*P                                                  */
@@ -97,7 +97,9 @@ typedef struct {
 
 /* Bytes the caller must allocate for each pointer of ssmv_cache, in declaration
  * order: state, conv_ring, win_xc[0], win_xc[1], win_dt[0], win_dt[1], win_B[0],
- * win_B[1], cur_slot, pend, pos, conv_head, last_k, win_par, err_flag. */
+ * win_B[1], cur_slot, pend, pos, conv_head, last_k, win_par, err_flag.  Each size is
+ * rounded up to a multiple of 256 bytes; the kernels may read (never write) up to
+ * the end of the last granule. */
 int ssmv_cache_sizes(const ssmv_dims *dims, size_t out_bytes[SSMV_CACHE_NPTR]);
 
 /* Start a cache: slot 0 <- h0 ([batch][H][P][N] fp32 device, NULL = zeros), the
@@ -135,6 +137,19 @@ int ssm_verify_multistep(const ssmv_dims *dims, const ssmv_cache *cache, const v
                          const void *dt, const void *Bm, const void *Cm, const float *A,
                          const float *D, int32_t k, void *y_out, void *hip_stream);
 
+/* conv1d_state_update and ssm_verify_multistep in ONE launch (Section 4.3: the
+ * paper fuses recomputation, multi-step decoding and caching; the conv roll over
+ * the circular buffer is folded into the same kernel's token staging here).
+ * Takes the raw conv inputs instead of xc: x_raw [batch][k][Cx], wgt [Cx][W],
+ * bias [Cx] or NULL (io_dtype, device).  Appends x_raw to the ring, computes
+ * xc exactly as conv1d_state_update does (same fp32 order, same rounding),
+ * stashes it in the window, and runs the verification on it.  xc itself is not
+ * returned.  Everything else as for ssm_verify_multistep. */
+int ssm_conv_verify_multistep(const ssmv_dims *dims, const ssmv_cache *cache, const void *x_raw,
+                              const void *wgt, const void *bias, const void *dt, const void *Bm,
+                              const void *Cm, const float *A, const float *D, int32_t k,
+                              void *y_out, void *hip_stream);
+
 /* Algorithm 2, "return h_k if k' = k else h_j", as integer bookkeeping.  Per
  * sequence with a = accepted[b] (device int32 [batch]; values outside
  * [0,last_k] are clamped and set err_flag):
@@ -146,6 +161,12 @@ int ssm_verify_multistep(const ssmv_dims *dims, const ssmv_cache *cache, const v
  * sets err_flag. */
 int ssm_commit_rollback(const ssmv_dims *dims, const ssmv_cache *cache, const int32_t *accepted,
                         void *hip_stream);
+
+/* The same commit for n_caches caches that share dims and the accepted lengths
+ * (the SSM layers of one model: acceptance is decided per sequence, once, after
+ * the last layer), in one launch per 32 caches.  `caches` is a HOST array. */
+int ssm_commit_rollback_multi(const ssmv_dims *dims, const ssmv_cache *caches, int32_t n_caches,
+                              const int32_t *accepted, void *hip_stream);
 
 /* State at pos+pend (live slot with the pending tokens folded in), written to
  * h_out [batch][H][P][N] fp32 device; the cache is not changed.  For tests and

@@ -29,7 +29,7 @@ ACT_CODES = {"none": SSMV_ACT_NONE, "silu": SSMV_ACT_SILU}
 
 EXPORTS = [
     "ssmv_cache_sizes", "ssmv_cache_reset", "conv1d_state_update", "ssm_verify_multistep",
-    "ssm_commit_rollback", "ssmv_materialize", "ssmv_first_conflict", "ssmv_check",
+    "ssm_conv_verify_multistep", "ssm_commit_rollback", "ssm_commit_rollback_multi", "ssmv_materialize", "ssmv_first_conflict", "ssmv_check",
     "ssmv_set_tuning", "ssmv_copy_probe", "ssmv_last_error", "ssmv_version",
 ]
 
@@ -83,7 +83,9 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.ssmv_cache_reset.argtypes = [dp, cp, vp, vp, vp]
     lib.conv1d_state_update.argtypes = [dp, cp, vp, vp, vp, i32, vp, vp]
     lib.ssm_verify_multistep.argtypes = [dp, cp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.ssm_conv_verify_multistep.argtypes = [dp, cp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.ssm_commit_rollback.argtypes = [dp, cp, vp, vp]
+    lib.ssm_commit_rollback_multi.argtypes = [dp, cp, i32, vp, vp]
     lib.ssmv_materialize.argtypes = [dp, cp, vp, vp, vp]
     lib.ssmv_first_conflict.argtypes = [vp, vp, i32, i32, vp, vp]
     lib.ssmv_check.argtypes = [cp, vp]
@@ -152,6 +154,18 @@ def conv1d_state_update(dims, cache, x_raw, wgt, bias, k: int, xc_out, stream=No
 def ssm_verify_multistep(dims, cache, xc, dt, Bm, Cm, A, D, k: int, y_out, stream=None) -> None:
     _ck(load_library().ssm_verify_multistep(ctypes.byref(dims), ctypes.byref(cache), _ptr(xc), _ptr(dt), _ptr(Bm), _ptr(Cm),
                                             _ptr(A), _ptr(D), k, _ptr(y_out), _stream(stream)))
+
+
+def ssm_conv_verify_multistep(dims, cache, x_raw, wgt, bias, dt, Bm, Cm, A, D, k: int, y_out, stream=None) -> None:
+    _ck(load_library().ssm_conv_verify_multistep(ctypes.byref(dims), ctypes.byref(cache), _ptr(x_raw), _ptr(wgt), _ptr(bias),
+                                                 _ptr(dt), _ptr(Bm), _ptr(Cm), _ptr(A), _ptr(D), k, _ptr(y_out), _stream(stream)))
+
+
+def ssm_commit_rollback_multi(dims, caches, accepted, stream=None) -> None:
+    """`caches`: a ctypes array (ssmv_cache * n) or a sequence of ssmv_cache structs."""
+    if not isinstance(caches, ctypes.Array):
+        caches = (ssmv_cache * len(caches))(*caches)
+    _ck(load_library().ssm_commit_rollback_multi(ctypes.byref(dims), caches, len(caches), _ptr(accepted), _stream(stream)))
 
 
 def ssm_commit_rollback(dims, cache, accepted, stream=None) -> None:

@@ -27,6 +27,11 @@ int hip_fail(int hip_code, const char *what)
     return fail(SSMV_EHIP, "%s: %s", what, hipGetErrorString((hipError_t)hip_code));
 }
 
+#ifdef SSMV_TRACE
+// Profiling builds (-DSSMV_TRACE) only: device buffer of 8 wall-clock stamps per verify workgroup.
+long long *g_trace = nullptr;
+extern "C" void ssmv_debug_set_trace(long long *t) { g_trace = t; }
+#endif
 std::atomic<int> g_tune_rows{0};
 std::atomic<int> g_tune_waves{0};
 
@@ -58,6 +63,10 @@ int check_dims(const ssmv_dims *d)
         if (d->ngroups != 1) return fail(SSMV_EUNSUPPORTED, "diag mode needs ngroups 1 (got %d)", d->ngroups);
         if (d->dstate > 64) return fail(SSMV_EUNSUPPORTED, "diag mode supports dstate <= 64 (got %d)", d->dstate);
     }
+    if (d->batch > 65535) return fail(SSMV_EUNSUPPORTED, "batch %d > 65535", d->batch);
+    if (d->a_mode == SSMV_A_SCALAR && d->nheads > 65535) return fail(SSMV_EUNSUPPORTED, "nheads %d > 65535 in scalar mode", d->nheads);
+    if ((double)d->batch * d->kmax * d->nheads * d->headdim >= 2.0e9 || (double)d->batch * d->ring_len * d->nheads * d->headdim >= 2.0e9)
+        return fail(SSMV_EUNSUPPORTED, "token tensors beyond 2^31 elements");
     const double slot = (double)d->batch * d->nheads * d->headdim * d->dstate;
     if (slot * 3 > 2.0e10) return fail(SSMV_EUNSUPPORTED, "state of %.3g elements is beyond what one cache may hold", slot * 3);
     if ((double)d->batch * d->nheads * d->headdim > 2.0e9) return fail(SSMV_EUNSUPPORTED, "too many state rows");
@@ -136,8 +145,11 @@ int choose_shape(const ssmv_dims *d, int lds_tokens, int k, VerifyShape *out, in
     out->waves = waves;
     *rows_wg = waves * rpi * R;
     *tiles = (dom + *rows_wg - 1) / *rows_wg;
+    if (*tiles > 65535 * 32) return fail(SSMV_EUNSUPPORTED, "too many row tiles (%d)", *tiles);
     return SSMV_OK;
 }
+
+int ilog2_host(int v) { int l = 0; while ((1 << (l + 1)) <= v) ++l; return l; }
 
 void fill_verify(VerifyParams &p, const ssmv_dims *d, const ssmv_cache *c)
 {
@@ -147,6 +159,10 @@ void fill_verify(VerifyParams &p, const ssmv_dims *d, const ssmv_cache *c)
     p.slot_stride = (size_t)d->batch * d->nheads * d->headdim * d->dstate;
     for (int i = 0; i < 2; ++i) { p.win_xc[i] = c->win_xc[i]; p.win_dt[i] = c->win_dt[i]; p.win_B[i] = c->win_B[i]; }
     p.cur_slot = c->cur_slot; p.pend = c->pend; p.last_k = c->last_k; p.win_par = c->win_par;
+    p.ring = c->conv_ring; p.conv_head = c->conv_head; p.ring_len = d->ring_len; p.conv_act = d->conv_act;
+#ifdef SSMV_TRACE
+    p.trace = g_trace;
+#endif
 }
 
 }  // namespace
@@ -187,6 +203,7 @@ int ssmv_cache_sizes(const ssmv_dims *d, size_t out_bytes[SSMV_CACHE_NPTR])
     o[12] = B * sizeof(int32_t);  // last_k
     o[13] = sizeof(int32_t);      // win_par
     o[14] = sizeof(int32_t);      // err_flag
+    for (int i = 0; i < SSMV_CACHE_NPTR; ++i) o[i] = (o[i] + 255) / 256 * 256;   // whole 256-byte granules
     return SSMV_OK;
 }
 
@@ -225,14 +242,21 @@ int conv1d_state_update(const ssmv_dims *d, const ssmv_cache *c, const void *x_r
     return hc == 0 ? SSMV_OK : hip_fail(hc, "conv1d_state_update");
 }
 
-int ssm_verify_multistep(const ssmv_dims *d, const ssmv_cache *c, const void *xc, const void *dt, const void *Bm,
-                         const void *Cm, const float *A, const float *D, int32_t k, void *y_out, void *hip_stream)
+static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const void *xc, const void *x_raw, const void *wgt,
+                         const void *bias, const void *dt, const void *Bm, const void *Cm, const float *A, const float *D,
+                         int32_t k, void *y_out, void *hip_stream, const char *what)
 {
     int rc;
     if ((rc = check_dims(d)) != SSMV_OK) return rc;
     if ((rc = check_cache(c)) != SSMV_OK) return rc;
     if ((rc = check_k(d, k)) != SSMV_OK) return rc;
-    if ((rc = check_ptr(xc, "xc")) != SSMV_OK) return rc;
+    if (x_raw) {
+        if ((rc = check_ptr(x_raw, "x_raw")) != SSMV_OK) return rc;
+        if ((rc = check_ptr(wgt, "wgt")) != SSMV_OK) return rc;
+        if (bias && !aligned16(bias)) return fail(SSMV_EALIGN, "bias is not 16-byte aligned");
+    } else {
+        if ((rc = check_ptr(xc, "xc")) != SSMV_OK) return rc;
+    }
     if ((rc = check_ptr(dt, "dt")) != SSMV_OK) return rc;
     if ((rc = check_ptr(Bm, "Bm")) != SSMV_OK) return rc;
     if ((rc = check_ptr(Cm, "Cm")) != SSMV_OK) return rc;
@@ -244,11 +268,27 @@ int ssm_verify_multistep(const ssmv_dims *d, const ssmv_cache *c, const void *xc
     p.k = k;
     p.lds_tokens = d->kmax - 1 + k;
     p.xc = xc; p.dt = dt; p.Bm = Bm; p.Cm = Cm; p.A = A; p.D = D; p.y = y_out; p.h_out = nullptr;
+    p.x_raw = x_raw; p.wgt = wgt; p.bias = bias;
     VerifyShape shape;
     if ((rc = choose_shape(d, p.lds_tokens, k, &shape, &p.rows_wg, &p.tiles)) != SSMV_OK) return rc;
+    p.log2_rows_wg = ilog2_host(p.rows_wg);
     const int hc = d->a_mode == SSMV_A_DIAG ? launch_verify_diag(p, shape, (hipStream_t)hip_stream)
                                              : launch_verify_scalar(p, shape, (hipStream_t)hip_stream);
-    return hc == 0 ? SSMV_OK : hip_fail(hc, "ssm_verify_multistep");
+    return hc == 0 ? SSMV_OK : hip_fail(hc, what);
+}
+
+int ssm_verify_multistep(const ssmv_dims *d, const ssmv_cache *c, const void *xc, const void *dt, const void *Bm,
+                         const void *Cm, const float *A, const float *D, int32_t k, void *y_out, void *hip_stream)
+{
+    return verify_common(d, c, xc, nullptr, nullptr, nullptr, dt, Bm, Cm, A, D, k, y_out, hip_stream, "ssm_verify_multistep");
+}
+
+int ssm_conv_verify_multistep(const ssmv_dims *d, const ssmv_cache *c, const void *x_raw, const void *wgt, const void *bias,
+                              const void *dt, const void *Bm, const void *Cm, const float *A, const float *D, int32_t k,
+                              void *y_out, void *hip_stream)
+{
+    if (!x_raw) return fail(SSMV_EINVAL, "x_raw is NULL");
+    return verify_common(d, c, nullptr, x_raw, wgt, bias, dt, Bm, Cm, A, D, k, y_out, hip_stream, "ssm_conv_verify_multistep");
 }
 
 int ssmv_materialize(const ssmv_dims *d, const ssmv_cache *c, const float *A, float *h_out, void *hip_stream)
@@ -266,24 +306,41 @@ int ssmv_materialize(const ssmv_dims *d, const ssmv_cache *c, const float *A, fl
     p.h_out = h_out;
     VerifyShape shape;
     if ((rc = choose_shape(d, p.lds_tokens, 0, &shape, &p.rows_wg, &p.tiles)) != SSMV_OK) return rc;
+    p.log2_rows_wg = ilog2_host(p.rows_wg);
     const int hc = d->a_mode == SSMV_A_DIAG ? launch_verify_diag(p, shape, (hipStream_t)hip_stream)
                                              : launch_verify_scalar(p, shape, (hipStream_t)hip_stream);
     return hc == 0 ? SSMV_OK : hip_fail(hc, "ssmv_materialize");
 }
 
-int ssm_commit_rollback(const ssmv_dims *d, const ssmv_cache *c, const int32_t *accepted, void *hip_stream)
+int ssm_commit_rollback_multi(const ssmv_dims *d, const ssmv_cache *caches, int32_t n_caches, const int32_t *accepted,
+                              void *hip_stream)
 {
     int rc;
     if ((rc = check_dims(d)) != SSMV_OK) return rc;
-    if ((rc = check_cache(c)) != SSMV_OK) return rc;
+    if (!caches) return fail(SSMV_EINVAL, "caches is NULL");
+    if (n_caches < 1) return fail(SSMV_EINVAL, "n_caches %d < 1", n_caches);
+    for (int i = 0; i < n_caches; ++i)
+        if ((rc = check_cache(&caches[i])) != SSMV_OK) return rc;
     if (!accepted) return fail(SSMV_EINVAL, "accepted is NULL");
     if ((reinterpret_cast<uintptr_t>(accepted) & 3u) != 0) return fail(SSMV_EALIGN, "accepted is not 4-byte aligned");
-    CommitParams p{};
-    p.batch = d->batch; p.R = d->ring_len;
-    p.cur_slot = c->cur_slot; p.pend = c->pend; p.conv_head = c->conv_head; p.last_k = c->last_k;
-    p.win_par = c->win_par; p.err_flag = c->err_flag; p.pos = c->pos; p.accepted = accepted;
-    const int hc = launch_commit(p, (hipStream_t)hip_stream);
-    return hc == 0 ? SSMV_OK : hip_fail(hc, "ssm_commit_rollback");
+    for (int first = 0; first < n_caches; first += kCommitMaxCaches) {
+        CommitParams p{};
+        p.batch = d->batch; p.R = d->ring_len; p.accepted = accepted;
+        p.n_caches = n_caches - first < kCommitMaxCaches ? n_caches - first : kCommitMaxCaches;
+        for (int i = 0; i < p.n_caches; ++i) {
+            const ssmv_cache &c = caches[first + i];
+            p.c[i] = CacheInts{c.cur_slot, c.pend, c.conv_head, c.last_k, c.win_par, c.err_flag, c.pos};
+        }
+        const int hc = launch_commit(p, (hipStream_t)hip_stream);
+        if (hc != 0) return hip_fail(hc, "ssm_commit_rollback");
+    }
+    return SSMV_OK;
+}
+
+int ssm_commit_rollback(const ssmv_dims *d, const ssmv_cache *c, const int32_t *accepted, void *hip_stream)
+{
+    if (!c) return fail(SSMV_EINVAL, "cache is NULL");
+    return ssm_commit_rollback_multi(d, c, 1, accepted, hip_stream);
 }
 
 int ssmv_first_conflict(const int32_t *draft, const int32_t *target, int32_t batch, int32_t k, int32_t *accepted,

@@ -5,68 +5,24 @@
 
 namespace ssmv {
 
-// ---- 16-byte vector access in the I/O storage type ------------------------------------------------
-
-template <int IO, int VEC>
-struct IoVec;
-
-template <>
-struct IoVec<SSMV_F32, 4> {
-    static __device__ __forceinline__ void load(const void *base, size_t idx, float (&v)[4])
-    {
-        const float4 t = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(base) + idx);
-        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-    }
-    static __device__ __forceinline__ void store(void *base, size_t idx, const float (&v)[4])
-    {
-        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(base) + idx) = make_float4(v[0], v[1], v[2], v[3]);
-    }
-};
-
-template <>
-struct IoVec<SSMV_BF16, 8> {
-    static __device__ __forceinline__ void load(const void *base, size_t idx, float (&v)[8])
-    {
-        const uint4 t = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(base) + idx);
-        const uint32_t w[4] = {t.x, t.y, t.z, t.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[2 * i] = __uint_as_float(w[i] << 16);
-            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-        }
-    }
-    static __device__ __forceinline__ void store(void *base, size_t idx, const float (&v)[8])
-    {
-        uint32_t w[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16_bits(v[2 * i]) | ((uint32_t)f32_to_bf16_bits(v[2 * i + 1]) << 16);
-        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(base) + idx) = make_uint4(w[0], w[1], w[2], w[3]);
-    }
-};
-
+// one element at a time, for channel counts that are no multiple of the 16-byte vector
 template <int IO>
-struct IoVec<IO, 1> {
+struct IoOne {
+    static constexpr int EV = 1;
     static __device__ __forceinline__ void load(const void *base, size_t idx, float (&v)[1]) { v[0] = load_io(base, idx, IO); }
     static __device__ __forceinline__ void store(void *base, size_t idx, const float (&v)[1]) { store_io(base, idx, v[0], IO); }
 };
-
-// round a value to the storage type and back, so that what is fed on matches what is stored
-template <int IO>
-__device__ __forceinline__ float round_io(float v)
-{
-    if (IO == SSMV_BF16) return bf16_bits_to_f32(f32_to_bf16_bits(v));
-    return v;
-}
 
 // ---- conv roll -----------------------------------------------------------------------------------
 // One thread owns VEC adjacent channels of one sequence for all k tokens: it reads the W-1 newest
 // committed ring entries, then per new token appends the raw input to the ring and emits the
 // width-4 causal dot product.  Ring slots written are head+1..head+k, slots read are
 // head-2..head, disjoint because R >= W-1+kmax.
-template <int IO, int VEC>
+template <int IO, typename VT>
 __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
 {
     constexpr int W = SSMV_CONV_WIDTH;
+    constexpr int VEC = VT::EV;
     const int chunks = p.Cx / VEC;
     const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= (long)p.batch * chunks) return;
@@ -78,7 +34,7 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
     float hist[W - 1][VEC];
 #pragma unroll
     for (int i = 0; i < W - 1; ++i)
-        IoVec<IO, VEC>::load(p.ring, ((size_t)b * p.R + ((head - (W - 2) + i) & mask)) * p.Cx + c0, hist[i]);
+        VT::load(p.ring, ((size_t)b * p.R + ((head - (W - 2) + i) & mask)) * p.Cx + c0, hist[i]);
 
     float w[VEC][W];
 #pragma unroll
@@ -91,8 +47,8 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
 
     for (int t = 0; t < p.k; ++t) {
         float x[VEC], out[VEC];
-        IoVec<IO, VEC>::load(p.x_raw, ((size_t)b * p.k + t) * p.Cx + c0, x);
-        IoVec<IO, VEC>::store(p.ring, ((size_t)b * p.R + ((head + 1 + t) & mask)) * p.Cx + c0, x);
+        VT::load(p.x_raw, ((size_t)b * p.k + t) * p.Cx + c0, x);
+        VT::store(p.ring, ((size_t)b * p.R + ((head + 1 + t) & mask)) * p.Cx + c0, x);
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
             float s = bias[c];
@@ -106,7 +62,7 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
             hist[1][c] = hist[2][c];
             hist[2][c] = x[c];
         }
-        IoVec<IO, VEC>::store(p.xc, ((size_t)b * p.k + t) * p.Cx + c0, out);
+        VT::store(p.xc, ((size_t)b * p.k + t) * p.Cx + c0, out);
     }
 }
 
@@ -118,52 +74,58 @@ int launch_conv(const ConvParams &p, hipStream_t stream)
     const int block = 256;
     const unsigned grid = (unsigned)((threads + block - 1) / block);
     if (p.io == SSMV_BF16) {
-        if (vec_ok) hipLaunchKernelGGL((conv_kernel<SSMV_BF16, 8>), dim3(grid), dim3(block), 0, stream, p);
-        else hipLaunchKernelGGL((conv_kernel<SSMV_BF16, 1>), dim3(grid), dim3(block), 0, stream, p);
+        if (vec_ok) hipLaunchKernelGGL((conv_kernel<SSMV_BF16, IoVec<SSMV_BF16>>), dim3(grid), dim3(block), 0, stream, p);
+        else hipLaunchKernelGGL((conv_kernel<SSMV_BF16, IoOne<SSMV_BF16>>), dim3(grid), dim3(block), 0, stream, p);
     } else {
-        if (vec_ok) hipLaunchKernelGGL((conv_kernel<SSMV_F32, 4>), dim3(grid), dim3(block), 0, stream, p);
-        else hipLaunchKernelGGL((conv_kernel<SSMV_F32, 1>), dim3(grid), dim3(block), 0, stream, p);
+        if (vec_ok) hipLaunchKernelGGL((conv_kernel<SSMV_F32, IoVec<SSMV_F32>>), dim3(grid), dim3(block), 0, stream, p);
+        else hipLaunchKernelGGL((conv_kernel<SSMV_F32, IoOne<SSMV_F32>>), dim3(grid), dim3(block), 0, stream, p);
     }
     return (int)hipGetLastError();
 }
 
 // ---- commit / rollback (Algorithm 2: "return h_k if k'=k else h_j", lazily advanced cache) -----------
+// grid.y = cache (layer), one thread per sequence.  Every load is issued before the first use:
+// the kernel is a chain of memory latencies and nothing else.
 __global__ __launch_bounds__(256) void commit_kernel(const CommitParams p)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= p.batch) return;
-    const int lk = p.last_k[b];
+    const CacheInts &c = p.c[blockIdx.y];
+    const int lk = c.last_k[b];
+    int a = p.accepted[b];
+    const int cur = c.cur_slot[b];
+    const int pd = c.pend[b];
+    const int head = c.conv_head[b];
+    const int64_t pos = c.pos[b];
+    const int par = b == 0 ? *c.win_par : 0;
     if (lk == 0) {                       // nothing was verified: leave everything, flag it
-        *p.err_flag = 1;
+        *c.err_flag = 1;
         return;
     }
-    int a = p.accepted[b];
     if (a < 0 || a > lk) {
-        *p.err_flag = 1;
+        *c.err_flag = 1;
         a = a < 0 ? 0 : lk;
     }
-    const int cur = p.cur_slot[b];
-    const int pd = p.pend[b];
     if (a == lk) {                       // every draft accepted: h_k becomes the live state
-        p.cur_slot[b] = (cur + 2) % 3;
-        p.pos[b] += pd + a;
-        p.pend[b] = 0;
+        c.cur_slot[b] = (cur + 2) % 3;
+        c.pos[b] = pos + pd + a;
+        c.pend[b] = 0;
     } else if (pd > 0) {                 // rejection: fall back to h_j, the accepted prefix stays pending
-        p.cur_slot[b] = (cur + 1) % 3;
-        p.pos[b] += pd;
-        p.pend[b] = a;
+        c.cur_slot[b] = (cur + 1) % 3;
+        c.pos[b] = pos + pd;
+        c.pend[b] = a;
     } else {                             // rejection with nothing pending: the live slot already is h_j
-        p.pend[b] = a;
+        c.pend[b] = a;
     }
-    p.conv_head[b] = (p.conv_head[b] + a) & (p.R - 1);
-    p.last_k[b] = 0;
-    if (b == 0) *p.win_par ^= 1;
+    c.conv_head[b] = (head + a) & (p.R - 1);
+    c.last_k[b] = 0;
+    if (b == 0) *c.win_par = par ^ 1;
 }
 
 int launch_commit(const CommitParams &p, hipStream_t stream)
 {
     const int block = 256;
-    hipLaunchKernelGGL(commit_kernel, dim3((p.batch + block - 1) / block), dim3(block), 0, stream, p);
+    hipLaunchKernelGGL(commit_kernel, dim3((p.batch + block - 1) / block, p.n_caches), dim3(block), 0, stream, p);
     return (int)hipGetLastError();
 }
 

@@ -18,6 +18,12 @@ struct VerifyParams {
     int rows_wg;         // state rows one workgroup owns
     int tiles;           // scalar mode: tiles per head; diag mode: tiles per sequence
     int lds_tokens;      // tokens the dynamic LDS was sized for (kmax-1+k)
+    int log2_rows_wg;    // rows_wg is a power of two
+    // fused conv roll (x_raw != nullptr): ring append + width-4 conv computed while staging
+    int ring_len, conv_act;
+    void *ring;
+    const int32_t *conv_head;
+    const void *x_raw, *wgt, *bias;
     // cache
     float *state;        // [3][batch][H][P][N]
     size_t slot_stride;  // elements per slot
@@ -33,6 +39,10 @@ struct VerifyParams {
     const float *A, *D;
     void *y;
     float *h_out;        // non-null: materialize mode (replay only, write here, touch nothing else)
+#ifdef SSMV_TRACE
+    long long *trace;    // profiling builds only: 8 wall-clock stamps per workgroup (start, bookkeeping read,
+                         // loads issued, staged, barrier passed, drafts begin, drafts done, stores acknowledged)
+#endif
 };
 
 struct ConvParams {
@@ -43,11 +53,17 @@ struct ConvParams {
     void *xc;
 };
 
-struct CommitParams {
-    int batch, R;
+struct CacheInts {
     int32_t *cur_slot, *pend, *conv_head, *last_k, *win_par, *err_flag;
     int64_t *pos;
+};
+
+constexpr int kCommitMaxCaches = 32;     // caches one commit launch covers (kernel argument space)
+
+struct CommitParams {
+    int batch, R, n_caches;
     const int32_t *accepted;
+    CacheInts c[kCommitMaxCaches];
 };
 
 struct ResetParams {
@@ -111,5 +127,93 @@ __device__ __forceinline__ void store_io(void *base, size_t idx, float v, int io
     else
         reinterpret_cast<float *>(base)[idx] = v;
 }
+
+// ---- 16-byte vector access in the I/O storage type -------------------------------------------------
+
+template <int IO>
+struct IoVec;
+
+template <>
+struct IoVec<SSMV_F32> {
+    static constexpr int EV = 4;
+    // raw 16-byte vector / raw scalar: load now, decode at the point of use
+    static __device__ __forceinline__ uint4 load_raw(const void *base, size_t idx)
+    {
+        return *reinterpret_cast<const uint4 *>(reinterpret_cast<const float *>(base) + idx);
+    }
+    static __device__ __forceinline__ void store_raw(void *base, size_t idx, uint4 r)
+    {
+        *reinterpret_cast<uint4 *>(reinterpret_cast<float *>(base) + idx) = r;
+    }
+    static __device__ __forceinline__ void decode(uint4 r, float (&v)[4])
+    {
+        v[0] = __uint_as_float(r.x); v[1] = __uint_as_float(r.y); v[2] = __uint_as_float(r.z); v[3] = __uint_as_float(r.w);
+    }
+    static __device__ __forceinline__ uint4 encode(const float (&v)[4])
+    {
+        return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+    }
+    static __device__ __forceinline__ uint32_t load_raw1(const void *base, size_t idx) { return reinterpret_cast<const uint32_t *>(base)[idx]; }
+    static __device__ __forceinline__ void store_raw1(void *base, size_t idx, uint32_t r) { reinterpret_cast<uint32_t *>(base)[idx] = r; }
+    static __device__ __forceinline__ float decode1(uint32_t r) { return __uint_as_float(r); }
+    static __device__ __forceinline__ void load(const void *base, size_t idx, float (&v)[4])
+    {
+        const float4 t = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(base) + idx);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    }
+    static __device__ __forceinline__ void store(void *base, size_t idx, const float (&v)[4])
+    {
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(base) + idx) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+
+template <>
+struct IoVec<SSMV_BF16> {
+    static constexpr int EV = 8;
+    static __device__ __forceinline__ uint4 load_raw(const void *base, size_t idx)
+    {
+        return *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(base) + idx);
+    }
+    static __device__ __forceinline__ void store_raw(void *base, size_t idx, uint4 r)
+    {
+        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(base) + idx) = r;
+    }
+    static __device__ __forceinline__ void decode(uint4 r, float (&v)[8])
+    {
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ uint4 encode(const float (&v)[8])
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16_bits(v[2 * i]) | ((uint32_t)f32_to_bf16_bits(v[2 * i + 1]) << 16);
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    static __device__ __forceinline__ uint32_t load_raw1(const void *base, size_t idx) { return reinterpret_cast<const uint16_t *>(base)[idx]; }
+    static __device__ __forceinline__ void store_raw1(void *base, size_t idx, uint32_t r) { reinterpret_cast<uint16_t *>(base)[idx] = (uint16_t)r; }
+    static __device__ __forceinline__ float decode1(uint32_t r) { return __uint_as_float(r << 16); }
+    static __device__ __forceinline__ void load(const void *base, size_t idx, float (&v)[8])
+    {
+        const uint4 t = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(base) + idx);
+        const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ void store(void *base, size_t idx, const float (&v)[8])
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16_bits(v[2 * i]) | ((uint32_t)f32_to_bf16_bits(v[2 * i + 1]) << 16);
+        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(base) + idx) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
 
 }  // namespace ssmv

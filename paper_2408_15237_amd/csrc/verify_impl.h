@@ -1,6 +1,7 @@
 // The fused multi-step verification kernel (Section 4.2 MultiStep, fused as in Section 4.3 of
 // arXiv 2408.15237): replay of the pending tokens, snapshot h_j, k draft steps with outputs,
-// snapshot h_k and the stash of this round's tokens, in one launch.
+// snapshot h_k and the stash of this round's tokens, in one launch; optionally with the conv
+// roll over the circular buffer (Section 4.3 footnote) folded into the token staging.
 //
 // Work decomposition (gfx950, wave64):
 //   * A state row is the N fp32 values h[row][0..N).  LPR = min(16, N/4) lanes share a row, each
@@ -12,14 +13,21 @@
 //   * A workgroup of `waves` waves owns rows_wg = waves*RPI*R rows of ONE (sequence, head)
 //     (scalar-A mode) or of one sequence's channels (diagonal-A mode), so the replay trip count
 //     pend[b] is uniform over the workgroup.
+//   * The kernel is latency-bound before it is bandwidth-bound (one verify moves a few tens of
+//     MB), so the prologue is kept short: the state loads are issued first, from a uniform base
+//     pointer plus 32-bit lane offsets; then every thread issues ALL its token loads (raw bits)
+//     before the first wait, and decodes them into LDS afterwards.
 //   * The pend+k tokens' B, C, decay, dt*x and D*x are staged once in LDS as fp32.
 //   * y_t[row] = sum_n C_t[n] h[row][n] is EPL FMAs in-lane, then a reduction over the LPR lanes
-//     of the row with DPP row operations (no LDS, no atomics).
+//     of the row with DPP row operations; the row's first lane adds it to D*x in LDS with a
+//     no-return LDS add, and the workgroup writes y with 16-byte stores at the end.
 #pragma once
 
 #include "ssmv_internal.h"
 
 namespace ssmv {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v)
@@ -38,6 +46,8 @@ __device__ __forceinline__ float row_sum(float v)
     return v;
 }
 
+__host__ __device__ constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
+
 // LDS plan (floats).  T = lds_tokens.
 //   sB   [T][N]        B of every token (pending first, then drafts)
 //   sC   [k][N]        C of the drafts
@@ -53,180 +63,360 @@ __host__ __device__ inline size_t verify_lds_floats(int T, int k, int N, int row
     return n;
 }
 
-template <int N, int R, bool DIAG>
+template <int N, int R, bool DIAG, int IO, bool CONV>
 __global__ __launch_bounds__(256) void verify_kernel(const VerifyParams p)
 {
     constexpr int LPR = lanes_per_row(N);
     constexpr int EPL = N / LPR;
     constexpr int V = EPL / 4;
     constexpr int RPI = 64 / LPR;
+    constexpr int LOG2N = ilog2(N);
     constexpr float LOG2E = 1.4426950408889634f;
+    using Vec = IoVec<IO>;
+    constexpr int EV = Vec::EV;
+    constexpr int VN = N / EV;                           // 16-byte vectors per token of B or C
+    constexpr int LOG2VN = ilog2(VN);
+    constexpr int W = SSMV_CONV_WIDTH;
 
     extern __shared__ float4 lds_raw[];
     float *lds = reinterpret_cast<float *>(lds_raw);
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int sub = lane % LPR;          // which strip of the row
-    const int rsel = lane / LPR;         // which of the RPI rows of a load instruction
+    const unsigned tid = threadIdx.x;
+    const unsigned lane = tid & 63u;
+    const unsigned wave = tid >> 6;
+    const unsigned sub = lane % LPR;         // which strip of the row
+    const unsigned rsel = lane / LPR;        // which of the RPI rows of a load instruction
     const int rows_wg = p.rows_wg;
     const int k = p.k;
     const bool materialize = p.h_out != nullptr;
+#ifdef SSMV_TRACE
+    long long *trace_ = p.trace ? p.trace + 8 * ((size_t)blockIdx.x + gridDim.x * (blockIdx.y + (size_t)gridDim.y * blockIdx.z)) : nullptr;
+#define SSMV_TP(i) do { if (trace_ && threadIdx.x == 0) trace_[i] = wall_clock64(); } while (0)
+#else
+#define SSMV_TP(i) do { } while (0)
+#endif
+    SSMV_TP(0);
 
-    // ---- which (sequence, head, tile) -------------------------------------------------------
-    int b, hd, tile;
-    {
-        int w = blockIdx.x;
-        tile = w % p.tiles;
-        w /= p.tiles;
-        if (DIAG) {
-            b = w;
-            hd = 0;
-        } else {
-            hd = w % p.H;
-            b = w / p.H;
-        }
-    }
+    // ---- which (sequence, head, tile): all uniform ------------------------------------------------
+    // grid = (tiles, heads, batch) in scalar mode, (tiles, batch) in diag mode: no integer division needed
+    const int tile = blockIdx.x;
+    const int hd = DIAG ? 0 : blockIdx.y;
+    const int b = DIAG ? blockIdx.y : blockIdx.z;
     const int rows_dom = DIAG ? p.H : p.P;              // rows of the tiled domain
     const int row0 = tile * rows_wg;                    // first row of this workgroup in the domain
-    const size_t grow0 = DIAG ? (size_t)b * p.H : ((size_t)b * p.H + hd) * p.P;   // global row of domain row 0
+    const size_t grow = (DIAG ? (size_t)b * p.H : ((size_t)b * p.H + hd) * p.P) + row0;   // its global row
 
     // bookkeeping written by the commit kernel; clamped so that a corrupted cache cannot index out of bounds
     const int cur = (int)((unsigned)p.cur_slot[b] % 3u);
     const int pd = min(max(p.pend[b], 0), p.kmax - 1);
     const int par = p.win_par[0] & 1;
     const int T = pd + k;
+    SSMV_TP(1);
 
-    // ---- issue the state loads first: they are the long-latency part ------------------------------
-    float4 h[R][V];
-    int lrow[R];                                        // row inside the workgroup
+    // ---- state loads first: uniform base pointer + 32-bit lane offsets -------------------------------
+    v4f h[R][V];
+    v4f a2[DIAG ? R : 1][DIAG ? V : 1];                 // diag mode: A strips times log2(e): the decay is one exp2
+    unsigned lrow[R];                                   // row inside the workgroup
+    unsigned loff[R];                                   // element offset of the lane's first strip of that row
     bool rvalid[R];
+    {
+        const float *src = p.state + (size_t)cur * p.slot_stride + (grow << LOG2N);
+        const float *srcA = p.A + ((size_t)row0 << LOG2N);
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        lrow[r] = wave * (RPI * R) + r * RPI + rsel;
-        rvalid[r] = (row0 + lrow[r]) < rows_dom;
-        const float *src = p.state + (size_t)cur * p.slot_stride + (grow0 + row0 + lrow[r]) * N + sub * 4;
+        for (int r = 0; r < R; ++r) {
+            lrow[r] = wave * (RPI * R) + r * RPI + rsel;
+            rvalid[r] = (int)(row0 + lrow[r]) < rows_dom;
+            loff[r] = (lrow[r] << LOG2N) + sub * 4;
+            const unsigned o = rvalid[r] ? loff[r] : sub * 4;         // clamp to row 0: unconditional in-bounds load
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-            h[r][v] = rvalid[r] ? *reinterpret_cast<const float4 *>(src + v * (LPR * 4)) : make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int v = 0; v < V; ++v) h[r][v] = *reinterpret_cast<const v4f *>(src + o + v * (LPR * 4));
+            if constexpr (DIAG) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) a2[r][v] = *reinterpret_cast<const v4f *>(srcA + o + v * (LPR * 4)) * LOG2E;
+            }
         }
     }
 
-    // diag mode: the lane's A strips, pre-multiplied by log2(e) so the decay is one exp2
-    float4 a2[DIAG ? R : 1][DIAG ? V : 1];
-    if constexpr (DIAG) {
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (rvalid[r]) t = *reinterpret_cast<const float4 *>(p.A + (size_t)(row0 + lrow[r]) * N + v * (LPR * 4) + sub * 4);
-                a2[r][v] = make_float4(t.x * LOG2E, t.y * LOG2E, t.z * LOG2E, t.w * LOG2E);
-            }
-    }
-
-    // ---- stage the tokens in LDS --------------------------------------------------------------------
+    // ---- LDS carve-up -------------------------------------------------------------------------------
     const int TL = p.lds_tokens;
     float *sB = lds;
-    float *sC = sB + (size_t)TL * N;
-    float *sDec = sC + (size_t)k * N;                                  // scalar: [T]; diag: sDt [T][rows_wg]
-    float *sDtx = sDec + (DIAG ? (size_t)TL * rows_wg : (size_t)((TL + 3) & ~3));
-    float *sY = sDtx + (size_t)TL * rows_wg;
+    float *sC = sB + TL * N;
+    float *sDec = sC + k * N;                                          // scalar: [T]; diag: sDt [T][rows_wg]
+    float *sDtx = sDec + (DIAG ? TL * rows_wg : ((TL + 3) & ~3));
+    float *sY = sDtx + TL * rows_wg;
 
-    const int HP = p.H * p.P;
+    // ---- token staging: uniform bases (element units of the I/O type), 32-bit offsets -----------------
+    const int H = p.H, HP = p.H * p.P, GN = p.G * N;
     const int nthreads = blockDim.x;
-    const int g = DIAG ? 0 : (int)(((long)hd * p.G) / p.H);
-    const int heads_per_group = p.H / p.G;
+    int g = 0;                                           // B/C group of this head
+    bool first_head_of_group = true;
+    if (!DIAG && p.G > 1) {
+        const int hpg = p.H / p.G;
+        g = hd / hpg;
+        first_head_of_group = hd - g * hpg == 0;
+    }
     const bool first_tile = tile == 0;
-    const bool writes_B = !materialize && first_tile && (DIAG || (hd % heads_per_group) == 0);
+    const bool writes_B = !materialize && first_tile && first_head_of_group;
+    const int ch0 = DIAG ? row0 : hd * p.P + row0;       // first x / conv channel of this workgroup
+    const int dth0 = DIAG ? row0 : hd;                   // first dt entry of this workgroup
+    const size_t tok_in = (size_t)b * k, tok_win = (size_t)b * p.kmax;   // first token row of this sequence
+    // pending window (read: half `par`; written: the other half) and this round's inputs
     const void *winB = p.win_B[par];
     void *winB_out = p.win_B[par ^ 1];
     const void *winX = p.win_xc[par];
     void *winX_out = p.win_xc[par ^ 1];
     const void *winDt = p.win_dt[par];
     void *winDt_out = p.win_dt[par ^ 1];
+    const size_t oB_win = tok_win * GN + (size_t)g * N, oB_in = tok_in * GN + (size_t)g * N;
+    const size_t oX_win = tok_win * HP + ch0, oX_in = tok_in * HP + ch0;
+    const size_t oDt_win = tok_win * H + dth0, oDt_in = tok_in * H + dth0;
+    const float D_h = DIAG ? 0.f : p.D[hd];
+    const float A_h = DIAG ? 0.f : p.A[hd];
+    // x (and dt): 16-byte vectors when channel offsets allow, else one element at a time
+    const bool vec_rows = (rows_dom % EV) == 0 && (rows_wg % EV) == 0 && (DIAG || (p.P % EV) == 0);
+    const int log2VR = p.log2_rows_wg - ilog2(EV);       // rows_wg is a power of two
+    const int nXv = vec_rows ? (T << log2VR) : 0;        // x vectors to stage
+    int conv_head = 0;
+    if constexpr (CONV) conv_head = p.conv_head[b] & (p.ring_len - 1);
 
-    for (int idx = tid; idx < T * N; idx += nthreads) {
-        const int tt = idx / N, n = idx - tt * N;
-        float v;
-        if (tt < pd) {
-            v = load_io(winB, (((size_t)b * p.kmax + tt) * p.G + g) * N + n, p.io);
-        } else {
-            const int t = tt - pd;
-            v = load_io(p.Bm, (((size_t)b * k + t) * p.G + g) * N + n, p.io);
-            if (writes_B) store_io(winB_out, (((size_t)b * p.kmax + t) * p.G + g) * N + n, v, p.io);
-            sC[(size_t)t * N + n] = load_io(p.Cm, (((size_t)b * k + t) * p.G + g) * N + n, p.io);
-        }
-        sB[(size_t)tt * N + n] = v;
-    }
-
-    if constexpr (!DIAG) {
-        const float A_h = p.A[hd];
-        for (int tt = tid; tt < T; tt += nthreads) {
-            float dtv;
-            if (tt < pd) {
-                dtv = load_io(winDt, ((size_t)b * p.kmax + tt) * p.H + hd, p.io);
-            } else {
-                dtv = load_io(p.dt, ((size_t)b * k + (tt - pd)) * p.H + hd, p.io);
-                if (first_tile && !materialize) store_io(winDt_out, ((size_t)b * p.kmax + (tt - pd)) * p.H + hd, dtv, p.io);
+    struct BReq { int tt, n; bool on; };
+    struct XReq { int tt, i; bool on, inb; };
+    auto b_req = [&](int idx, int count) {
+        BReq q;
+        q.on = idx < count;
+        const int c = q.on ? idx : 0;
+        q.tt = c >> LOG2VN;
+        q.n = (c & (VN - 1)) * EV;
+        return q;
+    };
+    auto x_req = [&](int idx) {
+        XReq q;
+        q.on = idx < nXv;
+        const int c = q.on ? idx : 0;
+        q.tt = c >> log2VR;
+        q.i = (c - (q.tt << log2VR)) * EV;
+        q.inb = row0 + q.i < rows_dom;
+        if (!q.inb) q.i = 0;                             // clamp: loads stay in bounds, results are not used
+        return q;
+    };
+    // Loads return raw bits; decoding to fp32 happens in the *_use step, after everything is in flight.
+    // Lanes with nothing to fetch issue no request.
+    auto b_load = [&](const BReq &q) {                   // B of token tt (pending window or this round's input)
+        uint4 r = make_uint4(0, 0, 0, 0);
+        const bool old = q.tt < pd;
+        if (q.on) r = Vec::load_raw(old ? winB : p.Bm, (old ? oB_win + q.tt * GN : oB_in + (q.tt - pd) * GN) + q.n);
+        return r;
+    };
+    auto c_load = [&](const BReq &q) {
+        uint4 r = make_uint4(0, 0, 0, 0);
+        if (q.on) r = Vec::load_raw(p.Cm, oB_in + q.tt * GN + q.n);
+        return r;
+    };
+    struct XRaw { uint4 x, dt; uint32_t dt1; uint4 tap[CONV ? W - 1 : 1], wv[CONV ? W : 1], bias; };
+    auto x_load = [&](const XReq &q) {
+        XRaw r;
+        r.dt = make_uint4(0, 0, 0, 0);
+        r.dt1 = 0;
+        r.x = make_uint4(0, 0, 0, 0);
+        if (!q.on) return r;                             // idle lane: no request at all
+        const bool old = q.tt < pd;
+        const int t = q.tt - pd;
+        if (CONV && !old) {
+            // newest tap = this token's raw input; older taps from earlier inputs of the round or the ring
+            r.x = Vec::load_raw(p.x_raw, oX_in + t * HP + q.i);
+#pragma unroll
+            for (int w = 0; w < W - 1; ++w) {
+                const int j = t - (W - 1) + w;           // position relative to the round's first token
+                const bool from_ring = j < 0;
+                const size_t ring_row = (size_t)b * p.ring_len + ((conv_head + 1 + j) & (p.ring_len - 1));
+                r.tap[w] = Vec::load_raw(from_ring ? p.ring : p.x_raw, (from_ring ? ring_row * HP + ch0 : oX_in + j * HP) + q.i);
             }
-            sDec[tt] = expf(dtv * A_h);
+#pragma unroll
+            for (int w = 0; w < W; ++w) r.wv[w] = Vec::load_raw(p.wgt, (size_t)(ch0 + q.i) * W + w * EV);
+            r.bias = p.bias ? Vec::load_raw(p.bias, ch0 + q.i) : make_uint4(0, 0, 0, 0);
+        } else {
+            r.x = Vec::load_raw(old ? winX : p.xc, (old ? oX_win + q.tt * HP : oX_in + t * HP) + q.i);
         }
-    }
+        if constexpr (DIAG) r.dt = Vec::load_raw(old ? winDt : p.dt, (old ? oDt_win + q.tt * H : oDt_in + t * H) + q.i);
+        else r.dt1 = Vec::load_raw1(old ? winDt : p.dt, old ? oDt_win + q.tt * H : oDt_in + t * H);
+        return r;
+    };
+    auto b_use = [&](const BReq &q, uint4 raw) {
+        if (!q.on) return;
+        if (q.tt >= pd && writes_B) Vec::store_raw(winB_out, oB_win + (q.tt - pd) * GN + q.n, raw);
+        float v[EV];
+        Vec::decode(raw, v);
+#pragma unroll
+        for (int e = 0; e < EV; ++e) sB[q.tt * N + q.n + e] = v[e];
+    };
+    auto c_use = [&](const BReq &q, uint4 raw) {
+        if (!q.on) return;
+        float v[EV];
+        Vec::decode(raw, v);
+#pragma unroll
+        for (int e = 0; e < EV; ++e) sC[q.tt * N + q.n + e] = v[e];
+    };
+    auto x_use = [&](const XReq &q, const XRaw &r) {
+        if (!q.on || !q.inb) return;                     // rows past the domain are never read back
+        const int t = q.tt - pd;
+        float xv[EV], dtv[EV], Dv[EV];
+        uint4 xbits = r.x;
+        Vec::decode(r.x, xv);
+        if (CONV && t >= 0) {
+            // width-4 causal depthwise conv, fp32 accumulate in tap order, rounded to the I/O type
+            float tap[W - 1][EV], wv[W * EV], bias[EV];
+#pragma unroll
+            for (int w = 0; w < W - 1; ++w) Vec::decode(r.tap[w], tap[w]);
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                float tmp[EV];
+                Vec::decode(r.wv[w], tmp);
+#pragma unroll
+                for (int e = 0; e < EV; ++e) wv[w * EV + e] = tmp[e];      // wgt[channel c][tap] sits at [c*W + tap]
+            }
+            Vec::decode(r.bias, bias);
+            Vec::store_raw(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 + t) & (p.ring_len - 1))) * HP + ch0 + q.i, r.x);
+#pragma unroll
+            for (int e = 0; e < EV; ++e) {
+                float s = bias[e];
+                s = fmaf(wv[e * W + 0], tap[0][e], s);
+                s = fmaf(wv[e * W + 1], tap[1][e], s);
+                s = fmaf(wv[e * W + 2], tap[2][e], s);
+                s = fmaf(wv[e * W + 3], xv[e], s);
+                if (p.conv_act == SSMV_ACT_SILU) s = s / (1.f + expf(-s));
+                xv[e] = s;
+            }
+            xbits = Vec::encode(xv);
+            Vec::decode(xbits, xv);                      // what is fed on is what is stored
+        }
+        if constexpr (DIAG) {
+            Vec::decode(r.dt, dtv);
+        } else {
+            const float d = Vec::decode1(r.dt1);
+#pragma unroll
+            for (int e = 0; e < EV; ++e) dtv[e] = d;
+        }
+#pragma unroll
+        for (int e = 0; e < EV; ++e) Dv[e] = DIAG ? p.D[row0 + q.i + e] : D_h;
+        if (t >= 0 && !materialize) {
+            Vec::store_raw(winX_out, oX_win + t * HP + q.i, xbits);
+            if (DIAG) Vec::store_raw(winDt_out, oDt_win + t * H + q.i, r.dt);
+        }
+#pragma unroll
+        for (int e = 0; e < EV; ++e) {
+            sDtx[q.tt * rows_wg + q.i + e] = dtv[e] * xv[e];
+            if (DIAG) sDec[q.tt * rows_wg + q.i + e] = dtv[e];             // A carries the log2(e) factor
+            if (t >= 0) sY[t * rows_wg + q.i + e] = Dv[e] * xv[e];
+        }
+    };
+    auto dec_load = [&](int tt) {                        // scalar mode: dt of token tt for the decay factor
+        const bool old = tt < pd || T == 0;
+        return Vec::load_raw1(old ? winDt : p.dt, old ? oDt_win + tt * H : oDt_in + (tt - pd) * H);
+    };
+    auto dec_use = [&](int tt, uint32_t raw) {
+        if (tt >= pd && first_tile && !materialize) Vec::store_raw1(winDt_out, oDt_win + (tt - pd) * H, raw);
+        sDec[tt] = expf(Vec::decode1(raw) * A_h);
+    };
 
-    {
-        const float D_h = DIAG ? 0.f : p.D[hd];
+    // first pass: every thread issues its B, C, x (and dt) loads, then consumes them
+    const int nB = T << LOG2VN, nC = k << LOG2VN;
+    const BReq qB = b_req(tid, nB), qC = b_req(tid, nC);
+    const XReq qX = x_req(tid);
+    const uint4 fB = b_load(qB);
+    const uint4 fC = c_load(qC);
+    const XRaw fX = x_load(qX);
+    uint32_t fDec = 0;
+    if constexpr (!DIAG) if ((int)tid < T) fDec = dec_load(tid);
+    __builtin_amdgcn_sched_barrier(0);
+    SSMV_TP(2);
+    b_use(qB, fB);
+    c_use(qC, fC);
+    x_use(qX, fX);
+    if (!DIAG && (int)tid < T) dec_use(tid, fDec);
+    // whatever one pass did not cover (large k, small workgroups)
+    for (int idx = tid + nthreads; idx < nB; idx += nthreads) {
+        const BReq q = b_req(idx, nB);
+        b_use(q, b_load(q));
+    }
+    for (int idx = tid + nthreads; idx < nC; idx += nthreads) {
+        const BReq q = b_req(idx, nC);
+        c_use(q, c_load(q));
+    }
+    for (int idx = tid + nthreads; idx < nXv; idx += nthreads) {
+        const XReq q = x_req(idx);
+        x_use(q, x_load(q));
+    }
+    if constexpr (!DIAG) {
+        for (int tt = tid + nthreads; tt < T; tt += nthreads) dec_use(tt, dec_load(tt));
+    }
+    if (!vec_rows) {
+        // odd shapes: one (token,row) element at a time
         for (int idx = tid; idx < T * rows_wg; idx += nthreads) {
             const int tt = idx / rows_wg, i = idx - tt * rows_wg;
-            const int row = row0 + i;
+            const int t = tt - pd;
             float xv = 0.f, dtv = 0.f, Dv = D_h;
-            if (row < rows_dom) {
-                const int ch = DIAG ? row : hd * p.P + row;            // conv channel == x channel
-                const int dth = DIAG ? row : hd;
-                if (tt < pd) {
-                    xv = load_io(winX, ((size_t)b * p.kmax + tt) * HP + ch, p.io);
-                    dtv = load_io(winDt, ((size_t)b * p.kmax + tt) * p.H + dth, p.io);
+            if (row0 + i < rows_dom) {
+                const size_t dti = DIAG ? i : 0;
+                if (t < 0) {
+                    xv = load_io(winX, oX_win + tt * HP + i, IO);
+                    dtv = load_io(winDt, oDt_win + tt * H + dti, IO);
                 } else {
-                    const int t = tt - pd;
-                    xv = load_io(p.xc, ((size_t)b * k + t) * HP + ch, p.io);
-                    dtv = load_io(p.dt, ((size_t)b * k + t) * p.H + dth, p.io);
+                    if constexpr (CONV) {
+                        float s = p.bias ? load_io(p.bias, ch0 + i, IO) : 0.f;
+#pragma unroll
+                        for (int w = 0; w < W; ++w) {
+                            const int j = t - (W - 1) + w;
+                            const size_t ring_row = (size_t)b * p.ring_len + ((conv_head + 1 + j) & (p.ring_len - 1));
+                            const float tapv = j < 0 ? load_io(p.ring, ring_row * HP + ch0 + i, IO) : load_io(p.x_raw, oX_in + j * HP + i, IO);
+                            s = fmaf(load_io(p.wgt, (size_t)(ch0 + i) * W + w, IO), tapv, s);
+                            if (w == W - 1)
+                                store_io(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 + t) & (p.ring_len - 1))) * HP + ch0 + i, tapv, IO);
+                        }
+                        if (p.conv_act == SSMV_ACT_SILU) s = s / (1.f + expf(-s));
+                        xv = IO == SSMV_BF16 ? bf16_bits_to_f32(f32_to_bf16_bits(s)) : s;
+                    } else {
+                        xv = load_io(p.xc, oX_in + t * HP + i, IO);
+                    }
+                    dtv = load_io(p.dt, oDt_in + t * H + dti, IO);
                     if (!materialize) {
-                        store_io(winX_out, ((size_t)b * p.kmax + t) * HP + ch, xv, p.io);
-                        if (DIAG) store_io(winDt_out, ((size_t)b * p.kmax + t) * p.H + dth, dtv, p.io);
+                        store_io(winX_out, oX_win + t * HP + i, xv, IO);
+                        if (DIAG) store_io(winDt_out, oDt_win + t * H + dti, dtv, IO);
                     }
                 }
-                if (DIAG) Dv = p.D[row];
+                if (DIAG) Dv = p.D[row0 + i];
             }
-            sDtx[(size_t)tt * rows_wg + i] = dtv * xv;
-            if (DIAG) sDec[(size_t)tt * rows_wg + i] = dtv;      // A carries the log2(e) factor
-            if (tt >= pd) sY[(size_t)(tt - pd) * rows_wg + i] = Dv * xv;
+            sDtx[tt * rows_wg + i] = dtv * xv;
+            if (DIAG) sDec[tt * rows_wg + i] = dtv;                        // A carries the log2(e) factor
+            if (t >= 0) sY[t * rows_wg + i] = Dv * xv;
         }
     }
     if (!materialize && first_tile && hd == 0 && tid == 0) p.last_k[b] = k;
+    SSMV_TP(3);
     __syncthreads();
+    SSMV_TP(4);
 
     // one recurrence step on the lane's strips: h <- decay*h + (dt*x) * B
-    auto step = [&](int tt, float4 (&Bv)[V]) {
+    auto step = [&](int tt) {
+        v4f Bv[V];
 #pragma unroll
-        for (int v = 0; v < V; ++v) Bv[v] = *reinterpret_cast<const float4 *>(sB + (size_t)tt * N + v * (LPR * 4) + sub * 4);
+        for (int v = 0; v < V; ++v) Bv[v] = *reinterpret_cast<const v4f *>(sB + tt * N + v * (LPR * 4) + sub * 4);
         float dec = 0.f;
         if constexpr (!DIAG) dec = sDec[tt];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const float dtx = sDtx[(size_t)tt * rows_wg + lrow[r]];
+            const float dtx = sDtx[tt * rows_wg + lrow[r]];
             float dt2 = 0.f;
-            if constexpr (DIAG) dt2 = sDec[(size_t)tt * rows_wg + lrow[r]];
+            if constexpr (DIAG) dt2 = sDec[tt * rows_wg + lrow[r]];
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                float4 d4;
+                v4f d4;
                 if constexpr (DIAG) {
                     d4.x = __builtin_amdgcn_exp2f(dt2 * a2[r][v].x);
                     d4.y = __builtin_amdgcn_exp2f(dt2 * a2[r][v].y);
                     d4.z = __builtin_amdgcn_exp2f(dt2 * a2[r][v].z);
                     d4.w = __builtin_amdgcn_exp2f(dt2 * a2[r][v].w);
                 } else {
-                    d4 = make_float4(dec, dec, dec, dec);
+                    d4 = v4f{dec, dec, dec, dec};
                 }
                 h[r][v].x = fmaf(d4.x, h[r][v].x, dtx * Bv[v].x);
                 h[r][v].y = fmaf(d4.y, h[r][v].y, dtx * Bv[v].y);
@@ -235,36 +425,31 @@ __global__ __launch_bounds__(256) void verify_kernel(const VerifyParams p)
             }
         }
     };
-
     auto store_state = [&](float *dst_base) {
+        float *dst = dst_base + (grow << LOG2N);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (!rvalid[r]) continue;
-            float *dst = dst_base + (grow0 + row0 + lrow[r]) * N + sub * 4;
 #pragma unroll
-            for (int v = 0; v < V; ++v) *reinterpret_cast<float4 *>(dst + v * (LPR * 4)) = h[r][v];
+            for (int v = 0; v < V; ++v) *reinterpret_cast<v4f *>(dst + loff[r] + v * (LPR * 4)) = h[r][v];
         }
     };
 
-    // ---- (i) replay the pending tokens: no outputs ------------------------------------------------
-    for (int s = 0; s < pd; ++s) {
-        float4 Bv[V];
-        step(s, Bv);
-    }
+    // (i) replay the pending tokens: no outputs
+    for (int s = 0; s < pd; ++s) step(s);
     if (materialize) {
         store_state(p.h_out);
         return;
     }
-    // ---- (ii) snapshot h_j --------------------------------------------------------------------------
+    // (ii) snapshot h_j
     if (pd > 0) store_state(p.state + (size_t)((cur + 1) % 3) * p.slot_stride);
-
-    // ---- (iii) the k draft tokens -------------------------------------------------------------------
+    // (iii) the k draft tokens
+    SSMV_TP(5);
     for (int t = 0; t < k; ++t) {
-        float4 Bv[V];
-        step(pd + t, Bv);
-        float4 Cv[V];
+        step(pd + t);
+        v4f Cv[V];
 #pragma unroll
-        for (int v = 0; v < V; ++v) Cv[v] = *reinterpret_cast<const float4 *>(sC + (size_t)t * N + v * (LPR * 4) + sub * 4);
+        for (int v = 0; v < V; ++v) Cv[v] = *reinterpret_cast<const v4f *>(sC + t * N + v * (LPR * 4) + sub * 4);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             float acc = 0.f;
@@ -276,30 +461,54 @@ __global__ __launch_bounds__(256) void verify_kernel(const VerifyParams p)
                 acc = fmaf(Cv[v].w, h[r][v].w, acc);
             }
             acc = row_sum<LPR>(acc);
-            if (sub == 0) sY[(size_t)t * rows_wg + lrow[r]] += acc;
+            // y = D*x + C.h : no-return LDS add by the row's first lane, nothing waits on it
+            if (sub == 0) __hip_atomic_fetch_add(&sY[t * rows_wg + lrow[r]], acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     }
-    // ---- (iv) snapshot h_k ---------------------------------------------------------------------------
+    // (iv) snapshot h_k
+    SSMV_TP(6);
     store_state(p.state + (size_t)((cur + 2) % 3) * p.slot_stride);
 
     __syncthreads();
-    for (int idx = tid; idx < k * rows_wg; idx += nthreads) {
-        const int t = idx / rows_wg, i = idx - t * rows_wg;
-        const int row = row0 + i;
-        if (row < rows_dom) {
-            const int ch = DIAG ? row : hd * p.P + row;
-            store_io(p.y, ((size_t)b * k + t) * HP + ch, sY[idx], p.io);
+    if (vec_rows) {
+        for (int idx = tid; idx < (k << log2VR); idx += nthreads) {
+            const int t = idx >> log2VR, i = (idx - (t << log2VR)) * EV;
+            if (row0 + i < rows_dom) {
+                float yv[EV];
+#pragma unroll
+                for (int e = 0; e < EV; ++e) yv[e] = sY[t * rows_wg + i + e];
+                Vec::store_raw(p.y, oX_in + t * HP + i, Vec::encode(yv));
+            }
+        }
+    } else {
+        for (int idx = tid; idx < k * rows_wg; idx += nthreads) {
+            const int t = idx / rows_wg, i = idx - t * rows_wg;
+            if (row0 + i < rows_dom) store_io(p.y, oX_in + t * HP + i, sY[idx], IO);
         }
     }
+#ifdef SSMV_TRACE
+    if (trace_ && threadIdx.x == 0) {                   // this wave's stores have been acknowledged
+        asm volatile("s_waitcnt vmcnt(0)");
+        trace_[7] = wall_clock64();
+    }
+#endif
 }
 
 // ---- host side ------------------------------------------------------------------------------------
 
 template <int N, int R, bool DIAG>
-static int launch_one(const VerifyParams &p, int waves, size_t lds_bytes, hipStream_t stream)
+static int launch_io(const VerifyParams &p, int waves, size_t lds_bytes, hipStream_t stream)
 {
-    const long groups = (long)p.batch * (DIAG ? 1 : p.H) * p.tiles;
-    hipLaunchKernelGGL((verify_kernel<N, R, DIAG>), dim3((unsigned)groups), dim3(64 * waves), lds_bytes, stream, p);
+    const dim3 grid = DIAG ? dim3(p.tiles, p.batch, 1) : dim3(p.tiles, p.H, p.batch);
+    const dim3 block(64 * waves);
+    const bool conv = p.x_raw != nullptr;
+    if (p.io == SSMV_BF16) {
+        if (conv) hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_BF16, true>), grid, block, lds_bytes, stream, p);
+        else hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_BF16, false>), grid, block, lds_bytes, stream, p);
+    } else {
+        if (conv) hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_F32, true>), grid, block, lds_bytes, stream, p);
+        else hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_F32, false>), grid, block, lds_bytes, stream, p);
+    }
     return (int)hipGetLastError();
 }
 
@@ -309,10 +518,10 @@ static int launch_n(const VerifyParams &p, VerifyShape s, size_t lds_bytes, hipS
     constexpr int V = (N / lanes_per_row(N)) / 4;
     constexpr int MAXRV = DIAG ? 4 : 8;      // registers: R*V float4 of state (+ as many of A in diag mode)
     switch (s.rows_per_lane) {
-        case 1: return launch_one<N, 1, DIAG>(p, s.waves, lds_bytes, stream);
-        case 2: if constexpr (2 * V <= MAXRV) return launch_one<N, 2, DIAG>(p, s.waves, lds_bytes, stream); break;
-        case 4: if constexpr (4 * V <= MAXRV) return launch_one<N, 4, DIAG>(p, s.waves, lds_bytes, stream); break;
-        case 8: if constexpr (8 * V <= MAXRV) return launch_one<N, 8, DIAG>(p, s.waves, lds_bytes, stream); break;
+        case 1: return launch_io<N, 1, DIAG>(p, s.waves, lds_bytes, stream);
+        case 2: if constexpr (2 * V <= MAXRV) return launch_io<N, 2, DIAG>(p, s.waves, lds_bytes, stream); break;
+        case 4: if constexpr (4 * V <= MAXRV) return launch_io<N, 4, DIAG>(p, s.waves, lds_bytes, stream); break;
+        case 8: if constexpr (8 * V <= MAXRV) return launch_io<N, 8, DIAG>(p, s.waves, lds_bytes, stream); break;
         default: break;
     }
     return (int)hipErrorInvalidConfiguration;

@@ -72,6 +72,22 @@ class HipLayer:
         ssmv.ssm_verify_multistep(self.dims, self.cache.c, xc, dt, Bm, Cm, self.A, self.D, k, y)
         return y
 
+    def conv_verify(self, x_raw, dt, Bm, Cm):
+        """conv roll + verification in one launch; returns (y, xc read back from the stash window)."""
+        k = x_raw.shape[1]
+        y = torch.empty_like(x_raw)
+        ssmv.ssm_conv_verify_multistep(self.dims, self.cache.c, x_raw, self.conv_w, self.conv_b, dt, Bm, Cm, self.A, self.D, k, y)
+        return y, self.stashed_xc(k)
+
+    def stashed_xc(self, k):
+        """This round's conv outputs as the verify kernel stashed them (the half that commit makes current)."""
+        wl = self.wl
+        par = self.cache.ints()["win_par"]
+        buf = self.cache.buffers["win_xc%d" % (par ^ 1)]
+        n = wl.batch * wl.kmax_eff * wl.conv_channels
+        t = buf.view(TORCH_IO[wl.io])[:n].view(wl.batch, wl.kmax_eff, wl.conv_channels)
+        return t[:, :k].clone()
+
     def commit(self, accepted_dev):
         ssmv.ssm_commit_rollback(self.dims, self.cache.c, accepted_dev)
 
@@ -88,7 +104,7 @@ def eager_oracle(wl: Workload, lp, conv_init=None):
 
 
 def run_parity(wl: Workload, data: WorkloadData, layer: int = 0, x_override=None, check_state_every: int = 1,
-               conv_init=None, reverify: bool = False):
+               conv_init=None, reverify: bool = False, fused: bool = False):
     """Full parity of one layer over all rounds of `data`.  Returns the worst errors seen."""
     lp = data.layers[layer]
     tol = TOL[wl.io]
@@ -102,11 +118,17 @@ def run_parity(wl: Workload, data: WorkloadData, layer: int = 0, x_override=None
         y_ref, xc_ref, _ = ora.verify(x_raw, rd.dt[layer], rd.B[layer], rd.C[layer])
         d_x, d_dt = to_dev(x_raw, wl.io), to_dev(rd.dt[layer], wl.io)
         d_B, d_C = to_dev(rd.B[layer], wl.io), to_dev(rd.C[layer], wl.io)
-        xc = hip.conv(d_x)
-        y = hip.verify(xc, d_dt, d_B, d_C)
-        if reverify:                                   # verify twice: must be idempotent
-            y2 = hip.verify(xc, d_dt, d_B, d_C)
-            assert torch.equal(y, y2), "verify is not idempotent (round %d)" % i
+        if fused:
+            y, xc = hip.conv_verify(d_x, d_dt, d_B, d_C)
+            if reverify:
+                y2, xc2 = hip.conv_verify(d_x, d_dt, d_B, d_C)
+                assert torch.equal(y, y2) and torch.equal(xc, xc2), "fused verify is not idempotent (round %d)" % i
+        else:
+            xc = hip.conv(d_x)
+            y = hip.verify(xc, d_dt, d_B, d_C)
+            if reverify:                                   # verify twice: must be idempotent
+                y2 = hip.verify(xc, d_dt, d_B, d_C)
+                assert torch.equal(y, y2), "verify is not idempotent (round %d)" % i
         bk.verify(k)
         e_xc, e_y = rel_err(to_host(xc), xc_ref), rel_err(to_host(y), y_ref)
         assert e_xc <= tol, "round %d: conv output error %.3g > %.3g" % (i, e_xc, tol)

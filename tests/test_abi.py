@@ -43,10 +43,12 @@ def test_cache_sizes():
     S = 32 * 32 * 128 * 64 * 4
     assert s[0] == 3 * S and s[1] == 32 * 8 * 4096 * 2 and s[2] == s[3] == 32 * 4 * 4096 * 2
     assert s[4] == s[5] == 32 * 4 * 32 * 2 and s[6] == s[7] == 32 * 4 * 64 * 2
-    assert s[8:] == [128, 128, 256, 128, 128, 4, 4]
+    assert s[8:] == [256] * 7                       # every size is rounded up to 256-byte granules
     d = ssmv.make_dims(1, 8192, 1, 16, kmax=8, io="f32", a_mode="diag")
     s = ssmv.ssmv_cache_sizes(d)
     assert s[0] == 3 * 8192 * 16 * 4 and s[1] == 16 * 8192 * 4
+    d = ssmv.make_dims(1, 1, 3, 16, kmax=1, io="bf16")
+    assert ssmv.ssmv_cache_sizes(d) == [768, 256] + [256] * 13
 
 
 def _code(fn, *a):

@@ -23,103 +23,176 @@ def _auto_tuning():
     ssmv.ssmv_set_tuning(0, 0)
 
 
-def test_cfg0_tiny_fp32():
+FUSED = pytest.mark.parametrize("fused", [False, True], ids=["split", "fused"])
+
+
+@FUSED
+def test_cfg0_tiny_fp32(fused):
     wl = CONFIGS["cfg0"]
-    worst = run_parity(wl, generate(wl), reverify=True)
+    worst = run_parity(wl, generate(wl), reverify=True, fused=fused)
     print("cfg0 worst errors", worst)
 
 
-def test_cfg1_shape_reduced_batch_bf16():
+@FUSED
+def test_cfg1_shape_reduced_batch_bf16(fused):
     wl = CONFIGS["cfg1"].scaled(nheads=4, rounds=16)
-    run_parity(wl, generate(wl), reverify=True)
+    run_parity(wl, generate(wl), reverify=True, fused=fused)
 
 
-def test_cfg1_shape_reduced_fp32():
+@FUSED
+def test_cfg1_shape_reduced_fp32(fused):
     wl = CONFIGS["cfg1"].scaled(nheads=3, rounds=16, io="f32", batch=2)
-    run_parity(wl, generate(wl))
+    run_parity(wl, generate(wl), fused=fused)
 
 
+@FUSED
 @pytest.mark.parametrize("rows,waves", [(r, w) for r in (1, 2, 4, 8) for w in (1, 2, 4)])
-def test_every_launch_shape_scalar(rows, waves):
+def test_every_launch_shape_scalar(rows, waves, fused):
     ssmv.ssmv_set_tuning(rows, waves)
     wl = Workload("shape", "scalar", batch=3, nheads=3, headdim=72, dstate=64, k=4, rounds=8, io="f32",
                   accept="uniform", seed=rows * 10 + waves)
-    run_parity(wl, generate(wl))
+    run_parity(wl, generate(wl), fused=fused)
 
 
+@FUSED
 @pytest.mark.parametrize("rows,waves", [(r, w) for r in (1, 2, 4) for w in (1, 2, 4)])
-def test_every_launch_shape_diag(rows, waves):
+def test_every_launch_shape_diag(rows, waves, fused):
     ssmv.ssmv_set_tuning(rows, waves)
     wl = Workload("shaped", "diag", batch=2, nheads=203, headdim=1, dstate=16, k=5, rounds=8, io="f32",
                   accept="geometric", seed=rows * 10 + waves)
-    run_parity(wl, generate(wl))
+    run_parity(wl, generate(wl), fused=fused)
 
 
+@FUSED
 @pytest.mark.parametrize("N,P,G,io", [(16, 24, 1, "f32"), (32, 20, 2, "bf16"), (64, 40, 2, "f32"),
-                                      (128, 12, 1, "f32"), (256, 6, 4, "bf16"), (64, 1, 1, "f32"), (16, 100, 4, "bf16")])
-def test_state_sizes_groups_and_ragged_tiles(N, P, G, io):
-    wl = Workload("sz", "scalar", batch=2, nheads=4, headdim=P, dstate=N, k=3, rounds=10, io=io, accept="uniform",
-                  ngroups=G, kmax=5, seed=N + P)
-    run_parity(wl, generate(wl))
+                                      (128, 12, 1, "f32"), (256, 6, 4, "bf16"), (64, 1, 1, "f32"), (16, 100, 4, "bf16"),
+                                      (64, 128, 1, "bf16"), (128, 64, 8, "bf16")])
+def test_state_sizes_groups_and_ragged_tiles(N, P, G, io, fused):
+    wl = Workload("sz", "scalar", batch=2, nheads=8 if G == 8 else 4, headdim=P, dstate=N, k=3, rounds=10, io=io,
+                  accept="uniform", ngroups=G, kmax=5, seed=N + P)
+    run_parity(wl, generate(wl), fused=fused)
 
 
+@FUSED
 @pytest.mark.parametrize("N,io", [(16, "bf16"), (32, "f32"), (64, "bf16")])
-def test_diag_mode(N, io):
+def test_diag_mode(N, io, fused):
     wl = CONFIGS["cfg2"].scaled(nheads=1000, dstate=N, rounds=12, io=io, batch=2)
-    run_parity(wl, generate(wl), reverify=True)
+    run_parity(wl, generate(wl), reverify=True, fused=fused)
 
 
+@FUSED
 @pytest.mark.parametrize("act,bias", [("silu", True), ("none", False), ("silu", False)])
-def test_conv_variants_and_initial_history(act, bias):
-    wl = Workload("conv", "scalar", batch=2, nheads=2, headdim=36, dstate=16, k=4, rounds=8, io="bf16",
+@pytest.mark.parametrize("P,io", [(36, "bf16"), (64, "bf16"), (64, "f32")])
+def test_conv_variants_and_initial_history(act, bias, P, io, fused):
+    wl = Workload("conv", "scalar", batch=2, nheads=2, headdim=P, dstate=16, k=4, rounds=8, io=io,
                   accept="uniform", conv_act=act, conv_bias=bias, seed=5)
     data = generate(wl)
     init = np.random.default_rng(1).standard_normal((wl.batch, wl.conv_width - 1, wl.conv_channels)).astype(np.float32)
     from workload import round_to_io
-    run_parity(wl, data, conv_init=round_to_io(init, wl.io))
+    run_parity(wl, data, conv_init=round_to_io(init, wl.io), fused=fused)
 
 
-def test_conv_scalar_channel_path():
-    # channel count that is no multiple of the 16-byte vector: the one-channel-per-thread kernel
+@FUSED
+def test_conv_scalar_channel_path(fused):
+    # channel count that is no multiple of the 16-byte vector: one channel at a time
     wl = Workload("convs", "scalar", batch=2, nheads=3, headdim=7, dstate=16, k=4, rounds=6, io="bf16",
                   accept="uniform", seed=6)
-    run_parity(wl, generate(wl))
+    run_parity(wl, generate(wl), fused=fused)
 
 
-def test_varying_k_up_to_the_limit():
+@FUSED
+def test_varying_k_up_to_the_limit(fused):
     ks = [1, 16, 7, 16, 2, 9, 1, 1, 16, 4]
     wl = Workload("kmax", "scalar", batch=3, nheads=2, headdim=32, dstate=64, k=4, kmax=16, rounds=len(ks), io="f32",
                   accept="uniform", seed=8)
-    run_parity(wl, generate(wl, k_schedule=ks))
+    run_parity(wl, generate(wl, k_schedule=ks), fused=fused)
 
 
-def test_varying_k_diag():
+@FUSED
+def test_varying_k_diag(fused):
     ks = [3, 16, 1, 12, 16, 5]
     wl = Workload("kmaxd", "diag", batch=2, nheads=70, headdim=1, dstate=16, k=4, kmax=16, rounds=len(ks), io="bf16",
                   accept="uniform", seed=9)
-    run_parity(wl, generate(wl, k_schedule=ks))
+    run_parity(wl, generate(wl, k_schedule=ks), fused=fused)
 
 
+@FUSED
+def test_large_k_on_the_8b_shape(fused):
+    # k = 16 with up to 15 pending tokens: the staging needs more than one pass per thread
+    ks = [16, 16, 8, 16, 16, 3]
+    wl = CONFIGS["cfg1"].scaled(nheads=2, batch=3, kmax=16, rounds=len(ks), seed=21)
+    data = generate(wl, k_schedule=ks)
+    data.rounds[0].accepted[:] = [15, 7, 16]
+    data.rounds[1].accepted[:] = [15, 15, 2]
+    run_parity(wl, data, fused=fused)
+
+
+@FUSED
 @pytest.mark.parametrize("accept", ["all", "none"])
-def test_accept_streaks(accept):
+def test_accept_streaks(accept, fused):
     wl = Workload("streak", "scalar", batch=2, nheads=2, headdim=64, dstate=64, k=4, rounds=7, io="bf16",
                   accept=accept, seed=10)
-    run_parity(wl, generate(wl))
+    run_parity(wl, generate(wl), fused=fused)
 
 
-def test_mixed_pending_counts_in_one_batch():
+@FUSED
+def test_mixed_pending_counts_in_one_batch(fused):
     wl = Workload("mixed", "scalar", batch=9, nheads=2, headdim=64, dstate=64, k=6, rounds=12, io="f32",
                   accept="uniform", seed=11)
     data = generate(wl)
     # force every pend value 0..k-1 to occur together in one launch
     data.rounds[0].accepted[:] = [0, 1, 2, 3, 4, 5, 6, 3, 0]
-    run_parity(wl, data)
+    run_parity(wl, data, fused=fused)
 
 
-def test_k1_single_step_rounds():
+@FUSED
+def test_k1_single_step_rounds(fused):
     wl = Workload("k1", "scalar", batch=2, nheads=2, headdim=64, dstate=64, k=1, rounds=10, io="f32",
                   accept="uniform", seed=12)
-    run_parity(wl, generate(wl))
+    run_parity(wl, generate(wl), fused=fused)
+
+
+def test_fused_launch_equals_the_two_separate_launches_bit_for_bit():
+    """Same fp32 order and rounding in both paths: y, the stash, the ring and the snapshots must be identical."""
+    for wl in (CONFIGS["cfg1"].scaled(nheads=3, batch=2, rounds=6, conv_act="silu"),
+               CONFIGS["cfg2"].scaled(nheads=512, batch=2, rounds=6)):
+        data = generate(wl)
+        lp = data.layers[0]
+        a, bb = HipLayer(wl, lp), HipLayer(wl, lp)
+        for rd in data.rounds:
+            dx, ddt, dB, dC = (to_dev(v, wl.io) for v in (rd.x_raw, rd.dt[0], rd.B[0], rd.C[0]))
+            xc = a.conv(dx)
+            y1 = a.verify(xc, ddt, dB, dC)
+            y2, xc2 = bb.conv_verify(dx, ddt, dB, dC)
+            assert torch.equal(y1, y2) and torch.equal(xc, xc2)
+            acc = torch.from_numpy(rd.accepted).to("cuda")
+            a.commit(acc)
+            bb.commit(acc)
+            for name in ("state", "conv_ring", "win_dt0", "win_dt1", "win_B0", "win_B1"):
+                assert torch.equal(a.cache.buffers[name], bb.cache.buffers[name]), name
+
+
+def test_commit_multi_matches_single_commits():
+    wl = Workload("cm", "scalar", batch=5, nheads=1, headdim=16, dstate=16, k=3, rounds=6, io="f32",
+                  accept="uniform", seed=17)
+    data = generate(wl)
+    lp = data.layers[0]
+    n_layers = 40                                        # more than one launch covers
+    multi = [HipLayer(wl, lp) for _ in range(n_layers)]
+    single = HipLayer(wl, lp)
+    for rd in data.rounds:
+        dx, ddt, dB, dC = (to_dev(v, wl.io) for v in (rd.x_raw, rd.dt[0], rd.B[0], rd.C[0]))
+        for layer in multi + [single]:
+            layer.conv_verify(dx, ddt, dB, dC)
+        acc = torch.from_numpy(rd.accepted).to("cuda")
+        ssmv.ssm_commit_rollback_multi(single.dims, [m.cache.c for m in multi], acc)
+        single.commit(acc)
+        ref = single.cache.ints()
+        for m in multi:
+            got = m.cache.ints()
+            for name in ("cur_slot", "pend", "pos", "conv_head", "last_k"):
+                assert np.array_equal(got[name], ref[name]), name
+            assert got["win_par"] == ref["win_par"] and got["err_flag"] == 0
 
 
 def test_multistep_equals_single_steps_on_gpu():
