@@ -129,9 +129,9 @@ int choose_shape(const ssmv_dims *d, int lds_tokens, int k, VerifyShape *out, in
                 const long t = (dom + rw - 1) / rw;
                 const long groups = domains * t;
                 const bool wasteful = rw > dom && rw > rpi;     // tile larger than the domain
-                long score;
-                if (groups >= 1024 && !wasteful) score = 1000000L + rw;      // big tiles first
-                else score = wasteful ? -rw : 500000L - rw;                   // else the more groups the better
+                long score;                                                    // ties: more waves, fewer rows per lane
+                if (groups >= 1024 && !wasteful) score = 1000000L + 16L * rw + w;   // big tiles first
+                else score = wasteful ? -16L * rw + w : 500000L - 16L * rw + w;     // else the more groups the better
                 if (score > best_rows) { best_rows = score; bestR = r; bestW = w; }
             }
         }

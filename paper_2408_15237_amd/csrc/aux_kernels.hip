@@ -204,25 +204,41 @@ int launch_reset(const ResetParams &p, hipStream_t stream)
 }
 
 // ---- plain copy: read n bytes, write them once or twice ----------------------------------------------
-__global__ __launch_bounds__(256) void copy_probe_kernel(const float4 *__restrict__ src, float4 *__restrict__ dst0,
-                                                         float4 *__restrict__ dst1, size_t n16)
+typedef float copy_v4f __attribute__((ext_vector_type(4)));
+
+// A workgroup copies contiguous tiles of 8 x 256 float4 (32 KiB): eight loads in flight per thread, then the
+// stores - the verify kernel's shape - with the same streaming hints as its state traffic.
+__global__ __launch_bounds__(256) void copy_probe_kernel(const copy_v4f *__restrict__ src, copy_v4f *__restrict__ dst0,
+                                                         copy_v4f *__restrict__ dst1, size_t n16)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
-        const float4 v = src[i];
-        dst0[i] = v;
-        if (dst1) dst1[i] = v;
+    constexpr int U = 8;
+    const size_t tiles = (n16 + U * 256 - 1) / (U * 256);
+    for (size_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        const size_t base = tile * (U * 256) + threadIdx.x;
+        copy_v4f v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t i = base + u * 256;
+            v[u] = __builtin_nontemporal_load(src + (i < n16 ? i : n16 - 1));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t i = base + u * 256;
+            if (i < n16) {
+                __builtin_nontemporal_store(v[u], dst0 + i);
+                if (dst1) __builtin_nontemporal_store(v[u], dst1 + i);
+            }
+        }
     }
 }
 
 int launch_copy_probe(const void *src, void *dst0, void *dst1, size_t n_bytes, hipStream_t stream)
 {
     const size_t n16 = n_bytes / 16;
-    const int block = 256;
-    size_t want = (n16 + block - 1) / block;
-    unsigned grid = (unsigned)(want > 256 * 16 ? 256 * 16 : (want ? want : 1));
-    hipLaunchKernelGGL(copy_probe_kernel, dim3(grid), dim3(block), 0, stream, reinterpret_cast<const float4 *>(src),
-                       reinterpret_cast<float4 *>(dst0), reinterpret_cast<float4 *>(dst1), n16);
+    const size_t tiles = (n16 + 8 * 256 - 1) / (8 * 256);
+    const unsigned grid = (unsigned)(tiles > 65536 ? 65536 : tiles);
+    hipLaunchKernelGGL(copy_probe_kernel, dim3(grid), dim3(256), 0, stream, reinterpret_cast<const copy_v4f *>(src),
+                       reinterpret_cast<copy_v4f *>(dst0), reinterpret_cast<copy_v4f *>(dst1), n16);
     return (int)hipGetLastError();
 }
 

@@ -21,6 +21,10 @@
 //   * y_t[row] = sum_n C_t[n] h[row][n] is EPL FMAs in-lane, then a reduction over the LPR lanes
 //     of the row with DPP row operations; the row's first lane adds it to D*x in LDS with a
 //     no-return LDS add, and the workgroup writes y with 16-byte stores at the end.
+//   * The state is read and the snapshots are written with non-temporal accesses: each byte is touched
+//     once per round and a decoder streams the model's weights through the caches before the next one.
+//     (Mixing a temporal and a non-temporal access to one address under an `if` lets the optimiser merge
+//     them and drop the hint - keep them unconditional.)
 #pragma once
 
 #include "ssmv_internal.h"
@@ -63,8 +67,9 @@ __host__ __device__ inline size_t verify_lds_floats(int T, int k, int N, int row
     return n;
 }
 
+// At least 4 waves per SIMD (<= 128 VGPRs): a second generation of workgroups costs far more than a few moves.
 template <int N, int R, bool DIAG, int IO, bool CONV>
-__global__ __launch_bounds__(256) void verify_kernel(const VerifyParams p)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void verify_kernel(const VerifyParams p)
 {
     constexpr int LPR = lanes_per_row(N);
     constexpr int EPL = N / LPR;
@@ -129,7 +134,8 @@ __global__ __launch_bounds__(256) void verify_kernel(const VerifyParams p)
             loff[r] = (lrow[r] << LOG2N) + sub * 4;
             const unsigned o = rvalid[r] ? loff[r] : sub * 4;         // clamp to row 0: unconditional in-bounds load
 #pragma unroll
-            for (int v = 0; v < V; ++v) h[r][v] = *reinterpret_cast<const v4f *>(src + o + v * (LPR * 4));
+            // streamed once per round: non-temporal, so that 100 MB per launch do not churn the caches
+            for (int v = 0; v < V; ++v) h[r][v] = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(src + o + v * (LPR * 4)));
             if constexpr (DIAG) {
 #pragma unroll
                 for (int v = 0; v < V; ++v) a2[r][v] = *reinterpret_cast<const v4f *>(srcA + o + v * (LPR * 4)) * LOG2E;
@@ -431,7 +437,7 @@ __global__ __launch_bounds__(256) void verify_kernel(const VerifyParams p)
         for (int r = 0; r < R; ++r) {
             if (!rvalid[r]) continue;
 #pragma unroll
-            for (int v = 0; v < V; ++v) *reinterpret_cast<v4f *>(dst + loff[r] + v * (LPR * 4)) = h[r][v];
+            for (int v = 0; v < V; ++v) __builtin_nontemporal_store(h[r][v], reinterpret_cast<v4f *>(dst + loff[r] + v * (LPR * 4)));
         }
     };
 
