@@ -216,4 +216,49 @@ struct IoVec<SSMV_BF16> {
     }
 };
 
+// XW elements of the I/O type as one access: 16 bytes (XW == IoVec::EV) or 4 bytes (2 bf16 / 1 fp32)
+template <int IO, int XW>
+struct XVec {
+    static_assert(XW == IoVec<IO>::EV, "16-byte case");
+    using Raw = uint4;
+    static __device__ __forceinline__ Raw zero() { return make_uint4(0, 0, 0, 0); }
+    static __device__ __forceinline__ Raw load(const void *base, size_t idx) { return IoVec<IO>::load_raw(base, idx); }
+    static __device__ __forceinline__ void store(void *base, size_t idx, Raw r) { IoVec<IO>::store_raw(base, idx, r); }
+    static __device__ __forceinline__ void decode(Raw r, float (&v)[XW]) { IoVec<IO>::decode(r, v); }
+    static __device__ __forceinline__ Raw encode(const float (&v)[XW]) { return IoVec<IO>::encode(v); }
+};
+
+template <>
+struct XVec<SSMV_BF16, 2> {
+    using Raw = uint32_t;
+    static __device__ __forceinline__ Raw zero() { return 0u; }
+    static __device__ __forceinline__ Raw load(const void *base, size_t idx)
+    {
+        return *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint16_t *>(base) + idx);
+    }
+    static __device__ __forceinline__ void store(void *base, size_t idx, Raw r)
+    {
+        *reinterpret_cast<uint32_t *>(reinterpret_cast<uint16_t *>(base) + idx) = r;
+    }
+    static __device__ __forceinline__ void decode(Raw r, float (&v)[2])
+    {
+        v[0] = __uint_as_float(r << 16);
+        v[1] = __uint_as_float(r & 0xffff0000u);
+    }
+    static __device__ __forceinline__ Raw encode(const float (&v)[2])
+    {
+        return (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
+    }
+};
+
+template <>
+struct XVec<SSMV_F32, 1> {
+    using Raw = uint32_t;
+    static __device__ __forceinline__ Raw zero() { return 0u; }
+    static __device__ __forceinline__ Raw load(const void *base, size_t idx) { return reinterpret_cast<const uint32_t *>(base)[idx]; }
+    static __device__ __forceinline__ void store(void *base, size_t idx, Raw r) { reinterpret_cast<uint32_t *>(base)[idx] = r; }
+    static __device__ __forceinline__ void decode(Raw r, float (&v)[1]) { v[0] = __uint_as_float(r); }
+    static __device__ __forceinline__ Raw encode(const float (&v)[1]) { return __float_as_uint(v[0]); }
+};
+
 }  // namespace ssmv

@@ -178,10 +178,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const size_t oDt_win = tok_win * H + dth0, oDt_in = tok_in * H + dth0;
     const float D_h = DIAG ? 0.f : p.D[hd];
     const float A_h = DIAG ? 0.f : p.A[hd];
-    // x (and dt): 16-byte vectors when channel offsets allow, else one element at a time
-    const bool vec_rows = (rows_dom % EV) == 0 && (rows_wg % EV) == 0 && (DIAG || (p.P % EV) == 0);
-    const int log2VR = p.log2_rows_wg - ilog2(EV);       // rows_wg is a power of two
-    const int nXv = vec_rows ? (T << log2VR) : 0;        // x vectors to stage
+    // x (and dt) items: XW adjacent rows of one token.  Without the conv a 16-byte vector; with it only 4 bytes
+    // (2 bf16 / 1 fp32), so that the conv arithmetic spreads over all lanes and waves instead of 64 lanes of
+    // one wave (a workgroup's waves run on different SIMDs).  Odd shapes fall back to one element at a time.
+    constexpr int XW = CONV ? (IO == SSMV_BF16 ? 2 : 1) : EV;
+    using XV = XVec<IO, XW>;
+    using XRawT = typename XV::Raw;
+    const bool vec_rows = (rows_dom % XW) == 0 && (rows_wg % XW) == 0 && (DIAG || (p.P % XW) == 0);
+    const int log2VR = p.log2_rows_wg - ilog2(XW);       // rows_wg is a power of two
+    const int nXv = vec_rows ? (T << log2VR) : 0;        // x items to stage
     int conv_head = 0;
     if constexpr (CONV) conv_head = p.conv_head[b] & (p.ring_len - 1);
 
@@ -200,7 +205,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         q.on = idx < nXv;
         const int c = q.on ? idx : 0;
         q.tt = c >> log2VR;
-        q.i = (c - (q.tt << log2VR)) * EV;
+        q.i = (c - (q.tt << log2VR)) * XW;
         q.inb = row0 + q.i < rows_dom;
         if (!q.inb) q.i = 0;                             // clamp: loads stay in bounds, results are not used
         return q;
@@ -218,32 +223,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         if (q.on) r = Vec::load_raw(p.Cm, oB_in + q.tt * GN + q.n);
         return r;
     };
-    struct XRaw { uint4 x, dt; uint32_t dt1; uint4 tap[CONV ? W - 1 : 1], wv[CONV ? W : 1], bias; };
+    struct XRaw { XRawT x, dt, bias; uint32_t dt1; XRawT tap[CONV ? W - 1 : 1]; uint4 wv; };
     auto x_load = [&](const XReq &q) {
         XRaw r;
-        r.dt = make_uint4(0, 0, 0, 0);
+        r.x = XV::zero();
+        r.dt = XV::zero();
         r.dt1 = 0;
-        r.x = make_uint4(0, 0, 0, 0);
         if (!q.on) return r;                             // idle lane: no request at all
         const bool old = q.tt < pd;
         const int t = q.tt - pd;
         if (CONV && !old) {
             // newest tap = this token's raw input; older taps from earlier inputs of the round or the ring
-            r.x = Vec::load_raw(p.x_raw, oX_in + t * HP + q.i);
+            r.x = XV::load(p.x_raw, oX_in + t * HP + q.i);
 #pragma unroll
             for (int w = 0; w < W - 1; ++w) {
                 const int j = t - (W - 1) + w;           // position relative to the round's first token
                 const bool from_ring = j < 0;
                 const size_t ring_row = (size_t)b * p.ring_len + ((conv_head + 1 + j) & (p.ring_len - 1));
-                r.tap[w] = Vec::load_raw(from_ring ? p.ring : p.x_raw, (from_ring ? ring_row * HP + ch0 : oX_in + j * HP) + q.i);
+                r.tap[w] = XV::load(from_ring ? p.ring : p.x_raw, (from_ring ? ring_row * HP + ch0 : oX_in + j * HP) + q.i);
             }
-#pragma unroll
-            for (int w = 0; w < W; ++w) r.wv[w] = Vec::load_raw(p.wgt, (size_t)(ch0 + q.i) * W + w * EV);
-            r.bias = p.bias ? Vec::load_raw(p.bias, ch0 + q.i) : make_uint4(0, 0, 0, 0);
+            r.wv = Vec::load_raw(p.wgt, (size_t)(ch0 + q.i) * W);           // XW channels x W taps = 16 bytes
+            r.bias = p.bias ? XV::load(p.bias, ch0 + q.i) : XV::zero();
         } else {
-            r.x = Vec::load_raw(old ? winX : p.xc, (old ? oX_win + q.tt * HP : oX_in + t * HP) + q.i);
+            r.x = XV::load(old ? winX : p.xc, (old ? oX_win + q.tt * HP : oX_in + t * HP) + q.i);
         }
-        if constexpr (DIAG) r.dt = Vec::load_raw(old ? winDt : p.dt, (old ? oDt_win + q.tt * H : oDt_in + t * H) + q.i);
+        if constexpr (DIAG) r.dt = XV::load(old ? winDt : p.dt, (old ? oDt_win + q.tt * H : oDt_in + t * H) + q.i);
         else r.dt1 = Vec::load_raw1(old ? winDt : p.dt, old ? oDt_win + q.tt * H : oDt_in + t * H);
         return r;
     };
@@ -265,25 +269,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     auto x_use = [&](const XReq &q, const XRaw &r) {
         if (!q.on || !q.inb) return;                     // rows past the domain are never read back
         const int t = q.tt - pd;
-        float xv[EV], dtv[EV], Dv[EV];
-        uint4 xbits = r.x;
-        Vec::decode(r.x, xv);
+        float xv[XW], dtv[XW], Dv[XW];
+        XRawT xbits = r.x;
+        XV::decode(r.x, xv);
         if (CONV && t >= 0) {
             // width-4 causal depthwise conv, fp32 accumulate in tap order, rounded to the I/O type
-            float tap[W - 1][EV], wv[W * EV], bias[EV];
+            float tap[W - 1][XW], wv[EV], bias[XW];
 #pragma unroll
-            for (int w = 0; w < W - 1; ++w) Vec::decode(r.tap[w], tap[w]);
+            for (int w = 0; w < W - 1; ++w) XV::decode(r.tap[w], tap[w]);
+            Vec::decode(r.wv, wv);                       // wgt[channel c][tap] sits at [c*W + tap]
+            XV::decode(r.bias, bias);
+            XV::store(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 + t) & (p.ring_len - 1))) * HP + ch0 + q.i, r.x);
 #pragma unroll
-            for (int w = 0; w < W; ++w) {
-                float tmp[EV];
-                Vec::decode(r.wv[w], tmp);
-#pragma unroll
-                for (int e = 0; e < EV; ++e) wv[w * EV + e] = tmp[e];      // wgt[channel c][tap] sits at [c*W + tap]
-            }
-            Vec::decode(r.bias, bias);
-            Vec::store_raw(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 + t) & (p.ring_len - 1))) * HP + ch0 + q.i, r.x);
-#pragma unroll
-            for (int e = 0; e < EV; ++e) {
+            for (int e = 0; e < XW; ++e) {
                 float s = bias[e];
                 s = fmaf(wv[e * W + 0], tap[0][e], s);
                 s = fmaf(wv[e * W + 1], tap[1][e], s);
@@ -292,24 +290,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
                 if (p.conv_act == SSMV_ACT_SILU) s = s / (1.f + expf(-s));
                 xv[e] = s;
             }
-            xbits = Vec::encode(xv);
-            Vec::decode(xbits, xv);                      // what is fed on is what is stored
+            xbits = XV::encode(xv);
+            XV::decode(xbits, xv);                       // what is fed on is what is stored
         }
         if constexpr (DIAG) {
-            Vec::decode(r.dt, dtv);
+            XV::decode(r.dt, dtv);
         } else {
             const float d = Vec::decode1(r.dt1);
 #pragma unroll
-            for (int e = 0; e < EV; ++e) dtv[e] = d;
+            for (int e = 0; e < XW; ++e) dtv[e] = d;
         }
 #pragma unroll
-        for (int e = 0; e < EV; ++e) Dv[e] = DIAG ? p.D[row0 + q.i + e] : D_h;
+        for (int e = 0; e < XW; ++e) Dv[e] = DIAG ? p.D[row0 + q.i + e] : D_h;
         if (t >= 0 && !materialize) {
-            Vec::store_raw(winX_out, oX_win + t * HP + q.i, xbits);
-            if (DIAG) Vec::store_raw(winDt_out, oDt_win + t * H + q.i, r.dt);
+            XV::store(winX_out, oX_win + t * HP + q.i, xbits);
+            if (DIAG) XV::store(winDt_out, oDt_win + t * H + q.i, r.dt);
         }
 #pragma unroll
-        for (int e = 0; e < EV; ++e) {
+        for (int e = 0; e < XW; ++e) {
             sDtx[q.tt * rows_wg + q.i + e] = dtv[e] * xv[e];
             if (DIAG) sDec[q.tt * rows_wg + q.i + e] = dtv[e];             // A carries the log2(e) factor
             if (t >= 0) sY[t * rows_wg + q.i + e] = Dv[e] * xv[e];
@@ -327,10 +325,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     // first pass: every thread issues its B, C, x (and dt) loads, then consumes them
     const int nB = T << LOG2VN, nC = k << LOG2VN;
     const BReq qB = b_req(tid, nB), qC = b_req(tid, nC);
-    const XReq qX = x_req(tid);
+    const XReq qX = x_req(tid), qX2 = x_req(tid + nthreads);           // two x items per thread before any wait
     const uint4 fB = b_load(qB);
     const uint4 fC = c_load(qC);
     const XRaw fX = x_load(qX);
+    const XRaw fX2 = x_load(qX2);
     uint32_t fDec = 0;
     if constexpr (!DIAG) if ((int)tid < T) fDec = dec_load(tid);
     __builtin_amdgcn_sched_barrier(0);
@@ -338,6 +337,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     b_use(qB, fB);
     c_use(qC, fC);
     x_use(qX, fX);
+    x_use(qX2, fX2);
     if (!DIAG && (int)tid < T) dec_use(tid, fDec);
     // whatever one pass did not cover (large k, small workgroups)
     for (int idx = tid + nthreads; idx < nB; idx += nthreads) {
@@ -348,7 +348,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         const BReq q = b_req(idx, nC);
         c_use(q, c_load(q));
     }
-    for (int idx = tid + nthreads; idx < nXv; idx += nthreads) {
+    for (int idx = tid + 2 * nthreads; idx < nXv; idx += nthreads) {
         const XReq q = x_req(idx);
         x_use(q, x_load(q));
     }
@@ -476,9 +476,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     store_state(p.state + (size_t)((cur + 2) % 3) * p.slot_stride);
 
     __syncthreads();
-    if (vec_rows) {
-        for (int idx = tid; idx < (k << log2VR); idx += nthreads) {
-            const int t = idx >> log2VR, i = (idx - (t << log2VR)) * EV;
+    const bool vec_y = (rows_dom % EV) == 0 && (rows_wg % EV) == 0 && (DIAG || (p.P % EV) == 0);
+    const int log2VY = p.log2_rows_wg - ilog2(EV);
+    if (vec_y) {
+        for (int idx = tid; idx < (k << log2VY); idx += nthreads) {
+            const int t = idx >> log2VY, i = (idx - (t << log2VY)) * EV;
             if (row0 + i < rows_dom) {
                 float yv[EV];
 #pragma unroll
