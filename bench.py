@@ -39,6 +39,9 @@ def parse_args():
     ap.add_argument("--rows", type=int, default=0, help="verify kernel: state rows per lane (0 = auto)")
     ap.add_argument("--waves", type=int, default=0, help="verify kernel: waves per workgroup (0 = auto)")
     ap.add_argument("--kernel-only", action="store_true", help="only the verify-kernel loop (for rocprofv3 runs)")
+    ap.add_argument("--naive", action="store_true",
+                    help="the unfused baseline the paper starts from: one state snapshot copy, then k single-token rounds "
+                         "(conv, verify with k=1, commit of 1) per layer-round; rollback work is not even included")
     ap.add_argument("--split", action="store_true",
                     help="three launches per step (conv1d_state_update, ssm_verify_multistep, ssm_commit_rollback) instead of "
                          "the fused conv+verify launch and one commit launch per round over all caches")
@@ -136,7 +139,14 @@ def main():
         ssmv.ssmv_cache_reset(dims, c.c, h0, None)
     torch.cuda.synchronize()
 
-    fused = not args.split
+    fused = not (args.split or args.naive)
+    if args.naive:
+        ones = torch.ones(wl.batch, dtype=torch.int32, device=dev)
+        for r in rounds:
+            for name in ("x", "dt", "B", "C"):
+                r[name + "1"] = [r[name][:, t:t + 1].contiguous() for t in range(k)]
+        x1_buf, y1_buf = torch.empty_like(rounds[0]["x1"][0]), torch.empty_like(rounds[0]["x1"][0])
+        slot_bytes = (sizes[0] // 3) // 16 * 16
     all_caches = (ssmv.ssmv_cache * n_inst)(*[c.c for c in caches])
 
     # The rotating caches play the SSM layers of one model: a round verifies layer after layer, then the
@@ -145,7 +155,14 @@ def main():
         i = s % n_inst
         c = caches[i].c
         r = rounds[(s // n_inst) % n_rounds]
-        if fused:
+        if args.naive:
+            base = caches[i].buffers["state"].data_ptr()
+            ssmv.ssmv_copy_probe(base, base + slot_bytes, None, slot_bytes)          # snapshot of the state before the drafts
+            for t in range(k):
+                ssmv.conv1d_state_update(dims, c, r["x1"][t], conv_w, conv_b, 1, x1_buf)
+                ssmv.ssm_verify_multistep(dims, c, x1_buf, r["dt1"][t], r["B1"][t], r["C1"][t], A, D, 1, y1_buf)
+                ssmv.ssm_commit_rollback(dims, c, ones)
+        elif fused:
             ssmv.ssm_conv_verify_multistep(dims, c, r["x"], conv_w, conv_b, r["dt"], r["B"], r["C"], A, D, k, y_buf)
             if i == n_inst - 1:
                 ssmv.ssm_commit_rollback_multi(dims, all_caches, r["acc"])
@@ -328,7 +345,8 @@ def main():
                    "batch": wl.batch, "k": k, "rounds": n_rounds, "instances": n_inst,
                    "launch": "hip-graph" if not args.no_graph else "eager",
                    "path": "fused conv+verify launch per layer, one commit launch per round over all caches" if fused
-                           else "conv, verify and commit launches per layer"},
+                           else ("naive: snapshot copy + k single-token (conv, verify, commit) rounds per layer" if args.naive
+                                 else "conv, verify and commit launches per layer")},
         "hbm_gbps_whole_step": round(result["step_hbm_gbps"], 1),
         "copy_r1w2_gbps": round(copy_gbps, 1),
         "roofline": roofline,
