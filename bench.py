@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--rows", type=int, default=0, help="verify kernel: state rows per lane (0 = auto)")
     ap.add_argument("--waves", type=int, default=0, help="verify kernel: waves per workgroup (0 = auto)")
     ap.add_argument("--kernel-only", action="store_true", help="only the verify-kernel loop (for rocprofv3 runs)")
+    ap.add_argument("--single-snapshot", action="store_true",
+                    help="the single-snapshot variant: h_k is never stored, every accepted token is replayed next round")
     ap.add_argument("--naive", action="store_true",
                     help="the unfused baseline the paper starts from: one state snapshot copy, then k single-token rounds "
                          "(conv, verify with k=1, commit of 1) per layer-round; rollback work is not even included")
@@ -48,14 +50,14 @@ def parse_args():
     return ap.parse_args()
 
 
-def pend_after(accepted_rounds, k_rounds):
+def pend_after(accepted_rounds, k_rounds, hj_only=False):
     """Host-side accounting of the pending-token count per sequence before each round (for byte counts only)."""
     import numpy as np
     pend = np.zeros_like(accepted_rounds[0])
     out = []
     for acc, k in zip(accepted_rounds, k_rounds):
         out.append(pend.copy())
-        pend = np.where(acc == k, 0, acc)
+        pend = acc.copy() if hj_only else np.where(acc == k, 0, acc)
     return out
 
 
@@ -68,7 +70,7 @@ def verify_bytes(wl, pend, k, fused):
     Cx, H, GN = wl.conv_channels, wl.nheads, wl.ngroups * wl.dstate
     total = 0
     for pd in pend:
-        total += S * (2 + (1 if pd > 0 else 0))
+        total += S * ((1 if wl.snapshot_mode == "hj_only" else 2) + (1 if pd > 0 else 0))
         total += k * (Cx + H + 2 * GN) * e          # xc (or x_raw), dt, B, C in
         total += k * Cx * e                         # y out
         total += k * (Cx + H + GN) * e              # stash out
@@ -111,6 +113,8 @@ def main():
     wl = CONFIGS[args.workload]
     if wl.layers != 1:
         wl = wl.scaled(layers=1)           # the metric is per SSM layer; the stack is covered by the parity tests
+    if args.single_snapshot:
+        wl = wl.scaled(snapshot_mode="hj_only")
     data = generate(wl)
     lp = data.layers[0]
     io_t = torch.bfloat16 if wl.io == "bf16" else torch.float32
@@ -120,7 +124,8 @@ def main():
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).to(io_t).contiguous()
 
     dims = ssmv.make_dims(wl.batch, wl.nheads, wl.headdim, wl.dstate, ngroups=wl.ngroups, kmax=wl.kmax_eff,
-                          ring_len=wl.ring_len, io=wl.io, a_mode=wl.a_mode, conv_act=wl.conv_act)
+                          ring_len=wl.ring_len, io=wl.io, a_mode=wl.a_mode, conv_act=wl.conv_act,
+                          snapshot_mode=wl.snapshot_mode)
     sizes = ssmv.ssmv_cache_sizes(dims)
     cache_bytes = sum(sizes)
     n_inst = args.instances or max(1, math.ceil(args.footprint_gib * 2 ** 30 / cache_bytes))
@@ -181,7 +186,8 @@ def main():
     K = args.steps if args.steps > 0 else n_inst * n_rounds
     W = args.warmup if args.warmup >= 0 else max(3, n_inst)
     rounds_run = (W + K + n_inst - 1) // n_inst + 1
-    pend_sched = pend_after([data.rounds[i % n_rounds].accepted for i in range(rounds_run)], [k] * rounds_run)
+    pend_sched = pend_after([data.rounds[i % n_rounds].accepted for i in range(rounds_run)], [k] * rounds_run,
+                            hj_only=wl.snapshot_mode == "hj_only")
 
     result = {}
     if args.kernel_only:
@@ -344,6 +350,7 @@ def main():
                                   n_rounds, n_inst, n_inst * cache_bytes / 2 ** 30),
                    "batch": wl.batch, "k": k, "rounds": n_rounds, "instances": n_inst,
                    "launch": "hip-graph" if not args.no_graph else "eager",
+                   "snapshots": "h_j only (single-snapshot variant)" if wl.snapshot_mode == "hj_only" else "h_j and h_k (Algorithm 2)",
                    "path": "fused conv+verify launch per layer, one commit launch per round over all caches" if fused
                            else ("naive: snapshot copy + k single-token (conv, verify, commit) rounds per layer" if args.naive
                                  else "conv, verify and commit launches per layer")},

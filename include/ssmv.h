@@ -58,6 +58,11 @@ typedef enum {
 enum { SSMV_F32 = 0, SSMV_BF16 = 1 };           /* io_dtype: storage type of tokens, y, conv ring, windows */
 enum { SSMV_A_SCALAR = 0, SSMV_A_DIAG = 1 };    /* a_mode: A[H] (one decay per head) or A[H][N], headdim 1  */
 enum { SSMV_ACT_NONE = 0, SSMV_ACT_SILU = 1 };  /* conv_act                                                */
+/* snapshot_mode.  BOTH is Algorithm 2 as printed: verify stores h_j (when tokens were pending) and h_k, and a
+ * fully accepted round makes h_k the live state.  HJ_ONLY never stores h_k: every accepted token, also those of
+ * a fully accepted round, stays pending and is replayed by the next verify.  Same outputs and same logical
+ * state; about a third fewer bytes per round for up to k more replay steps. */
+enum { SSMV_SNAP_BOTH = 0, SSMV_SNAP_HJ_ONLY = 1 };
 
 #define SSMV_KMAX_LIMIT 16      /* largest supported kmax                   */
 #define SSMV_CONV_WIDTH 4       /* the only supported conv width            */
@@ -76,6 +81,7 @@ typedef struct {
     int32_t io_dtype;       /* SSMV_F32 | SSMV_BF16                                               */
     int32_t a_mode;         /* SSMV_A_SCALAR | SSMV_A_DIAG                                        */
     int32_t conv_act;       /* SSMV_ACT_NONE | SSMV_ACT_SILU                                      */
+    int32_t snapshot_mode;  /* SSMV_SNAP_BOTH | SSMV_SNAP_HJ_ONLY                                 */
 } ssmv_dims;
 
 /* The per-layer cache (Section 4.2: one cached state per sequence, advanced lazily;
@@ -87,7 +93,7 @@ typedef struct {
     void    *win_dt[2];    /* [batch][kmax][H]    io_dtype                                          */
     void    *win_B[2];     /* [batch][kmax][G][N] io_dtype                                          */
     int32_t *cur_slot;     /* [batch] in {0,1,2}: the live slot, holds the state at `pos`           */
-    int32_t *pend;         /* [batch] in [0,kmax): accepted tokens not yet folded into the slot     */
+    int32_t *pend;         /* [batch] in [0,kmax) (HJ_ONLY: [0,kmax]): accepted tokens not yet folded  */
     int64_t *pos;          /* [batch] tokens folded into state[cur_slot]                            */
     int32_t *conv_head;    /* [batch] ring index of the newest COMMITTED raw input                  */
     int32_t *last_k;       /* [batch] k of the verify that has not been committed yet, else 0       */
@@ -126,8 +132,8 @@ int conv1d_state_update(const ssmv_dims *dims, const ssmv_cache *cache, const vo
  * from the window, (ii) if pend[b] > 0 store that state h_j into slot
  * (cur+1)%3, (iii) run the k draft tokens
  *   h <- exp(dt_t*A) * h + (dt_t * x_t) (x) B_t ,   y_t = C_t . h + D * x_t
- * (Eq. 1; fp32 state and arithmetic), (iv) store h_k into slot (cur+2)%3 and
- * this round's (xc, dt, B) into the other half of the window.  Intermediate
+ * (Eq. 1; fp32 state and arithmetic), (iv) store h_k into slot (cur+2)%3 (not with
+ * SSMV_SNAP_HJ_ONLY) and this round's (xc, dt, B) into the other half of the window.  Intermediate
  * states and the discrete parameters live in registers/LDS only.
  *   xc [batch][k][H*P], dt [batch][k][H], Bm, Cm [batch][k][G][N]: io_dtype, device;
  *   dt is the final positive step size; A [H] or [H][N] (negative reals) and D [H]:
@@ -158,7 +164,8 @@ int ssm_conv_verify_multistep(const ssmv_dims *dims, const ssmv_cache *cache, co
  *   otherwise   :                                      pend <- a
  *   always      : conv_head <- (conv_head+a) & (R-1), last_k <- 0
  * and win_par flips once.  A commit with no verify pending changes nothing and
- * sets err_flag. */
+ * sets err_flag.  With SSMV_SNAP_HJ_ONLY the first case does not exist: pend > 0
+ * moves to h_j as above, and pend <- a in every case. */
 int ssm_commit_rollback(const ssmv_dims *dims, const ssmv_cache *cache, const int32_t *accepted,
                         void *hip_stream);
 

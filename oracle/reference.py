@@ -170,9 +170,12 @@ class BookkeepingModel:
     slot (cur+2)%3 and touches no integer except last_k.
     """
 
-    def __init__(self, batch: int, ring_len: int, conv_width: int = 4):
+    def __init__(self, batch: int, ring_len: int, conv_width: int = 4, hj_only: bool = False):
         assert ring_len & (ring_len - 1) == 0
         self.batch, self.R = batch, ring_len
+        # hj_only: the single-snapshot variant.  h_k is never stored; every accepted token stays pending,
+        # also after a fully accepted round, and is replayed by the next verify.
+        self.hj_only = hj_only
         self.cur = [0] * batch
         self.pend = [0] * batch
         self.pos = [0] * batch
@@ -194,7 +197,7 @@ class BookkeepingModel:
             if a < 0 or a > lk:
                 self.err = 1
                 a = min(max(a, 0), lk)
-            if a == lk:
+            if a == lk and not self.hj_only:
                 self.cur[b] = (self.cur[b] + 2) % 3
                 self.pos[b] += self.pend[b] + a
                 self.pend[b] = 0
@@ -213,7 +216,7 @@ class LazyMirror:
     """O3: fp64 mirror of the lazy three-slot policy (CPU only; proves lazy == eager)."""
 
     def __init__(self, a_mode: str, A, D, conv_w, conv_b, h0, io: str, kmax: int, ring_len: int,
-                 act: str = "none", ngroups: int = 1, conv_init=None):
+                 act: str = "none", ngroups: int = 1, conv_init=None, hj_only: bool = False):
         self.a_mode, self.io, self.act, self.G = a_mode, io, act, ngroups
         self.A, self.D = _c(A), _c(D)
         self.conv_w = _c(conv_w)
@@ -231,7 +234,8 @@ class LazyMirror:
         self.win_xc = np.zeros((2, self.batch, kmax, self.Cx))
         self.win_dt = np.zeros((2, self.batch, kmax, self.H))
         self.win_B = np.zeros((2, self.batch, kmax, ngroups, self.N))
-        self.bk = BookkeepingModel(self.batch, ring_len, self.W)
+        self.hj_only = hj_only
+        self.bk = BookkeepingModel(self.batch, ring_len, self.W, hj_only=hj_only)
 
     def _replayed(self, b: int) -> np.ndarray:
         """State of sequence b at pos+pend: live slot with the pending tokens folded in."""
@@ -268,7 +272,8 @@ class LazyMirror:
             yb, snap = scan_tokens(self.a_mode, g[None], xc[b:b + 1], dt[b:b + 1], Bm[b:b + 1], Cm[b:b + 1],
                                    self.A, self.D)
             y[b] = yb[0]
-            self.slots[(cur + 2) % 3, b] = snap[k, 0]                # snapshot h_k
+            if not self.hj_only:
+                self.slots[(cur + 2) % 3, b] = snap[k, 0]            # snapshot h_k
         npar = bk.win_par ^ 1
         self.win_xc[npar, :, :k] = xc
         self.win_dt[npar, :, :k] = dt

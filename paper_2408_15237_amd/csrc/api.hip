@@ -47,6 +47,8 @@ int check_dims(const ssmv_dims *d)
     if (d->io_dtype != SSMV_F32 && d->io_dtype != SSMV_BF16) return fail(SSMV_EINVAL, "io_dtype %d unknown", d->io_dtype);
     if (d->a_mode != SSMV_A_SCALAR && d->a_mode != SSMV_A_DIAG) return fail(SSMV_EINVAL, "a_mode %d unknown", d->a_mode);
     if (d->conv_act != SSMV_ACT_NONE && d->conv_act != SSMV_ACT_SILU) return fail(SSMV_EINVAL, "conv_act %d unknown", d->conv_act);
+    if (d->snapshot_mode != SSMV_SNAP_BOTH && d->snapshot_mode != SSMV_SNAP_HJ_ONLY)
+        return fail(SSMV_EINVAL, "snapshot_mode %d unknown", d->snapshot_mode);
     if (d->nheads % d->ngroups != 0) return fail(SSMV_EINVAL, "nheads %d not a multiple of ngroups %d", d->nheads, d->ngroups);
     if ((long)d->conv_channels != (long)d->nheads * d->headdim)
         return fail(SSMV_EINVAL, "conv_channels %d != nheads*headdim %ld", d->conv_channels, (long)d->nheads * d->headdim);
@@ -266,7 +268,9 @@ static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const void *xc
     VerifyParams p{};
     fill_verify(p, d, c);
     p.k = k;
-    p.lds_tokens = d->kmax - 1 + k;
+    p.pend_max = d->snapshot_mode == SSMV_SNAP_HJ_ONLY ? d->kmax : d->kmax - 1;
+    p.write_hk = d->snapshot_mode != SSMV_SNAP_HJ_ONLY;
+    p.lds_tokens = p.pend_max + k;
     p.xc = xc; p.dt = dt; p.Bm = Bm; p.Cm = Cm; p.A = A; p.D = D; p.y = y_out; p.h_out = nullptr;
     p.x_raw = x_raw; p.wgt = wgt; p.bias = bias;
     VerifyShape shape;
@@ -301,7 +305,9 @@ int ssmv_materialize(const ssmv_dims *d, const ssmv_cache *c, const float *A, fl
     VerifyParams p{};
     fill_verify(p, d, c);
     p.k = 0;
-    p.lds_tokens = d->kmax - 1 > 0 ? d->kmax - 1 : 1;
+    p.pend_max = d->snapshot_mode == SSMV_SNAP_HJ_ONLY ? d->kmax : d->kmax - 1;
+    p.write_hk = 0;
+    p.lds_tokens = p.pend_max > 0 ? p.pend_max : 1;
     p.A = A; p.D = A;   // D is not read when k == 0
     p.h_out = h_out;
     VerifyShape shape;
@@ -326,6 +332,7 @@ int ssm_commit_rollback_multi(const ssmv_dims *d, const ssmv_cache *caches, int3
     for (int first = 0; first < n_caches; first += kCommitMaxCaches) {
         CommitParams p{};
         p.batch = d->batch; p.R = d->ring_len; p.accepted = accepted;
+        p.hj_only = d->snapshot_mode == SSMV_SNAP_HJ_ONLY;
         p.n_caches = n_caches - first < kCommitMaxCaches ? n_caches - first : kCommitMaxCaches;
         for (int i = 0; i < p.n_caches; ++i) {
             const ssmv_cache &c = caches[first + i];

@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void commit_kernel(const CommitParams p)
         *c.err_flag = 1;
         a = a < 0 ? 0 : lk;
     }
-    if (a == lk) {                       // every draft accepted: h_k becomes the live state
+    if (a == lk && !p.hj_only) {         // every draft accepted: h_k becomes the live state
         c.cur_slot[b] = (cur + 2) % 3;
         c.pos[b] = pos + pd + a;
         c.pend[b] = 0;

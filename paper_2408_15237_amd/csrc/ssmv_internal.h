@@ -17,7 +17,9 @@ struct VerifyParams {
     int io;              // SSMV_F32 | SSMV_BF16
     int rows_wg;         // state rows one workgroup owns
     int tiles;           // scalar mode: tiles per head; diag mode: tiles per sequence
-    int lds_tokens;      // tokens the dynamic LDS was sized for (kmax-1+k)
+    int lds_tokens;      // tokens the dynamic LDS was sized for (pend_max + k)
+    int pend_max;        // largest legal pend: kmax-1, or kmax when h_k is never stored
+    int write_hk;        // 0: SSMV_SNAP_HJ_ONLY
     int log2_rows_wg;    // rows_wg is a power of two
     // fused conv roll (x_raw != nullptr): ring append + width-4 conv computed while staging
     int ring_len, conv_act;
@@ -61,7 +63,7 @@ struct CacheInts {
 constexpr int kCommitMaxCaches = 32;     // caches one commit launch covers (kernel argument space)
 
 struct CommitParams {
-    int batch, R, n_caches;
+    int batch, R, n_caches, hj_only;
     const int32_t *accepted;
     CacheInts c[kCommitMaxCaches];
 };

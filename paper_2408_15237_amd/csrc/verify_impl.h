@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
 
     // bookkeeping written by the commit kernel; clamped so that a corrupted cache cannot index out of bounds
     const int cur = (int)((unsigned)p.cur_slot[b] % 3u);
-    const int pd = min(max(p.pend[b], 0), p.kmax - 1);
+    const int pd = min(max(p.pend[b], 0), p.pend_max);
     const int par = p.win_par[0] & 1;
     const int T = pd + k;
     SSMV_TP(1);
@@ -471,9 +471,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             if (sub == 0) __hip_atomic_fetch_add(&sY[t * rows_wg + lrow[r]], acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     }
-    // (iv) snapshot h_k
+    // (iv) snapshot h_k (Algorithm 2), unless every accepted token is to stay pending
     SSMV_TP(6);
-    store_state(p.state + (size_t)((cur + 2) % 3) * p.slot_stride);
+    if (p.write_hk) store_state(p.state + (size_t)((cur + 2) % 3) * p.slot_stride);
 
     __syncthreads();
     const bool vec_y = (rows_dom % EV) == 0 && (rows_wg % EV) == 0 && (DIAG || (p.P % EV) == 0);

@@ -39,7 +39,8 @@ def to_host(t) -> np.ndarray:
 
 def dims_of(wl: Workload):
     return ssmv.make_dims(wl.batch, wl.nheads, wl.headdim, wl.dstate, ngroups=wl.ngroups, kmax=wl.kmax_eff,
-                          ring_len=wl.ring_len, io=wl.io, a_mode=wl.a_mode, conv_act=wl.conv_act)
+                          ring_len=wl.ring_len, io=wl.io, a_mode=wl.a_mode, conv_act=wl.conv_act,
+                          snapshot_mode=wl.snapshot_mode)
 
 
 class HipLayer:
@@ -110,7 +111,7 @@ def run_parity(wl: Workload, data: WorkloadData, layer: int = 0, x_override=None
     tol = TOL[wl.io]
     hip = HipLayer(wl, lp, conv_init=conv_init)
     ora = eager_oracle(wl, lp, conv_init=conv_init)
-    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width, hj_only=wl.snapshot_mode == "hj_only")
     worst = {"y": 0.0, "xc": 0.0, "h": 0.0}
     for i, rd in enumerate(data.rounds):
         x_raw = rd.x_raw if x_override is None else x_override[i]

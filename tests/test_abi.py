@@ -33,7 +33,7 @@ def test_constants_match_header():
     for name in ("SSMV_KMAX_LIMIT", "SSMV_CONV_WIDTH", "SSMV_CACHE_NPTR"):
         m = re.search(r"#define\s+%s\s+(\d+)" % name, text)
         assert int(m.group(1)) == getattr(ssmv, name)
-    assert ctypes.sizeof(ssmv.ssmv_dims) == 12 * 4
+    assert ctypes.sizeof(ssmv.ssmv_dims) == 13 * 4
     assert ctypes.sizeof(ssmv.ssmv_cache) == 15 * 8
 
 
@@ -72,6 +72,7 @@ def test_dims_validation():
     assert _code(sizes, mk(1, 4, 2, 16, a_mode="diag")) == ssmv.SSMV_EINVAL        # diag needs headdim 1
     assert _code(sizes, mk(1, 4, 1, 128, a_mode="diag")) == ssmv.SSMV_EUNSUPPORTED
     assert _code(sizes, mk(1, 4, 16, 16, io=7)) == ssmv.SSMV_EINVAL
+    assert _code(sizes, mk(1, 4, 16, 16, snapshot_mode=2)) == ssmv.SSMV_EINVAL
     assert "dstate" in ssmv.load_library().ssmv_last_error().decode() or True
 
 

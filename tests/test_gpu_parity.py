@@ -152,6 +152,52 @@ def test_k1_single_step_rounds(fused):
     run_parity(wl, generate(wl), fused=fused)
 
 
+@FUSED
+@pytest.mark.parametrize("case", ["cfg1", "cfg2", "kmax16", "all", "none", "mixed"])
+def test_single_snapshot_variant(case, fused):
+    """SSMV_SNAP_HJ_ONLY: h_k is never stored and every accepted token stays pending (up to kmax of them);
+    outputs, logical state and the integer model's bookkeeping must still match."""
+    if case == "cfg1":
+        wl, ks = CONFIGS["cfg1"].scaled(nheads=4, batch=3, rounds=16, snapshot_mode="hj_only"), None
+    elif case == "cfg2":
+        wl, ks = CONFIGS["cfg2"].scaled(nheads=1000, batch=2, rounds=12, snapshot_mode="hj_only"), None
+    elif case == "kmax16":
+        ks = [16, 16, 1, 16, 7, 16, 16, 2]
+        wl = Workload("hj16", "scalar", batch=3, nheads=2, headdim=64, dstate=64, k=4, kmax=16, rounds=len(ks), io="f32",
+                      accept="uniform", seed=31, snapshot_mode="hj_only")
+    elif case in ("all", "none"):
+        wl, ks = Workload("hjs", "scalar", batch=2, nheads=2, headdim=64, dstate=64, k=4, rounds=7, io="bf16",
+                          accept=case, seed=32, snapshot_mode="hj_only"), None
+    else:
+        wl, ks = Workload("hjm", "scalar", batch=9, nheads=2, headdim=64, dstate=64, k=6, rounds=12, io="f32",
+                          accept="uniform", seed=33, snapshot_mode="hj_only"), None
+    data = generate(wl, k_schedule=ks)
+    if case == "kmax16":
+        data.rounds[0].accepted[:] = [16, 16, 9]           # a fully accepted round leaves kmax tokens pending
+        data.rounds[1].accepted[:] = [16, 0, 16]
+    if case == "mixed":
+        data.rounds[0].accepted[:] = [0, 1, 2, 3, 4, 5, 6, 6, 0]
+    run_parity(wl, data, fused=fused, reverify=True)
+
+
+def test_single_snapshot_never_writes_the_third_slot():
+    wl = CONFIGS["cfg1"].scaled(nheads=2, batch=2, rounds=6, snapshot_mode="hj_only")
+    data = generate(wl)
+    hip = HipLayer(wl, data.layers[0])
+    hip.cache.state_view()[1:].fill_(123.0)                # slots 1, 2: sentinel
+    untouched = None
+    for rd in data.rounds:
+        ints = hip.cache.ints()
+        cur = torch.from_numpy(ints["cur_slot"]).long()
+        third = (cur + 2) % 3
+        before = hip.cache.state_view()[third, torch.arange(wl.batch)].clone()
+        dx, ddt, dB, dC = (to_dev(v, wl.io) for v in (rd.x_raw, rd.dt[0], rd.B[0], rd.C[0]))
+        hip.conv_verify(dx, ddt, dB, dC)
+        after = hip.cache.state_view()[third, torch.arange(wl.batch)]
+        assert torch.equal(before, after)
+        hip.commit(torch.from_numpy(rd.accepted).to("cuda"))
+
+
 def test_fused_launch_equals_the_two_separate_launches_bit_for_bit():
     """Same fp32 order and rounding in both paths: y, the stash, the ring and the snapshots must be identical."""
     for wl in (CONFIGS["cfg1"].scaled(nheads=3, batch=2, rounds=6, conv_act="silu"),

@@ -33,7 +33,7 @@ def _eager(wl, data, layer=0):
 def _lazy(wl, data, layer=0):
     lp = data.layers[layer]
     return oracle.LazyMirror(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.kmax_eff, wl.ring_len,
-                             wl.conv_act, wl.ngroups)
+                             wl.conv_act, wl.ngroups, hj_only=wl.snapshot_mode == "hj_only")
 
 
 @pytest.mark.parametrize("wl", [TINY, TINY_DIAG], ids=lambda w: w.name)
@@ -128,21 +128,26 @@ def _run_both(wl, data, accepted_per_round, ks=None):
         assert np.allclose(lazy.materialize(), eager.h, rtol=1e-12, atol=1e-13)
         for b in range(wl.batch):
             assert bk.pos[b] + bk.pend[b] == total[b] == eager.j[b]
-            assert bk.cur[b] in (0, 1, 2) and 0 <= bk.pend[b] < k
+            assert bk.cur[b] in (0, 1, 2) and 0 <= bk.pend[b] <= (k if bk.hj_only else k - 1)
             assert bk.conv_head[b] == (wl.conv_width - 2 + total[b]) % wl.ring_len
             assert bk.last_k[b] == 0
         assert bk.win_par == (i + 1) % 2 and bk.err == 0
     return eager, lazy
 
 
-@pytest.mark.parametrize("wl", [TINY, TINY_DIAG], ids=lambda w: w.name)
+TINY_HJ = TINY.scaled(name="tiny_hj", snapshot_mode="hj_only")
+TINY_DIAG_HJ = TINY_DIAG.scaled(name="tinyd_hj", snapshot_mode="hj_only")
+
+
+@pytest.mark.parametrize("wl", [TINY, TINY_DIAG, TINY_HJ, TINY_DIAG_HJ], ids=lambda w: w.name)
 def test_lazy_policy_equals_eager_on_random_schedule(wl):
     data = generate(wl)
     _run_both(wl, data, [rd.accepted for rd in data.rounds])
 
 
-def test_lazy_policy_with_varying_k_and_kmax():
-    wl = TINY.scaled(kmax=6, rounds=12, seed=9)
+@pytest.mark.parametrize("snap", ["both", "hj_only"])
+def test_lazy_policy_with_varying_k_and_kmax(snap):
+    wl = TINY.scaled(kmax=6, rounds=12, seed=9, snapshot_mode=snap)
     ks = [1, 6, 3, 6, 2, 5, 1, 1, 6, 4, 2, 6]
     data = generate(wl, k_schedule=ks)
     rng = np.random.default_rng(1)
@@ -150,19 +155,21 @@ def test_lazy_policy_with_varying_k_and_kmax():
     _run_both(wl, data, acc)
 
 
-def test_lazy_policy_all_accept_and_all_reject_streaks():
-    wl = TINY.scaled(rounds=9)
+@pytest.mark.parametrize("snap", ["both", "hj_only"])
+def test_lazy_policy_all_accept_and_all_reject_streaks(snap):
+    wl = TINY.scaled(rounds=9, snapshot_mode=snap)
     data = generate(wl)
     k = wl.k
     acc = [[k, k], [k, k], [0, 0], [0, 0], [k, 0], [0, k], [k - 1, 1], [k, k], [0, 0]]
     _run_both(wl, data, acc)
 
 
-def test_bruteforce_every_acceptance_sequence():
+@pytest.mark.parametrize("snap", ["both", "hj_only"])
+def test_bruteforce_every_acceptance_sequence(snap):
     """All (k+1)^rounds acceptance sequences for k<=3 over 4 rounds: lazy state == eager state, ints consistent."""
     for k in (1, 2, 3):
         wl = Workload("bf", "scalar", batch=1, nheads=2, headdim=2, dstate=3, k=k, rounds=4, io="f32",
-                      accept="uniform", seed=20 + k)
+                      accept="uniform", seed=20 + k, snapshot_mode=snap)
         data = generate(wl)
         for seq in itertools.product(range(k + 1), repeat=wl.rounds):
             _run_both(wl, data, [[a] for a in seq])
@@ -188,6 +195,26 @@ def test_bookkeeping_slot_semantics_bruteforce():
                 assert slot_pos[bk.cur[0]] == bk.pos[0]
                 assert bk.pos[0] + bk.pend[0] == total
                 assert 0 <= bk.pend[0] < k
+                assert bk.conv_head[0] == (2 + total) % R
+
+
+def test_bookkeeping_slot_semantics_bruteforce_single_snapshot():
+    """Single-snapshot variant: only h_j is ever written; the live slot must still stand for `pos`."""
+    R = 8
+    for k in (1, 2, 3):
+        for seq in itertools.product(range(k + 1), repeat=5):
+            bk = oracle.BookkeepingModel(1, R, 4, hj_only=True)
+            slot_pos = {0: 0}
+            total = 0
+            for a in seq:
+                cur, pend, pos = bk.cur[0], bk.pend[0], bk.pos[0]
+                bk.verify(k)
+                if pend > 0:
+                    slot_pos[(cur + 1) % 3] = pos + pend          # h_j written, nothing else
+                bk.commit([a])
+                total += a
+                assert slot_pos[bk.cur[0]] == bk.pos[0]
+                assert bk.pos[0] + bk.pend[0] == total and 0 <= bk.pend[0] <= k
                 assert bk.conv_head[0] == (2 + total) % R
 
 

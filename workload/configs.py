@@ -27,6 +27,7 @@ class Workload:
     conv_width: int = 4
     conv_act: str = "none"   # "none" | "silu"
     conv_bias: bool = True
+    snapshot_mode: str = "both"   # "both": h_j and h_k as Algorithm 2 | "hj_only": single-snapshot variant
     kmax: int = 0        # 0 -> k
     layers: int = 1
     seed: int = 0
