@@ -228,13 +228,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         XRaw r;
         r.x = XV::zero();
         r.dt = XV::zero();
-        r.dt1 = 0;
-        if (!q.on) return r;                             // idle lane: no request at all
         const bool old = q.tt < pd;
         const int t = q.tt - pd;
-        if (CONV && !old) {
-            // newest tap = this token's raw input; older taps from earlier inputs of the round or the ring
-            r.x = XV::load(p.x_raw, oX_in + t * HP + q.i);
+        // The one-element dt load is unconditional (an idle lane reads token 0 of the window): under a branch
+        // the compiler moves the decode next to the load and waits there for every load issued so far, the
+        // state included.
+        if constexpr (!DIAG) {
+            const bool w = old || !q.on;
+            r.dt1 = Vec::load_raw1(w ? winDt : p.dt, w ? oDt_win + q.tt * H : oDt_in + t * H);
+        } else {
+            r.dt1 = 0;
+        }
+        if (!q.on) return r;                             // idle lane: no other request
+        // one x load whatever the source (window, conv output, or raw input = newest tap): x_raw and xc share
+        // the [batch][k][channels] layout.  Two exclusive branches with a load each would share registers and
+        // make the second wait for the first.
+        const bool fresh = CONV && !old;
+        r.x = XV::load(fresh ? p.x_raw : (old ? winX : p.xc), (old ? oX_win + q.tt * HP : oX_in + t * HP) + q.i);
+        if (fresh) {
+            // older taps from earlier inputs of the round or the ring
 #pragma unroll
             for (int w = 0; w < W - 1; ++w) {
                 const int j = t - (W - 1) + w;           // position relative to the round's first token
@@ -244,11 +256,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             }
             r.wv = Vec::load_raw(p.wgt, (size_t)(ch0 + q.i) * W);           // XW channels x W taps = 16 bytes
             r.bias = p.bias ? XV::load(p.bias, ch0 + q.i) : XV::zero();
-        } else {
-            r.x = XV::load(old ? winX : p.xc, (old ? oX_win + q.tt * HP : oX_in + t * HP) + q.i);
         }
         if constexpr (DIAG) r.dt = XV::load(old ? winDt : p.dt, (old ? oDt_win + q.tt * H : oDt_in + t * H) + q.i);
-        else r.dt1 = Vec::load_raw1(old ? winDt : p.dt, old ? oDt_win + q.tt * H : oDt_in + t * H);
         return r;
     };
     auto b_use = [&](const BReq &q, uint4 raw) {
@@ -331,7 +340,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const XRaw fX = x_load(qX);
     const XRaw fX2 = x_load(qX2);
     uint32_t fDec = 0;
-    if constexpr (!DIAG) if ((int)tid < T) fDec = dec_load(tid);
+    if constexpr (!DIAG) fDec = dec_load((int)tid < T ? tid : 0);      // unconditional (idle lanes read token 0), like dt above
     __builtin_amdgcn_sched_barrier(0);
     SSMV_TP(2);
     b_use(qB, fB);
