@@ -47,6 +47,11 @@ def parse_args():
     ap.add_argument("--split", action="store_true",
                     help="three launches per step (conv1d_state_update, ssm_verify_multistep, ssm_commit_rollback) instead of "
                          "the fused conv+verify launch and one commit launch per round over all caches")
+    ap.add_argument("--block", action="store_true",
+                    help="the launch as a whole Mamba block's recurrence: dt = softplus(raw + bias) ahead of it, SiLU gate behind it")
+    ap.add_argument("--draft", action="store_true",
+                    help="the draft side: a round is fed by k single-token calls (the first one replays the tokens accepted "
+                         "last round), one commit per round; implies the general entry point")
     return ap.parse_args()
 
 
@@ -61,7 +66,7 @@ def pend_after(accepted_rounds, k_rounds, hj_only=False):
     return out
 
 
-def verify_bytes(wl, pend, k, fused):
+def verify_bytes(wl, pend, k, fused, gate=False, calls=1):
     """Algorithmic HBM bytes of one verify launch: state read once, h_k written, h_j written where
     tokens were pending, token inputs read, y and the stash written, pending tokens re-read; with the
     conv roll fused in: the raw inputs instead of xc, the ring append, 3 history rows, weights and bias."""
@@ -76,16 +81,19 @@ def verify_bytes(wl, pend, k, fused):
         total += k * (Cx + H + GN) * e              # stash out
         total += int(pd) * (Cx + H + GN) * e        # pending tokens in
         if fused:
-            total += (k * Cx + 3 * Cx + 5 * Cx) * e # ring append, ring history, conv weights + bias
+            total += (k * Cx + calls * (3 * Cx + 5 * Cx)) * e   # ring append; per call: ring history, conv weights + bias
+        if gate:
+            total += k * Cx * e                     # z in
+        total += (calls - 1) * 2 * S                # every later call of a round: state in, state out
     return int(total)
 
 
-def round_bytes(wl, pend, k, fused):
+def round_bytes(wl, pend, k, fused, gate=False, calls=1):
     """Whole round.  Split path: the verify launch plus the conv launch (x_raw in, ring append, xc out, 3
     history rows and weights in).  Fused path: the one launch."""
     e = 2 if wl.io == "bf16" else 4
     if fused:
-        return verify_bytes(wl, pend, k, True)
+        return verify_bytes(wl, pend, k, True, gate, calls)
     conv = len(pend) * (k * wl.conv_channels * 3 + 3 * wl.conv_channels + 5 * wl.conv_channels) * e
     return verify_bytes(wl, pend, k, False) + conv
 
@@ -101,7 +109,7 @@ def main():
     import torch
 
     import paper_2408_15237_amd as ssmv
-    from workload import CONFIGS, generate
+    from workload import CONFIGS, block_extras, generate
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
@@ -145,6 +153,24 @@ def main():
     torch.cuda.synchronize()
 
     fused = not (args.split or args.naive)
+    general = args.block or args.draft
+    if general and not fused:
+        print("bench.py: --block/--draft use the fused launch; not with --split/--naive", file=sys.stderr)
+        sys.exit(2)
+    if args.draft and args.single_snapshot:
+        print("bench.py: a round fed by several calls needs the h_k slot; not with --single-snapshot", file=sys.stderr)
+        sys.exit(2)
+    blk = {}
+    if args.block:
+        ex = block_extras(data)
+        blk = dict(dt_bias=torch.from_numpy(ex.dt_bias[0]).to(dev), dt_softplus=True)
+        for r, raw, zz in zip(rounds, ex.dt_raw, ex.z):
+            r["dt"], r["z"] = up(raw[0]), up(zz)
+    if args.draft:
+        for r in rounds:
+            for name in ("x", "dt", "B", "C") + (("z",) if args.block else ()):
+                r[name + "1"] = [r[name][:, t:t + 1].contiguous() for t in range(k)]
+        y1_buf = torch.empty_like(rounds[0]["x1"][0])
     if args.naive:
         ones = torch.ones(wl.batch, dtype=torch.int32, device=dev)
         for r in rounds:
@@ -167,6 +193,18 @@ def main():
                 ssmv.conv1d_state_update(dims, c, r["x1"][t], conv_w, conv_b, 1, x1_buf)
                 ssmv.ssm_verify_multistep(dims, c, x1_buf, r["dt1"][t], r["B1"][t], r["C1"][t], A, D, 1, y1_buf)
                 ssmv.ssm_commit_rollback(dims, c, ones)
+        elif args.draft:
+            for t in range(k):
+                ssmv.ssm_block_multistep(dims, c, x_raw=r["x1"][t], conv_wgt=conv_w, conv_bias=conv_b, dt=r["dt1"][t], Bm=r["B1"][t],
+                                         Cm=r["C1"][t], A=A, D=D, k=1, tok0=t, y_out=y1_buf,
+                                         z=r["z1"][t] if args.block else None, **blk)
+            if i == n_inst - 1:
+                ssmv.ssm_commit_rollback_multi(dims, all_caches, r["acc"])
+        elif general:
+            ssmv.ssm_block_multistep(dims, c, x_raw=r["x"], conv_wgt=conv_w, conv_bias=conv_b, dt=r["dt"], Bm=r["B"], Cm=r["C"],
+                                     A=A, D=D, k=k, y_out=y_buf, z=r["z"], **blk)
+            if i == n_inst - 1:
+                ssmv.ssm_commit_rollback_multi(dims, all_caches, r["acc"])
         elif fused:
             ssmv.ssm_conv_verify_multistep(dims, c, r["x"], conv_w, conv_b, r["dt"], r["B"], r["C"], A, D, k, y_buf)
             if i == n_inst - 1:
@@ -231,7 +269,7 @@ def main():
         # algorithmic bytes of exactly the timed steps
         tot_bytes = 0
         for s in range(W, W + K):
-            tot_bytes += round_bytes(wl, pend_sched[s // n_inst], k, fused)
+            tot_bytes += round_bytes(wl, pend_sched[s // n_inst], k, fused, gate=args.block, calls=k if args.draft else 1)
         tokens = wl.batch * k * K
         result.update(
             value=tokens / (total_ms * 1e-3),
@@ -248,7 +286,13 @@ def main():
     r0 = rounds[0]
 
     def dominant(c):
-        if fused:
+        if args.draft:      # a later call of a round: one token, state read and written in place
+            ssmv.ssm_block_multistep(dims, c, x_raw=r0["x1"][1], conv_wgt=conv_w, conv_bias=conv_b, dt=r0["dt1"][1], Bm=r0["B1"][1],
+                                     Cm=r0["C1"][1], A=A, D=D, k=1, tok0=1, y_out=y1_buf, z=r0["z1"][1] if args.block else None, **blk)
+        elif general:
+            ssmv.ssm_block_multistep(dims, c, x_raw=r0["x"], conv_wgt=conv_w, conv_bias=conv_b, dt=r0["dt"], Bm=r0["B"], Cm=r0["C"],
+                                     A=A, D=D, k=k, y_out=y_buf, z=r0["z"], **blk)
+        elif fused:
             ssmv.ssm_conv_verify_multistep(dims, c, r0["x"], conv_w, conv_b, r0["dt"], r0["B"], r0["C"], A, D, k, y_buf)
         else:
             ssmv.ssm_verify_multistep(dims, c, r0["x"], r0["dt"], r0["B"], r0["C"], A, D, k, y_buf)
@@ -256,7 +300,13 @@ def main():
     for i in range(n_inst):
         dominant(caches[i].c)
     torch.cuda.synchronize()
-    kbytes = sum(verify_bytes(wl, pend_now[i % n_inst], k, fused) for i in range(n_meas))
+    if args.draft:
+        e_io = 2 if wl.io == "bf16" else 4
+        Cx_, H_, GN_ = wl.conv_channels, wl.nheads, wl.ngroups * wl.dstate
+        per_seq = 2 * wl.state_elems * 4 + ((Cx_ + H_ + 2 * GN_) + Cx_ + (Cx_ + H_ + GN_) + Cx_ + 8 * Cx_ + (Cx_ if args.block else 0)) * e_io
+        kbytes = per_seq * wl.batch * n_meas
+    else:
+        kbytes = sum(verify_bytes(wl, pend_now[i % n_inst], k, fused, gate=args.block) for i in range(n_meas))
     side2 = torch.cuda.Stream()
     side2.wait_stream(torch.cuda.current_stream())
     kgraph = torch.cuda.CUDAGraph()
@@ -280,13 +330,15 @@ def main():
     achieved = (kbytes / n_meas) / (avg_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "verify_kernel_%s_pmc.txt" % wl.name)
-    if os.path.exists(tpath):
+    default_path = fused and not general and wl.snapshot_mode == "both" and args.rows == 0 and args.waves == 0
+    if default_path and os.path.exists(tpath):     # the counters were read on the default launch only
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                 "frac": round(achieved / PEAK_HBM_GBPS, 4), "traffic": traffic,
-                "kernel": "verify_kernel (conv roll fused)" if fused else "verify_kernel", "avg_launch_us": round(avg_ms * 1e3, 3),
+                "kernel": ("verify_kernel (conv roll fused, one token appended to the round)" if args.draft else
+                           "verify_kernel (conv roll fused)" if fused else "verify_kernel"), "avg_launch_us": round(avg_ms * 1e3, 3),
                 "median_launch_us": round(durs[len(durs) // 2] * 1e3, 3),
                 "algorithmic_bytes_per_launch": kbytes // n_meas, "launches_timed": n_meas * len(durs)}
 
@@ -351,7 +403,9 @@ def main():
                    "batch": wl.batch, "k": k, "rounds": n_rounds, "instances": n_inst,
                    "launch": "hip-graph" if not args.no_graph else "eager",
                    "snapshots": "h_j only (single-snapshot variant)" if wl.snapshot_mode == "hj_only" else "h_j and h_k (Algorithm 2)",
-                   "path": "fused conv+verify launch per layer, one commit launch per round over all caches" if fused
+                   "path": ("draft side: k single-token calls per layer-round (first one replays), one commit launch per round" if args.draft else
+                            "fused conv+verify launch per layer, one commit launch per round over all caches") +
+                           (", softplus(dt+bias) and SiLU gate fused" if args.block else "") if fused
                            else ("naive: snapshot copy + k single-token (conv, verify, commit) rounds per layer" if args.naive
                                  else "conv, verify and commit launches per layer")},
         "hbm_gbps_whole_step": round(result["step_hbm_gbps"], 1),

@@ -156,6 +156,43 @@ int ssm_conv_verify_multistep(const ssmv_dims *dims, const ssmv_cache *cache, co
                               const void *Cm, const float *A, const float *D, int32_t k,
                               void *y_out, void *hip_stream);
 
+/* The general form of the two calls above, with the optional pieces that make the launch a whole
+ * Mamba block's recurrence and that let a round be fed by several calls:
+ *   - dt <- softplus(dt + dt_bias) ahead of the discretisation (Section 2.2 takes the positive step
+ *     size as given; a Mamba block obtains it this way).  dt_bias [H] (diag mode: per channel) fp32 device
+ *     or NULL (= 0); dt_softplus 0/1.  The window keeps the raw dt and replay transforms it again, so
+ *     both must be the same on every call on one cache, ssmv_materialize_block included;
+ *   - y <- y * z * sigmoid(z), the block's SiLU gate, in fp32 ahead of the rounding of y.
+ *     z [batch][k][H*P] io_dtype device, or NULL for no gate;
+ *   - tok0 > 0: the draft side (Section 4.3: a draft model that is itself an SSM produces one token
+ *     per call, and its first call of a round recomputes the tokens accepted last round).  The first
+ *     call of a round has tok0 = 0 and is a verify as above; a later call, with tok0 = the number
+ *     of tokens the round has been fed so far, continues from the state in the h_k slot, updates that
+ *     slot in place, replays nothing, appends its k tokens to the round's window and conv ring, and sets
+ *     last_k[b] = tok0 + k.  After the calls the slots, the window and the ring hold exactly what one
+ *     call with all tok0+k tokens would have left, so ssm_commit_rollback applies unchanged.
+ *     tok0 + k <= kmax; not with SSMV_SNAP_HJ_ONLY (SSMV_EUNSUPPORTED); a later call is NOT idempotent.
+ * Exactly one of x_raw (conv fused; needs conv_wgt) and xc is non-NULL.  Other arguments as above. */
+typedef struct ssmv_step_args {
+    const void *x_raw;      /* [batch][k][Cx] io_dtype, or NULL */
+    const void *xc;         /* [batch][k][H*P] io_dtype, or NULL */
+    const void *conv_wgt;   /* [Cx][W] io_dtype (with x_raw) */
+    const void *conv_bias;  /* [Cx] io_dtype or NULL */
+    const void *dt;         /* [batch][k][H] io_dtype */
+    const float *dt_bias;   /* [H] fp32 or NULL */
+    const void *Bm;         /* [batch][k][G][N] io_dtype */
+    const void *Cm;         /* [batch][k][G][N] io_dtype */
+    const void *z;          /* [batch][k][H*P] io_dtype or NULL */
+    const float *A;         /* [H] or [H][N] fp32 */
+    const float *D;         /* [H] fp32 */
+    void *y_out;            /* [batch][k][H*P] io_dtype */
+    int32_t k;
+    int32_t tok0;
+    int32_t dt_softplus;
+} ssmv_step_args;
+int ssm_block_multistep(const ssmv_dims *dims, const ssmv_cache *cache, const ssmv_step_args *args,
+                        void *hip_stream);
+
 /* Algorithm 2, "return h_k if k' = k else h_j", as integer bookkeeping.  Per
  * sequence with a = accepted[b] (device int32 [batch]; values outside
  * [0,last_k] are clamped and set err_flag):
@@ -180,6 +217,9 @@ int ssm_commit_rollback_multi(const ssmv_dims *dims, const ssmv_cache *caches, i
  * for handing the state to another engine. */
 int ssmv_materialize(const ssmv_dims *dims, const ssmv_cache *cache, const float *A, float *h_out,
                      void *hip_stream);
+/* The same for a cache that is driven with a dt transform (see ssm_block_multistep). */
+int ssmv_materialize_block(const ssmv_dims *dims, const ssmv_cache *cache, const float *A,
+                           const float *dt_bias, int32_t dt_softplus, float *h_out, void *hip_stream);
 
 /* FirstConflict of Algorithm 2: accepted[b] = length of the longest prefix on
  * which draft[b][.] and target[b][.] agree.  draft, target [batch][k] and

@@ -104,6 +104,27 @@ def scan_tokens(a_mode: str, h_in, x, dt, Bm, Cm, A, D):
     return y, snap
 
 
+def softplus(x) -> np.ndarray:
+    """log(1 + exp(x)), the map from a raw step-size projection to the positive step dt of Section 2.2
+    (evaluated as max(x,0) + log1p(exp(-|x|)) so that no exponential overflows)."""
+    x = _c(x)
+    return np.maximum(x, 0.0) + np.log1p(np.exp(-np.abs(x)))
+
+
+def step_size(dt_raw, dt_bias=None, use_softplus: bool = False) -> np.ndarray:
+    """dt = softplus(dt_raw + dt_bias) (bias broadcast over the last axis); identity pieces when not asked for."""
+    dt = _c(dt_raw)
+    if dt_bias is not None:
+        dt = dt + _c(dt_bias)
+    return softplus(dt) if use_softplus else dt
+
+
+def silu_gate(y, z) -> np.ndarray:
+    """y * z * sigmoid(z): the output gate of a Mamba block."""
+    y, z = _c(y), _c(z)
+    return y * z / (1.0 + np.exp(-z))
+
+
 def first_conflict(draft, target) -> np.ndarray:
     """Length of the longest prefix on which draft and target agree (Algorithm 2, FirstConflict)."""
     draft = np.asarray(draft)
@@ -121,8 +142,10 @@ class EagerOracle:
     """O1: the plain definition.  No slots, no laziness, unbounded conv history."""
 
     def __init__(self, a_mode: str, A, D, conv_w, conv_b, h0, io: str, act: str = "none",
-                 ngroups: int = 1, conv_init=None):
+                 ngroups: int = 1, conv_init=None, dt_bias=None, dt_softplus: bool = False):
         self.a_mode, self.io, self.act, self.G = a_mode, io, act, ngroups
+        self.dt_bias = None if dt_bias is None else _c(dt_bias)
+        self.dt_softplus = dt_softplus
         self.A, self.D = _c(A), _c(D)
         self.conv_w = _c(conv_w)
         self.conv_b = None if conv_b is None else _c(conv_b)
@@ -136,14 +159,17 @@ class EagerOracle:
         self.j = np.zeros(self.batch, dtype=np.int64)
         self._last = None
 
-    def verify(self, x_raw, dt, Bm, Cm):
-        """Returns (y, xc, h_snap); h_snap[t] is the state after t of the new tokens."""
+    def verify(self, x_raw, dt, Bm, Cm, z=None):
+        """Returns (y, xc, h_snap); h_snap[t] is the state after t of the new tokens.  With z, y is gated."""
         x_raw = _c(x_raw)
+        dt = step_size(dt, self.dt_bias, self.dt_softplus)
         W = self.W
         raw = np.stack([np.concatenate([self.hist[b][-(W - 1):], x_raw[b]], axis=0)
                         for b in range(self.batch)])
         xc = conv_causal(raw, self.conv_w, self.conv_b, self.act, self.io)
         y, snap = scan_tokens(self.a_mode, self.h, xc, dt, Bm, Cm, self.A, self.D)
+        if z is not None:
+            y = silu_gate(y, z)
         self._last = (x_raw, snap)
         return y, xc, snap
 
@@ -184,8 +210,9 @@ class BookkeepingModel:
         self.win_par = 0
         self.err = 0
 
-    def verify(self, k: int) -> None:
-        self.last_k = [k] * self.batch
+    def verify(self, k: int, tok0: int = 0) -> None:
+        """tok0 > 0: a later call of a round that several calls feed (draft side); the round then holds tok0+k tokens."""
+        self.last_k = [tok0 + k] * self.batch
 
     def commit(self, accepted) -> None:
         if self.last_k[0] == 0:

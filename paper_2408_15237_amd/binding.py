@@ -31,9 +31,15 @@ SNAP_CODES = {"both": SSMV_SNAP_BOTH, "hj_only": SSMV_SNAP_HJ_ONLY}
 
 EXPORTS = [
     "ssmv_cache_sizes", "ssmv_cache_reset", "conv1d_state_update", "ssm_verify_multistep",
-    "ssm_conv_verify_multistep", "ssm_commit_rollback", "ssm_commit_rollback_multi", "ssmv_materialize", "ssmv_first_conflict", "ssmv_check",
+    "ssm_conv_verify_multistep", "ssm_block_multistep", "ssmv_materialize_block", "ssm_commit_rollback", "ssm_commit_rollback_multi", "ssmv_materialize", "ssmv_first_conflict", "ssmv_check",
     "ssmv_set_tuning", "ssmv_copy_probe", "ssmv_last_error", "ssmv_version",
 ]
+
+
+class ssmv_step_args(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in (
+        "x_raw", "xc", "conv_wgt", "conv_bias", "dt", "dt_bias", "Bm", "Cm", "z", "A", "D", "y_out")] + [
+        (n, ctypes.c_int32) for n in ("k", "tok0", "dt_softplus")]
 
 
 class SsmvError(RuntimeError):
@@ -89,6 +95,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.ssm_commit_rollback.argtypes = [dp, cp, vp, vp]
     lib.ssm_commit_rollback_multi.argtypes = [dp, cp, i32, vp, vp]
     lib.ssmv_materialize.argtypes = [dp, cp, vp, vp, vp]
+    lib.ssm_block_multistep.argtypes = [dp, cp, ctypes.POINTER(ssmv_step_args), vp]
+    lib.ssmv_materialize_block.argtypes = [dp, cp, vp, vp, i32, vp, vp]
     lib.ssmv_first_conflict.argtypes = [vp, vp, i32, i32, vp, vp]
     lib.ssmv_check.argtypes = [cp, vp]
     lib.ssmv_set_tuning.argtypes = [i32, i32]
@@ -162,6 +170,18 @@ def ssm_verify_multistep(dims, cache, xc, dt, Bm, Cm, A, D, k: int, y_out, strea
 def ssm_conv_verify_multistep(dims, cache, x_raw, wgt, bias, dt, Bm, Cm, A, D, k: int, y_out, stream=None) -> None:
     _ck(load_library().ssm_conv_verify_multistep(ctypes.byref(dims), ctypes.byref(cache), _ptr(x_raw), _ptr(wgt), _ptr(bias),
                                                  _ptr(dt), _ptr(Bm), _ptr(Cm), _ptr(A), _ptr(D), k, _ptr(y_out), _stream(stream)))
+
+
+def ssm_block_multistep(dims, cache, *, dt, Bm, Cm, A, D, k: int, y_out, x_raw=None, xc=None, conv_wgt=None, conv_bias=None,
+                        dt_bias=None, dt_softplus: bool = False, z=None, tok0: int = 0, stream=None) -> None:
+    a = ssmv_step_args(_ptr(x_raw), _ptr(xc), _ptr(conv_wgt), _ptr(conv_bias), _ptr(dt), _ptr(dt_bias), _ptr(Bm), _ptr(Cm),
+                       _ptr(z), _ptr(A), _ptr(D), _ptr(y_out), k, tok0, int(dt_softplus))
+    _ck(load_library().ssm_block_multistep(ctypes.byref(dims), ctypes.byref(cache), ctypes.byref(a), _stream(stream)))
+
+
+def ssmv_materialize_block(dims, cache, A, dt_bias, dt_softplus: bool, h_out, stream=None) -> None:
+    _ck(load_library().ssmv_materialize_block(ctypes.byref(dims), ctypes.byref(cache), _ptr(A), _ptr(dt_bias), int(dt_softplus),
+                                              _ptr(h_out), _stream(stream)))
 
 
 def ssm_commit_rollback_multi(dims, caches, accepted, stream=None) -> None:

@@ -101,7 +101,7 @@ int check_k(const ssmv_dims *d, int k)
 }
 
 // rows per lane and waves per workgroup for the verify kernel
-int choose_shape(const ssmv_dims *d, int lds_tokens, int k, VerifyShape *out, int *rows_wg, int *tiles)
+int choose_shape(const ssmv_dims *d, int lds_tokens, int k, bool gated, VerifyShape *out, int *rows_wg, int *tiles)
 {
     const bool diag = d->a_mode == SSMV_A_DIAG;
     const int N = d->dstate;
@@ -114,6 +114,7 @@ int choose_shape(const ssmv_dims *d, int lds_tokens, int k, VerifyShape *out, in
     auto fits = [&](int r, int w) {
         VerifyParams q{};
         q.lds_tokens = lds_tokens; q.k = k; q.N = N; q.rows_wg = w * rpi * r;
+        q.z = gated ? static_cast<const void *>(&q) : nullptr;      // only tested against null: LDS for the gate factors
         return verify_lds_bytes(q, diag) <= 64 * 1024;
     };
     if (autoR || autoW) {
@@ -244,37 +245,50 @@ int conv1d_state_update(const ssmv_dims *d, const ssmv_cache *c, const void *x_r
     return hc == 0 ? SSMV_OK : hip_fail(hc, "conv1d_state_update");
 }
 
-static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const void *xc, const void *x_raw, const void *wgt,
-                         const void *bias, const void *dt, const void *Bm, const void *Cm, const float *A, const float *D,
-                         int32_t k, void *y_out, void *hip_stream, const char *what)
+static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const ssmv_step_args *a, void *hip_stream, const char *what)
 {
     int rc;
     if ((rc = check_dims(d)) != SSMV_OK) return rc;
     if ((rc = check_cache(c)) != SSMV_OK) return rc;
+    if (!a) return fail(SSMV_EINVAL, "args is NULL");
+    const int k = a->k;
     if ((rc = check_k(d, k)) != SSMV_OK) return rc;
-    if (x_raw) {
-        if ((rc = check_ptr(x_raw, "x_raw")) != SSMV_OK) return rc;
-        if ((rc = check_ptr(wgt, "wgt")) != SSMV_OK) return rc;
-        if (bias && !aligned16(bias)) return fail(SSMV_EALIGN, "bias is not 16-byte aligned");
+    if (a->tok0 < 0 || a->tok0 + k > d->kmax) return fail(SSMV_EINVAL, "tok0 %d + k %d outside [0, kmax=%d]", a->tok0, k, d->kmax);
+    if (a->tok0 > 0 && d->snapshot_mode == SSMV_SNAP_HJ_ONLY)
+        return fail(SSMV_EUNSUPPORTED, "a round fed by several calls needs the h_k slot (not with SSMV_SNAP_HJ_ONLY)");
+    if (a->dt_softplus != 0 && a->dt_softplus != 1) return fail(SSMV_EINVAL, "dt_softplus %d not in {0,1}", a->dt_softplus);
+    if ((a->x_raw != nullptr) == (a->xc != nullptr)) return fail(SSMV_EINVAL, "exactly one of x_raw and xc must be given");
+    if (a->x_raw) {
+        if ((rc = check_ptr(a->x_raw, "x_raw")) != SSMV_OK) return rc;
+        if ((rc = check_ptr(a->conv_wgt, "wgt")) != SSMV_OK) return rc;
+        if (a->conv_bias && !aligned16(a->conv_bias)) return fail(SSMV_EALIGN, "bias is not 16-byte aligned");
     } else {
-        if ((rc = check_ptr(xc, "xc")) != SSMV_OK) return rc;
+        if ((rc = check_ptr(a->xc, "xc")) != SSMV_OK) return rc;
     }
-    if ((rc = check_ptr(dt, "dt")) != SSMV_OK) return rc;
-    if ((rc = check_ptr(Bm, "Bm")) != SSMV_OK) return rc;
-    if ((rc = check_ptr(Cm, "Cm")) != SSMV_OK) return rc;
-    if ((rc = check_ptr(A, "A")) != SSMV_OK) return rc;
-    if ((rc = check_ptr(D, "D")) != SSMV_OK) return rc;
-    if ((rc = check_ptr(y_out, "y_out")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(a->dt, "dt")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(a->Bm, "Bm")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(a->Cm, "Cm")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(a->A, "A")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(a->D, "D")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(a->y_out, "y_out")) != SSMV_OK) return rc;
+    if (a->z && !aligned16(a->z)) return fail(SSMV_EALIGN, "z is not 16-byte aligned");
+    if (a->dt_bias && ((uintptr_t)a->dt_bias & 3)) return fail(SSMV_EALIGN, "dt_bias is not 4-byte aligned");
     VerifyParams p{};
     fill_verify(p, d, c);
     p.k = k;
+    p.tok0 = a->tok0;
+    p.pend_mask = a->tok0 > 0 ? 0 : ~0;
+    p.src_add = a->tok0 > 0 ? 2 : 0;
+    p.dt_softplus = a->dt_softplus;
+    p.dt_bias = a->dt_bias;
+    p.z = a->z;
     p.pend_max = d->snapshot_mode == SSMV_SNAP_HJ_ONLY ? d->kmax : d->kmax - 1;
     p.write_hk = d->snapshot_mode != SSMV_SNAP_HJ_ONLY;
-    p.lds_tokens = p.pend_max + k;
-    p.xc = xc; p.dt = dt; p.Bm = Bm; p.Cm = Cm; p.A = A; p.D = D; p.y = y_out; p.h_out = nullptr;
-    p.x_raw = x_raw; p.wgt = wgt; p.bias = bias;
+    p.lds_tokens = (a->tok0 > 0 ? 0 : p.pend_max) + k;
+    p.xc = a->xc; p.dt = a->dt; p.Bm = a->Bm; p.Cm = a->Cm; p.A = a->A; p.D = a->D; p.y = a->y_out; p.h_out = nullptr;
+    p.x_raw = a->x_raw; p.wgt = a->conv_wgt; p.bias = a->conv_bias;
     VerifyShape shape;
-    if ((rc = choose_shape(d, p.lds_tokens, k, &shape, &p.rows_wg, &p.tiles)) != SSMV_OK) return rc;
+    if ((rc = choose_shape(d, p.lds_tokens, k, p.z != nullptr, &shape, &p.rows_wg, &p.tiles)) != SSMV_OK) return rc;
     p.log2_rows_wg = ilog2_host(p.rows_wg);
     const int hc = d->a_mode == SSMV_A_DIAG ? launch_verify_diag(p, shape, (hipStream_t)hip_stream)
                                              : launch_verify_scalar(p, shape, (hipStream_t)hip_stream);
@@ -284,7 +298,10 @@ static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const void *xc
 int ssm_verify_multistep(const ssmv_dims *d, const ssmv_cache *c, const void *xc, const void *dt, const void *Bm,
                          const void *Cm, const float *A, const float *D, int32_t k, void *y_out, void *hip_stream)
 {
-    return verify_common(d, c, xc, nullptr, nullptr, nullptr, dt, Bm, Cm, A, D, k, y_out, hip_stream, "ssm_verify_multistep");
+    if (!xc) return fail(SSMV_EINVAL, "xc is NULL");
+    ssmv_step_args a{};
+    a.xc = xc; a.dt = dt; a.Bm = Bm; a.Cm = Cm; a.A = A; a.D = D; a.k = k; a.y_out = y_out;
+    return verify_common(d, c, &a, hip_stream, "ssm_verify_multistep");
 }
 
 int ssm_conv_verify_multistep(const ssmv_dims *d, const ssmv_cache *c, const void *x_raw, const void *wgt, const void *bias,
@@ -292,30 +309,47 @@ int ssm_conv_verify_multistep(const ssmv_dims *d, const ssmv_cache *c, const voi
                               void *y_out, void *hip_stream)
 {
     if (!x_raw) return fail(SSMV_EINVAL, "x_raw is NULL");
-    return verify_common(d, c, nullptr, x_raw, wgt, bias, dt, Bm, Cm, A, D, k, y_out, hip_stream, "ssm_conv_verify_multistep");
+    ssmv_step_args a{};
+    a.x_raw = x_raw; a.conv_wgt = wgt; a.conv_bias = bias; a.dt = dt; a.Bm = Bm; a.Cm = Cm; a.A = A; a.D = D; a.k = k; a.y_out = y_out;
+    return verify_common(d, c, &a, hip_stream, "ssm_conv_verify_multistep");
 }
 
-int ssmv_materialize(const ssmv_dims *d, const ssmv_cache *c, const float *A, float *h_out, void *hip_stream)
+int ssm_block_multistep(const ssmv_dims *d, const ssmv_cache *c, const ssmv_step_args *args, void *hip_stream)
+{
+    return verify_common(d, c, args, hip_stream, "ssm_block_multistep");
+}
+
+int ssmv_materialize_block(const ssmv_dims *d, const ssmv_cache *c, const float *A, const float *dt_bias, int32_t dt_softplus,
+                           float *h_out, void *hip_stream)
 {
     int rc;
     if ((rc = check_dims(d)) != SSMV_OK) return rc;
     if ((rc = check_cache(c)) != SSMV_OK) return rc;
     if ((rc = check_ptr(A, "A")) != SSMV_OK) return rc;
     if ((rc = check_ptr(h_out, "h_out")) != SSMV_OK) return rc;
+    if (dt_softplus != 0 && dt_softplus != 1) return fail(SSMV_EINVAL, "dt_softplus %d not in {0,1}", dt_softplus);
     VerifyParams p{};
     fill_verify(p, d, c);
     p.k = 0;
+    p.pend_mask = ~0;
+    p.dt_softplus = dt_softplus;
+    p.dt_bias = dt_bias;
     p.pend_max = d->snapshot_mode == SSMV_SNAP_HJ_ONLY ? d->kmax : d->kmax - 1;
     p.write_hk = 0;
     p.lds_tokens = p.pend_max > 0 ? p.pend_max : 1;
     p.A = A; p.D = A;   // D is not read when k == 0
     p.h_out = h_out;
     VerifyShape shape;
-    if ((rc = choose_shape(d, p.lds_tokens, 0, &shape, &p.rows_wg, &p.tiles)) != SSMV_OK) return rc;
+    if ((rc = choose_shape(d, p.lds_tokens, 0, false, &shape, &p.rows_wg, &p.tiles)) != SSMV_OK) return rc;
     p.log2_rows_wg = ilog2_host(p.rows_wg);
     const int hc = d->a_mode == SSMV_A_DIAG ? launch_verify_diag(p, shape, (hipStream_t)hip_stream)
                                              : launch_verify_scalar(p, shape, (hipStream_t)hip_stream);
     return hc == 0 ? SSMV_OK : hip_fail(hc, "ssmv_materialize");
+}
+
+int ssmv_materialize(const ssmv_dims *d, const ssmv_cache *c, const float *A, float *h_out, void *hip_stream)
+{
+    return ssmv_materialize_block(d, c, A, nullptr, 0, h_out, hip_stream);
 }
 
 int ssm_commit_rollback_multi(const ssmv_dims *d, const ssmv_cache *caches, int32_t n_caches, const int32_t *accepted,

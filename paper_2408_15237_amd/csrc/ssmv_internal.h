@@ -20,6 +20,12 @@ struct VerifyParams {
     int lds_tokens;      // tokens the dynamic LDS was sized for (pend_max + k)
     int pend_max;        // largest legal pend: kmax-1, or kmax when h_k is never stored
     int write_hk;        // 0: SSMV_SNAP_HJ_ONLY
+    int tok0;            // tokens earlier calls have already fed to this round (0: first call)
+    int pend_mask;       // tok0 > 0 ? 0 : ~0  (a later call replays nothing)
+    int src_add;         // tok0 > 0 ? 2 : 0   (a later call continues in the h_k slot)
+    int dt_softplus;     // 1: dt <- softplus(dt + dt_bias) before use
+    const float *dt_bias;  // [nheads] or null
+    const void *z;       // gate input [batch][k][channels] or null
     int log2_rows_wg;    // rows_wg is a power of two
     // fused conv roll (x_raw != nullptr): ring append + width-4 conv computed while staging
     int ring_len, conv_act;

@@ -55,20 +55,25 @@ __host__ __device__ constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v
 // LDS plan (floats).  T = lds_tokens.
 //   sB   [T][N]        B of every token (pending first, then drafts)
 //   sC   [k][N]        C of the drafts
-//   sDec [T]           scalar mode: exp(dt*A) per token
+//   sDec [T]           scalar mode: exp(dt*A) per token, then dt [T] behind it
 //   sDt  [T][rows_wg]  diag mode: dt per (token,row)
-//   sDtx [T][rows_wg]  dt*x per (token,row)
+//   sDtx [T][rows_wg]  diag mode: dt*x per (token,row); scalar mode: x (dt is one number per token and is
+//                      folded into B in the step instead, so the x items never wait for or touch dt)
 //   sY   [k][rows_wg]  D*x per (draft,row), turned into y in place
+//   sG   [k][rows_wg]  with a gate: z*sigmoid(z) per (draft,row)
 template <bool DIAG>
-__host__ __device__ inline size_t verify_lds_floats(int T, int k, int N, int rows_wg)
+__host__ __device__ inline size_t verify_lds_floats(int T, int k, int N, int rows_wg, bool gated)
 {
     size_t n = (size_t)T * N + (size_t)k * N + (size_t)T * rows_wg + (size_t)k * rows_wg;
-    n += DIAG ? (size_t)T * rows_wg : (size_t)((T + 3) & ~3);
+    n += DIAG ? (size_t)T * rows_wg : 2 * (size_t)((T + 3) & ~3);
+    if (gated) n += (size_t)k * rows_wg;
     return n;
 }
 
 // At least 4 waves per SIMD (<= 128 VGPRs): a second generation of workgroups costs far more than a few moves.
-template <int N, int R, bool DIAG, int IO, bool CONV>
+// EXTRA: the optional pieces (step-size transform, gate, rounds fed by several calls) are compiled in; the plain
+// verification launch carries none of their instructions.
+template <int N, int R, bool DIAG, int IO, bool CONV, bool EXTRA>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void verify_kernel(const VerifyParams p)
 {
     constexpr int LPR = lanes_per_row(N);
@@ -112,8 +117,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const size_t grow = (DIAG ? (size_t)b * p.H : ((size_t)b * p.H + hd) * p.P) + row0;   // its global row
 
     // bookkeeping written by the commit kernel; clamped so that a corrupted cache cannot index out of bounds
+    // tok0 > 0: a later call of a round that was begun by an earlier call (draft side, Section 4.3: the draft
+    // model produces its tokens one call at a time).  It continues from the state the earlier call left in the
+    // h_k slot, updates that slot in place (each workgroup has read its rows before it writes them), replays
+    // nothing, and appends its tokens to the round's stash and conv ring behind the tok0 earlier ones.
+    const int t0 = EXTRA ? p.tok0 : 0;
     const int cur = (int)((unsigned)p.cur_slot[b] % 3u);
-    const int pd = min(max(p.pend[b], 0), p.pend_max);
+    // branch-free on purpose (pend_mask = 0 and src_add = 2 for a later call, else ~0 and 0): a select here becomes a
+    // branch around the load of pend[b], and that serialises two scalar-load round trips ahead of the state loads
+    const int pd = min(max(p.pend[b], 0), p.pend_max) & (EXTRA ? p.pend_mask : ~0);
+    const int src_slot = EXTRA ? (cur + p.src_add) % 3 : cur;
     const int par = p.win_par[0] & 1;
     const int T = pd + k;
     SSMV_TP(1);
@@ -125,7 +138,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     unsigned loff[R];                                   // element offset of the lane's first strip of that row
     bool rvalid[R];
     {
-        const float *src = p.state + (size_t)cur * p.slot_stride + (grow << LOG2N);
+        const float *src = p.state + (size_t)src_slot * p.slot_stride + (grow << LOG2N);
         const float *srcA = p.A + ((size_t)row0 << LOG2N);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -148,8 +161,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     float *sB = lds;
     float *sC = sB + TL * N;
     float *sDec = sC + k * N;                                          // scalar: [T]; diag: sDt [T][rows_wg]
-    float *sDtx = sDec + (DIAG ? TL * rows_wg : ((TL + 3) & ~3));
+    float *sDtF = sDec + ((TL + 3) & ~3);                              // scalar: dt [T]
+    float *sDtx = sDec + (DIAG ? TL * rows_wg : 2 * ((TL + 3) & ~3));
     float *sY = sDtx + TL * rows_wg;
+    float *sG = sY + k * rows_wg;                                      // only with a gate
 
     // ---- token staging: uniform bases (element units of the I/O type), 32-bit offsets -----------------
     const int H = p.H, HP = p.H * p.P, GN = p.G * N;
@@ -176,6 +191,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const size_t oB_win = tok_win * GN + (size_t)g * N, oB_in = tok_in * GN + (size_t)g * N;
     const size_t oX_win = tok_win * HP + ch0, oX_in = tok_in * HP + ch0;
     const size_t oDt_win = tok_win * H + dth0, oDt_in = tok_in * H + dth0;
+    const size_t oB_wout = oB_win + (size_t)t0 * GN, oX_wout = oX_win + (size_t)t0 * HP, oDt_wout = oDt_win + (size_t)t0 * H;
+    // optional softplus(dt + dt_bias) ahead of the discretisation (Section 2.2: dt is the positive step)
+    const float dtb_h = (EXTRA && !DIAG && p.dt_bias) ? p.dt_bias[hd] : 0.f;
+    // softplus and SiLU on the hardware exp2/log2/rcp (about 1 ulp each); log(1+t) by its series where 1+t would
+    // lose the low bits of t
+    auto dt_fix = [&](float d, float bias) {
+        if constexpr (EXTRA) {
+            d += bias;
+            if (p.dt_softplus && d <= 20.f) {
+                const float t = __builtin_amdgcn_exp2f(d * LOG2E);
+                const float series = t * (1.f - t * (0.5f - t * (0.33333334f - t * (0.25f - t * 0.2f))));
+                d = t < 0.0625f ? series : __builtin_amdgcn_logf(1.f + t) * 0.6931471805599453f;
+            }
+        }
+        return d;
+    };
+    const bool gated = EXTRA && p.z != nullptr;
+    auto silu = [&](float zv) { return zv * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-zv * LOG2E)); };
+    auto dt_bias_of = [&](int row) { return (EXTRA && p.dt_bias) ? p.dt_bias[row] : 0.f; };   // diag mode: per channel
     const float D_h = DIAG ? 0.f : p.D[hd];
     const float A_h = DIAG ? 0.f : p.A[hd];
     // x (and dt) items: XW adjacent rows of one token.  Without the conv a 16-byte vector; with it only 4 bytes
@@ -188,7 +222,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const int log2VR = p.log2_rows_wg - ilog2(XW);       // rows_wg is a power of two
     const int nXv = vec_rows ? (T << log2VR) : 0;        // x items to stage
     int conv_head = 0;
-    if constexpr (CONV) conv_head = p.conv_head[b] & (p.ring_len - 1);
+    if constexpr (CONV) conv_head = (p.conv_head[b] + t0) & (p.ring_len - 1);   // newest raw input fed so far
 
     struct BReq { int tt, n; bool on; };
     struct XReq { int tt, i; bool on, inb; };
@@ -223,23 +257,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         if (q.on) r = Vec::load_raw(p.Cm, oB_in + q.tt * GN + q.n);
         return r;
     };
-    struct XRaw { XRawT x, dt, bias; uint32_t dt1; XRawT tap[CONV ? W - 1 : 1]; uint4 wv; };
+    // (scalar mode: the x items carry no dt - it is one number per token, handled by dec_load/dec_use below)
+    struct XRaw { XRawT x, dt, bias, z; XRawT tap[CONV ? W - 1 : 1]; uint4 wv; };
     auto x_load = [&](const XReq &q) {
         XRaw r;
         r.x = XV::zero();
         r.dt = XV::zero();
         const bool old = q.tt < pd;
         const int t = q.tt - pd;
-        // The one-element dt load is unconditional (an idle lane reads token 0 of the window): under a branch
-        // the compiler moves the decode next to the load and waits there for every load issued so far, the
-        // state included.
-        if constexpr (!DIAG) {
-            const bool w = old || !q.on;
-            r.dt1 = Vec::load_raw1(w ? winDt : p.dt, w ? oDt_win + q.tt * H : oDt_in + t * H);
-        } else {
-            r.dt1 = 0;
-        }
-        if (!q.on) return r;                             // idle lane: no other request
+        if (!q.on) return r;                             // idle lane: no request at all
         // one x load whatever the source (window, conv output, or raw input = newest tap): x_raw and xc share
         // the [batch][k][channels] layout.  Two exclusive branches with a load each would share registers and
         // make the second wait for the first.
@@ -258,11 +284,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             r.bias = p.bias ? XV::load(p.bias, ch0 + q.i) : XV::zero();
         }
         if constexpr (DIAG) r.dt = XV::load(old ? winDt : p.dt, (old ? oDt_win + q.tt * H : oDt_in + t * H) + q.i);
+        if (gated && !old) r.z = XV::load(p.z, oX_in + t * HP + q.i);
         return r;
     };
     auto b_use = [&](const BReq &q, uint4 raw) {
         if (!q.on) return;
-        if (q.tt >= pd && writes_B) Vec::store_raw(winB_out, oB_win + (q.tt - pd) * GN + q.n, raw);
+        if (q.tt >= pd && writes_B) Vec::store_raw(winB_out, oB_wout + (q.tt - pd) * GN + q.n, raw);
         float v[EV];
         Vec::decode(raw, v);
 #pragma unroll
@@ -304,16 +331,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         }
         if constexpr (DIAG) {
             XV::decode(r.dt, dtv);
-        } else {
-            const float d = Vec::decode1(r.dt1);
 #pragma unroll
-            for (int e = 0; e < XW; ++e) dtv[e] = d;
+            for (int e = 0; e < XW; ++e) dtv[e] = dt_fix(dtv[e], dt_bias_of(row0 + q.i + e));
+        } else {
+#pragma unroll
+            for (int e = 0; e < XW; ++e) dtv[e] = 1.f;   // the step scales B by dt instead
+        }
+        if (gated && t >= 0) {
+            float zv[XW];
+            XV::decode(r.z, zv);
+#pragma unroll
+            for (int e = 0; e < XW; ++e) sG[t * rows_wg + q.i + e] = silu(zv[e]);
         }
 #pragma unroll
         for (int e = 0; e < XW; ++e) Dv[e] = DIAG ? p.D[row0 + q.i + e] : D_h;
         if (t >= 0 && !materialize) {
-            XV::store(winX_out, oX_win + t * HP + q.i, xbits);
-            if (DIAG) XV::store(winDt_out, oDt_win + t * H + q.i, r.dt);
+            XV::store(winX_out, oX_wout + t * HP + q.i, xbits);
+            if (DIAG) XV::store(winDt_out, oDt_wout + t * H + q.i, r.dt);      // the raw dt: replay applies dt_fix again
         }
 #pragma unroll
         for (int e = 0; e < XW; ++e) {
@@ -327,8 +361,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         return Vec::load_raw1(old ? winDt : p.dt, old ? oDt_win + tt * H : oDt_in + (tt - pd) * H);
     };
     auto dec_use = [&](int tt, uint32_t raw) {
-        if (tt >= pd && first_tile && !materialize) Vec::store_raw1(winDt_out, oDt_win + (tt - pd) * H, raw);
-        sDec[tt] = expf(Vec::decode1(raw) * A_h);
+        if (tt >= pd && first_tile && !materialize) Vec::store_raw1(winDt_out, oDt_wout + (tt - pd) * H, raw);
+        const float d = dt_fix(Vec::decode1(raw), dtb_h);
+        sDec[tt] = expf(d * A_h);
+        sDtF[tt] = d;
     };
 
     // first pass: every thread issues its B, C, x (and dt) loads, then consumes them
@@ -339,6 +375,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const uint4 fC = c_load(qC);
     const XRaw fX = x_load(qX);
     const XRaw fX2 = x_load(qX2);
+    const bool vec_y = (rows_dom % EV) == 0 && (rows_wg % EV) == 0 && (DIAG || (p.P % EV) == 0);
+    const int log2VY = p.log2_rows_wg - ilog2(EV);
     uint32_t fDec = 0;
     if constexpr (!DIAG) fDec = dec_load((int)tid < T ? tid : 0);      // unconditional (idle lanes read token 0), like dt above
     __builtin_amdgcn_sched_barrier(0);
@@ -394,18 +432,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
                     }
                     dtv = load_io(p.dt, oDt_in + t * H + dti, IO);
                     if (!materialize) {
-                        store_io(winX_out, oX_win + t * HP + i, xv, IO);
-                        if (DIAG) store_io(winDt_out, oDt_win + t * H + dti, dtv, IO);
+                        store_io(winX_out, oX_wout + t * HP + i, xv, IO);
+                        if (DIAG) store_io(winDt_out, oDt_wout + t * H + dti, dtv, IO);
                     }
                 }
+                dtv = DIAG ? dt_fix(dtv, dt_bias_of(row0 + i)) : 1.f;
                 if (DIAG) Dv = p.D[row0 + i];
+                if (gated && t >= 0) sG[t * rows_wg + i] = silu(load_io(p.z, oX_in + t * HP + i, IO));
             }
             sDtx[tt * rows_wg + i] = dtv * xv;
             if (DIAG) sDec[tt * rows_wg + i] = dtv;                        // A carries the log2(e) factor
             if (t >= 0) sY[t * rows_wg + i] = Dv * xv;
         }
     }
-    if (!materialize && first_tile && hd == 0 && tid == 0) p.last_k[b] = k;
+    if (!materialize && first_tile && hd == 0 && tid == 0) p.last_k[b] = t0 + k;
     SSMV_TP(3);
     __syncthreads();
     SSMV_TP(4);
@@ -416,7 +456,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
 #pragma unroll
         for (int v = 0; v < V; ++v) Bv[v] = *reinterpret_cast<const v4f *>(sB + tt * N + v * (LPR * 4) + sub * 4);
         float dec = 0.f;
-        if constexpr (!DIAG) dec = sDec[tt];
+        if constexpr (!DIAG) {
+            dec = sDec[tt];
+            const float dts = sDtF[tt];
+#pragma unroll
+            for (int v = 0; v < V; ++v) Bv[v] *= dts;
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const float dtx = sDtx[tt * rows_wg + lrow[r]];
@@ -485,8 +530,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     if (p.write_hk) store_state(p.state + (size_t)((cur + 2) % 3) * p.slot_stride);
 
     __syncthreads();
-    const bool vec_y = (rows_dom % EV) == 0 && (rows_wg % EV) == 0 && (DIAG || (p.P % EV) == 0);
-    const int log2VY = p.log2_rows_wg - ilog2(EV);
+    // y <- y * z * sigmoid(z) when a gate is given (the SiLU gate of a Mamba block), in fp32 before the rounding
     if (vec_y) {
         for (int idx = tid; idx < (k << log2VY); idx += nthreads) {
             const int t = idx >> log2VY, i = (idx - (t << log2VY)) * EV;
@@ -494,13 +538,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
                 float yv[EV];
 #pragma unroll
                 for (int e = 0; e < EV; ++e) yv[e] = sY[t * rows_wg + i + e];
+                if (gated) {
+#pragma unroll
+                    for (int e = 0; e < EV; ++e) yv[e] *= sG[t * rows_wg + i + e];
+                }
                 Vec::store_raw(p.y, oX_in + t * HP + i, Vec::encode(yv));
             }
         }
     } else {
         for (int idx = tid; idx < k * rows_wg; idx += nthreads) {
             const int t = idx / rows_wg, i = idx - t * rows_wg;
-            if (row0 + i < rows_dom) store_io(p.y, oX_in + t * HP + i, sY[idx], IO);
+            if (row0 + i < rows_dom) {
+                float yv = sY[idx];
+                if (gated) yv *= sG[idx];
+                store_io(p.y, oX_in + t * HP + i, yv, IO);
+            }
         }
     }
 #ifdef SSMV_TRACE
@@ -519,12 +571,17 @@ static int launch_io(const VerifyParams &p, int waves, size_t lds_bytes, hipStre
     const dim3 grid = DIAG ? dim3(p.tiles, p.batch, 1) : dim3(p.tiles, p.H, p.batch);
     const dim3 block(64 * waves);
     const bool conv = p.x_raw != nullptr;
-    if (p.io == SSMV_BF16) {
-        if (conv) hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_BF16, true>), grid, block, lds_bytes, stream, p);
-        else hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_BF16, false>), grid, block, lds_bytes, stream, p);
-    } else {
-        if (conv) hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_F32, true>), grid, block, lds_bytes, stream, p);
-        else hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_F32, false>), grid, block, lds_bytes, stream, p);
+    const bool extra = p.tok0 > 0 || p.dt_softplus || p.dt_bias || p.z;
+    const int sel = (p.io == SSMV_BF16 ? 4 : 0) + (conv ? 2 : 0) + (extra ? 1 : 0);
+    switch (sel) {
+        case 0: hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_F32, false, false>), grid, block, lds_bytes, stream, p); break;
+        case 1: hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_F32, false, true>), grid, block, lds_bytes, stream, p); break;
+        case 2: hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_F32, true, false>), grid, block, lds_bytes, stream, p); break;
+        case 3: hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_F32, true, true>), grid, block, lds_bytes, stream, p); break;
+        case 4: hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_BF16, false, false>), grid, block, lds_bytes, stream, p); break;
+        case 5: hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_BF16, false, true>), grid, block, lds_bytes, stream, p); break;
+        case 6: hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_BF16, true, false>), grid, block, lds_bytes, stream, p); break;
+        default: hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_BF16, true, true>), grid, block, lds_bytes, stream, p); break;
     }
     return (int)hipGetLastError();
 }
@@ -547,7 +604,7 @@ static int launch_n(const VerifyParams &p, VerifyShape s, size_t lds_bytes, hipS
 template <bool DIAG>
 static int launch_verify_any(const VerifyParams &p, VerifyShape s, hipStream_t stream)
 {
-    const size_t lds_bytes = verify_lds_floats<DIAG>(p.lds_tokens, p.k, p.N, p.rows_wg) * sizeof(float);
+    const size_t lds_bytes = verify_lds_floats<DIAG>(p.lds_tokens, p.k, p.N, p.rows_wg, p.z != nullptr) * sizeof(float);
     switch (p.N) {
         case 16: return launch_n<16, DIAG>(p, s, lds_bytes, stream);
         case 32: return launch_n<32, DIAG>(p, s, lds_bytes, stream);

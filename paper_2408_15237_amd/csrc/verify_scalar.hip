@@ -10,8 +10,8 @@ int launch_verify_scalar(const VerifyParams &p, VerifyShape shape, hipStream_t s
 
 size_t verify_lds_bytes(const VerifyParams &p, bool diag)
 {
-    return (diag ? verify_lds_floats<true>(p.lds_tokens, p.k, p.N, p.rows_wg)
-                 : verify_lds_floats<false>(p.lds_tokens, p.k, p.N, p.rows_wg)) * sizeof(float);
+    return (diag ? verify_lds_floats<true>(p.lds_tokens, p.k, p.N, p.rows_wg, p.z != nullptr)
+                 : verify_lds_floats<false>(p.lds_tokens, p.k, p.N, p.rows_wg, p.z != nullptr)) * sizeof(float);
 }
 
 bool verify_shape_supported(int N, int R, bool diag)

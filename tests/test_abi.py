@@ -51,9 +51,9 @@ def test_cache_sizes():
     assert ssmv.ssmv_cache_sizes(d) == [768, 256] + [256] * 13
 
 
-def _code(fn, *a):
+def _code(fn, *a, **kw):
     with pytest.raises(ssmv.SsmvError) as ei:
-        fn(*a)
+        fn(*a, **kw)
     return ei.value.code
 
 
@@ -101,6 +101,18 @@ def test_argument_validation_precedes_any_gpu_work():
     assert _code(ssmv.conv1d_state_update, d, c, P, P, None, 9, P, 0) == ssmv.SSMV_EINVAL
     assert _code(ssmv.conv1d_state_update, d, c, P, None, None, 2, P, 0) == ssmv.SSMV_EINVAL
     assert _code(ssmv.conv1d_state_update, d, c, P, P, P + 2, 2, P, 0) == ssmv.SSMV_EALIGN
+    # the general call: exactly one of x_raw / xc, tok0 + k within kmax, flag values, no multi-call rounds without h_k
+    blk = dict(dt=P, Bm=P, Cm=P, A=P, D=P, y_out=P, stream=0)
+    assert _code(ssmv.ssm_block_multistep, d, c, k=4, **blk) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssm_block_multistep, d, c, k=4, xc=P, x_raw=P, conv_wgt=P, **blk) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssm_block_multistep, d, c, k=4, x_raw=P, **blk) == ssmv.SSMV_EINVAL          # no conv weights
+    assert _code(ssmv.ssm_block_multistep, d, c, k=2, tok0=3, xc=P, **blk) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssm_block_multistep, d, c, k=1, tok0=-1, xc=P, **blk) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssm_block_multistep, d, c, k=1, xc=P, dt_softplus=2, **blk) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssm_block_multistep, d, c, k=1, xc=P, z=P + 2, **blk) == ssmv.SSMV_EALIGN
+    d_hj = ssmv.make_dims(2, 4, 16, 16, kmax=4, io="f32", snapshot_mode="hj_only")
+    assert _code(ssmv.ssm_block_multistep, d_hj, c, k=1, tok0=1, xc=P, **blk) == ssmv.SSMV_EUNSUPPORTED
+    assert _code(ssmv.ssmv_materialize_block, d, c, P, None, 3, P, 0) == ssmv.SSMV_EINVAL
     # broken cache struct
     bad = _fake_cache()
     bad.pend = None

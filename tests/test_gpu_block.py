@@ -1,0 +1,178 @@
+"""GPU parity of the optional pieces around the recurrence (ssm_block_multistep): the step-size transform
+softplus(dt + dt_bias), the SiLU output gate, and rounds that several calls feed (the draft side)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2408_15237_amd as ssmv
+from workload import CONFIGS, block_extras, generate
+
+from _harness import HipLayer, TOL, dims_of, rel_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _auto_tuning():
+    ssmv.ssmv_set_tuning(0, 0)
+    yield
+    ssmv.ssmv_set_tuning(0, 0)
+
+
+def _block_oracle(wl, lp, bias, softplus):
+    return oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.conv_act, wl.ngroups,
+                              dt_bias=bias, dt_softplus=softplus)
+
+
+def _check_ints(hip, bk, where):
+    ints = hip.cache.ints()
+    assert ints["cur_slot"].tolist() == bk.cur, where
+    assert ints["pend"].tolist() == bk.pend, where
+    assert ints["pos"].tolist() == bk.pos, where
+    assert ints["conv_head"].tolist() == bk.conv_head, where
+    assert ints["last_k"].tolist() == bk.last_k, where
+    assert ints["win_par"] == bk.win_par and ints["err_flag"] == bk.err == 0, where
+
+
+CASES = {
+    "cfg0": CONFIGS["cfg0"],
+    "cfg1_small": CONFIGS["cfg1"].scaled(nheads=4, batch=3, rounds=10),
+    "cfg2_small": CONFIGS["cfg2"].scaled(nheads=192, rounds=10),
+    "f32_groups": CONFIGS["cfg0"].scaled(io="f32", ngroups=2, nheads=4, batch=5, k=3, kmax=5, rounds=10),
+    "ragged_rows": CONFIGS["cfg0"].scaled(headdim=24, dstate=32, batch=3, rounds=8),
+}
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["split", "fused"])
+@pytest.mark.parametrize("gate", [False, True], ids=["nogate", "gate"])
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_step_size_transform_and_gate(name, gate, fused):
+    wl = CASES[name]
+    data = generate(wl)
+    ex = block_extras(data)
+    lp, bias = data.layers[0], ex.dt_bias[0]
+    tol = TOL[wl.io]
+    hip = HipLayer(wl, lp)
+    ora = _block_oracle(wl, lp, bias, True)
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
+    d_bias = torch.from_numpy(bias).to("cuda")
+    for i, rd in enumerate(data.rounds):
+        k = rd.x_raw.shape[1]
+        z = ex.z[i] if gate else None
+        y_ref, xc_ref, _ = ora.verify(rd.x_raw, ex.dt_raw[i][0], rd.B[0], rd.C[0], z=z)
+        d_x = to_dev(rd.x_raw, wl.io)
+        y = torch.empty_like(d_x)
+        kw = dict(dt=to_dev(ex.dt_raw[i][0], wl.io), Bm=to_dev(rd.B[0], wl.io), Cm=to_dev(rd.C[0], wl.io), A=hip.A, D=hip.D,
+                  k=k, y_out=y, dt_bias=d_bias, dt_softplus=True, z=None if z is None else to_dev(z, wl.io))
+        if fused:
+            ssmv.ssm_block_multistep(hip.dims, hip.cache.c, x_raw=d_x, conv_wgt=hip.conv_w, conv_bias=hip.conv_b, **kw)
+        else:
+            ssmv.ssm_block_multistep(hip.dims, hip.cache.c, xc=hip.conv(d_x), **kw)
+        bk.verify(k)
+        e_y = rel_err(to_host(y), y_ref)
+        assert e_y <= tol, "round %d: y error %.3g > %.3g" % (i, e_y, tol)
+        hip.commit(torch.from_numpy(rd.accepted.astype(np.int32)).to("cuda"))
+        ora.commit(rd.accepted)
+        bk.commit(rd.accepted)
+        _check_ints(hip, bk, "round %d" % i)
+        h = torch.empty((wl.batch, wl.nheads, wl.headdim, wl.dstate), dtype=torch.float32, device="cuda")
+        ssmv.ssmv_materialize_block(hip.dims, hip.cache.c, hip.A, d_bias, True, h)
+        e_h = rel_err(to_host(h), ora.h)
+        assert e_h <= tol, "round %d: state error %.3g > %.3g" % (i, e_h, tol)
+    ssmv.ssmv_check(hip.cache.c)
+
+
+def test_transform_off_and_no_gate_is_the_plain_call_bit_for_bit():
+    wl = CASES["cfg1_small"]
+    data = generate(wl)
+    a, b = HipLayer(wl, data.layers[0]), HipLayer(wl, data.layers[0])
+    for rd in data.rounds:
+        d_x, d_dt, d_B, d_C = (to_dev(v, wl.io) for v in (rd.x_raw, rd.dt[0], rd.B[0], rd.C[0]))
+        y_a, _ = a.conv_verify(d_x, d_dt, d_B, d_C)
+        y_b = torch.empty_like(d_x)
+        ssmv.ssm_block_multistep(b.dims, b.cache.c, x_raw=d_x, conv_wgt=b.conv_w, conv_bias=b.conv_b, dt=d_dt, Bm=d_B, Cm=d_C,
+                                 A=b.A, D=b.D, k=rd.x_raw.shape[1], y_out=y_b)
+        assert torch.equal(y_a, y_b)
+        acc = torch.from_numpy(rd.accepted.astype(np.int32)).to("cuda")
+        a.commit(acc); b.commit(acc)
+    assert torch.equal(a.cache.state_view(), b.cache.state_view())
+
+
+SPLITS = {"ones": None, "2+2": [2, 2], "1+3": [1, 3], "3+1": [3, 1]}
+
+
+@pytest.mark.parametrize("split", sorted(SPLITS))
+@pytest.mark.parametrize("name", ["cfg0", "cfg1_small", "cfg2_small", "f32_groups"])
+def test_round_fed_by_several_calls_equals_one_call(name, split):
+    """Draft side: the calls of one round (first with tok0 = 0, later ones continuing in the h_k slot) leave the
+    outputs, the three slots, the window, the ring and - after the same commit - the integers exactly as ONE
+    call with all the tokens does (bit for bit: same arithmetic in the same order), and both match the oracle."""
+    wl = CASES[name]
+    data = generate(wl)
+    lp = data.layers[0]
+    tol = TOL[wl.io]
+    one, many = HipLayer(wl, lp), HipLayer(wl, lp)
+    ora = oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.conv_act, wl.ngroups)
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
+    for i, rd in enumerate(data.rounds):
+        k = rd.x_raw.shape[1]
+        parts = SPLITS[split] if SPLITS[split] is not None and sum(SPLITS[split]) == k else [1] * k
+        d_x, d_dt, d_B, d_C = (to_dev(v, wl.io) for v in (rd.x_raw, rd.dt[0], rd.B[0], rd.C[0]))
+        y_one, _ = one.conv_verify(d_x, d_dt, d_B, d_C)
+        y_ref, _, _ = ora.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
+        t0, ys = 0, []
+        for n in parts:
+            sl = slice(t0, t0 + n)
+            y = torch.empty_like(d_x[:, sl])
+            ssmv.ssm_block_multistep(many.dims, many.cache.c, x_raw=d_x[:, sl].contiguous(), conv_wgt=many.conv_w,
+                                     conv_bias=many.conv_b, dt=d_dt[:, sl].contiguous(), Bm=d_B[:, sl].contiguous(),
+                                     Cm=d_C[:, sl].contiguous(), A=many.A, D=many.D, k=n, tok0=t0, y_out=y)
+            bk.verify(n, tok0=t0)
+            ys.append(y)
+            t0 += n
+        y_many = torch.cat(ys, dim=1)
+        assert torch.equal(y_many, y_one), "round %d: outputs differ from the single call" % i
+        assert rel_err(to_host(y_many), y_ref) <= tol
+        assert many.cache.ints()["last_k"].tolist() == [k] * wl.batch
+        acc = torch.from_numpy(rd.accepted.astype(np.int32)).to("cuda")
+        one.commit(acc); many.commit(acc)
+        ora.commit(rd.accepted)
+        bk.commit(rd.accepted)
+        _check_ints(many, bk, "round %d" % i)
+        assert torch.equal(many.cache.state_view(), one.cache.state_view()), "round %d: slots differ" % i
+        for nm in ("conv_ring", "win_xc0", "win_xc1", "win_dt0", "win_dt1", "win_B0", "win_B1"):
+            assert torch.equal(many.cache.buffers[nm], one.cache.buffers[nm]), nm
+        assert rel_err(to_host(many.materialize()), ora.h) <= tol
+    ssmv.ssmv_check(many.cache.c)
+
+
+def test_draft_model_round_trip_with_rejections():
+    """A draft-side round as the paper describes it: k single-token calls (the first recomputes the tokens
+    accepted last round), then the verifier's verdict rolls the draft's own cache back."""
+    wl = CONFIGS["cfg1"].scaled(nheads=4, batch=4, rounds=12, accept="geometric", accept_p=0.4)
+    data = generate(wl)
+    ex = block_extras(data)
+    lp, bias = data.layers[0], ex.dt_bias[0]
+    hip = HipLayer(wl, lp)
+    ora = _block_oracle(wl, lp, bias, True)
+    d_bias = torch.from_numpy(bias).to("cuda")
+    tol = TOL[wl.io]
+    for i, rd in enumerate(data.rounds):
+        k = rd.x_raw.shape[1]
+        y_ref, _, _ = ora.verify(rd.x_raw, ex.dt_raw[i][0], rd.B[0], rd.C[0], z=ex.z[i])
+        d_x, d_dt, d_B, d_C, d_z = (to_dev(v, wl.io) for v in (rd.x_raw, ex.dt_raw[i][0], rd.B[0], rd.C[0], ex.z[i]))
+        for t in range(k):
+            sl = slice(t, t + 1)
+            y = torch.empty_like(d_x[:, sl])
+            ssmv.ssm_block_multistep(hip.dims, hip.cache.c, x_raw=d_x[:, sl].contiguous(), conv_wgt=hip.conv_w, conv_bias=hip.conv_b,
+                                     dt=d_dt[:, sl].contiguous(), dt_bias=d_bias, dt_softplus=True, Bm=d_B[:, sl].contiguous(),
+                                     Cm=d_C[:, sl].contiguous(), z=d_z[:, sl].contiguous(), A=hip.A, D=hip.D, k=1, tok0=t, y_out=y)
+            e = rel_err(to_host(y), y_ref[:, sl])
+            assert e <= tol, "round %d token %d: %.3g" % (i, t, e)
+        hip.commit(torch.from_numpy(rd.accepted.astype(np.int32)).to("cuda"))
+        ora.commit(rd.accepted)
+    h = torch.empty((wl.batch, wl.nheads, wl.headdim, wl.dstate), dtype=torch.float32, device="cuda")
+    ssmv.ssmv_materialize_block(hip.dims, hip.cache.c, hip.A, d_bias, True, h)
+    assert rel_err(to_host(h), ora.h) <= tol
+    ssmv.ssmv_check(hip.cache.c)

@@ -261,3 +261,59 @@ def test_first_conflict_examples():
     draft = np.array([[1, 2, 3, 4], [1, 2, 3, 4], [9, 2, 3, 4], [1, 2, 3, 4]])
     target = np.array([[1, 2, 3, 4], [1, 2, 7, 4], [1, 2, 3, 4], [1, 2, 3, 5]])
     assert oracle.first_conflict(draft, target).tolist() == [4, 2, 0, 3]
+
+
+# ---- the pieces of a whole Mamba block around the recurrence: step-size transform and output gate ----
+
+def test_softplus_closed_forms_and_library():
+    """softplus(0) = ln 2; softplus(x) - softplus(-x) = x; softplus(x) -> x for large x and -> exp(x) for very
+    negative x (no overflow on either side); and torch's softplus in fp64 as the library routine."""
+    assert oracle.softplus(0.0) == pytest.approx(np.log(2.0), rel=1e-15)
+    x = np.linspace(-30, 30, 241)
+    np.testing.assert_allclose(oracle.softplus(x) - oracle.softplus(-x), x, rtol=0, atol=1e-13)
+    assert oracle.softplus(800.0) == 800.0 and np.isfinite(oracle.softplus(-800.0))
+    np.testing.assert_allclose(oracle.softplus(-40.0), np.exp(-40.0), rtol=1e-12)
+    ref = torch.nn.functional.softplus(torch.from_numpy(x), beta=1.0, threshold=1e9).numpy()
+    np.testing.assert_allclose(oracle.softplus(x), ref, rtol=1e-13)
+    # planted mistakes: log(1+exp(x)) without the bias term / with the wrong sign
+    assert not np.allclose(np.log1p(np.exp(-x)), ref)
+    assert not np.allclose(np.maximum(x, 0) - np.log1p(np.exp(-np.abs(x))), ref)
+
+
+def test_step_size_bias_is_added_before_the_softplus():
+    r = np.random.default_rng(5)
+    raw, bias = r.standard_normal((2, 3, 4)), r.standard_normal(4)
+    got = oracle.step_size(raw, bias, True)
+    ref = torch.nn.functional.softplus(torch.from_numpy(raw) + torch.from_numpy(bias), threshold=1e9).numpy()
+    np.testing.assert_allclose(got, ref, rtol=1e-13)
+    assert not np.allclose(oracle.softplus(raw) + bias, ref)                 # bias after the softplus: caught
+    np.testing.assert_array_equal(oracle.step_size(raw), raw)                # nothing asked for: identity
+    np.testing.assert_allclose(oracle.step_size(raw, bias), raw + bias, rtol=0, atol=0)
+
+
+def test_silu_gate_library_and_limits():
+    r = np.random.default_rng(6)
+    y, z = r.standard_normal((3, 5, 8)), r.standard_normal((3, 5, 8)) * 3
+    ref = (torch.from_numpy(y) * torch.nn.functional.silu(torch.from_numpy(z))).numpy()
+    np.testing.assert_allclose(oracle.silu_gate(y, z), ref, rtol=1e-13, atol=1e-15)
+    np.testing.assert_array_equal(oracle.silu_gate(y, np.zeros_like(z)), np.zeros_like(y))      # silu(0) = 0
+    np.testing.assert_allclose(oracle.silu_gate(y, np.full_like(z, 50.0)), 50.0 * y, rtol=1e-12)  # silu(z) -> z
+    assert not np.allclose(y / (1 + np.exp(-z)), ref)                        # sigmoid gate instead of SiLU: caught
+
+
+def test_eager_oracle_block_pieces_compose_with_the_plain_scan():
+    """EagerOracle with a step-size transform and a gate = the plain scan on the transformed dt, gated afterwards:
+    the transform acts on dt only (not on x, B or the skip term) and the gate on y only (not on the state)."""
+    d = _draw(11)
+    r = np.random.default_rng(12)
+    H, P = d["D"].shape[0], d["h0"].shape[2]
+    conv_w = np.zeros((H * P, 4)); conv_w[:, 3] = 1.0                        # identity conv: xc = x
+    bias = r.standard_normal(H) * 0.3
+    raw = r.standard_normal(d["dt"].shape) - 1.0
+    z = r.standard_normal(d["x"].shape)
+    blk = oracle.EagerOracle("scalar", d["A"], d["D"], conv_w, None, d["h0"], "f32", dt_bias=bias, dt_softplus=True)
+    y, _, snap = blk.verify(d["x"], raw, d["B"], d["C"], z=z)
+    dt = np.logaddexp(0.0, raw + bias)                                       # softplus through another routine
+    y_ref, snap_ref = oracle.scan_tokens("scalar", d["h0"], oracle.round_io(d["x"], "f32"), dt, d["B"], d["C"], d["A"], d["D"])
+    np.testing.assert_allclose(snap, snap_ref, rtol=1e-12, atol=1e-14)       # the gate leaves the state alone
+    np.testing.assert_allclose(y, y_ref * z / (1 + np.exp(-z)), rtol=1e-12, atol=1e-14)

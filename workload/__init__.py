@@ -6,5 +6,5 @@ that both the CPU oracle's tests and the HIP path's tests/bench may share.
 """
 from .configs import Workload, CONFIGS, get_workload  # noqa: F401
 from .generate import (  # noqa: F401
-    WorkloadData, RoundInputs, LayerParams, generate, round_to_io, draw_accepted,
+    WorkloadData, RoundInputs, LayerParams, generate, round_to_io, draw_accepted, BlockExtras, block_extras,
 )

@@ -131,3 +131,27 @@ def generate(wl: Workload, rounds: Optional[int] = None, k_schedule=None) -> Wor
         assert 1 <= k <= wl.kmax_eff
         data.rounds.append(_draw_round(rng, wl, k))
     return data
+
+
+@dataclass
+class BlockExtras:
+    """Inputs of the optional block pieces, drawn from a stream of their own (seed + 1000003) so that the
+    data sets above do not change: per layer a step-size bias, per round and layer a raw step-size projection
+    (the step is softplus(raw + bias)), per round a gate input z."""
+    dt_bias: List[np.ndarray]            # per layer [nheads] float32
+    dt_raw: List[List[np.ndarray]]       # [round][layer] [batch][k][nheads], io-representable
+    z: List[np.ndarray]                  # [round] [batch][k][conv_channels], io-representable
+
+
+def block_extras(data: WorkloadData) -> BlockExtras:
+    """raw ~ N(0,1) - 4 and bias ~ U(-0.5, 0.5): softplus(raw + bias) has the spread of the plain workloads' dt;
+    z ~ N(0,1)."""
+    wl = data.wl
+    rng = np.random.Generator(np.random.PCG64(wl.seed + 1000003))
+    bias = [rng.uniform(-0.5, 0.5, size=wl.nheads).astype(np.float32) for _ in range(wl.layers)]
+    dt_raw, z = [], []
+    for rd in data.rounds:
+        k = rd.x_raw.shape[1]
+        dt_raw.append([round_to_io(rng.standard_normal((wl.batch, k, wl.nheads)) - 4.0, wl.io) for _ in range(wl.layers)])
+        z.append(round_to_io(rng.standard_normal((wl.batch, k, wl.conv_channels)), wl.io))
+    return BlockExtras(dt_bias=bias, dt_raw=dt_raw, z=z)
