@@ -8,8 +8,9 @@
 //     holding EPL = N/LPR values as V = EPL/4 float4 strips, so one global_load_dwordx4 of a wave
 //     covers RPI = 64/LPR consecutive rows (N*4*RPI = 1 KiB contiguous at N = 64): every
 //     state access is a full-width coalesced 16-byte access.
-//   * A lane keeps R rows (interleaved: row = base + r*RPI + lane/LPR) in VGPRs for the whole
-//     pend+k steps; the state is read once and written once per snapshot.
+//   * A lane keeps R adjacent rows (row = base + (lane/LPR)*R + r) in VGPRs for the whole pend+k steps, so
+//     one load instruction of a wave covers RPI pieces of N*4 contiguous bytes, R rows apart; the state
+//     is read once and written once per snapshot.
 //   * A workgroup of `waves` waves owns rows_wg = waves*RPI*R rows of ONE (sequence, head)
 //     (scalar-A mode) or of one sequence's channels (diagonal-A mode), so the replay trip count
 //     pend[b] is uniform over the workgroup.
@@ -48,6 +49,28 @@ __device__ __forceinline__ float row_sum(float v)
     if constexpr (LPR >= 8) v += dpp_move<0x141>(v);   // row_half_mirror
     if constexpr (LPR >= 16) v += dpp_move<0x140>(v);  // row_mirror
     return v;
+}
+
+// the same for R independent values, stage by stage
+template <int LPR, int R>
+__device__ __forceinline__ void row_sum_all(float (&v)[R])
+{
+    if constexpr (LPR >= 2) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) v[r] += dpp_move<0xB1>(v[r]);
+    }
+    if constexpr (LPR >= 4) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) v[r] += dpp_move<0x4E>(v[r]);
+    }
+    if constexpr (LPR >= 8) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) v[r] += dpp_move<0x141>(v[r]);
+    }
+    if constexpr (LPR >= 16) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) v[r] += dpp_move<0x140>(v[r]);
+    }
 }
 
 __host__ __device__ constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
@@ -134,18 +157,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     // ---- state loads first: uniform base pointer + 32-bit lane offsets -------------------------------
     v4f h[R][V];
     v4f a2[DIAG ? R : 1][DIAG ? V : 1];                 // diag mode: A strips times log2(e): the decay is one exp2
-    unsigned lrow[R];                                   // row inside the workgroup
-    unsigned loff[R];                                   // element offset of the lane's first strip of that row
-    bool rvalid[R];
+    // a lane's R rows are adjacent (their per-row scalars are one LDS vector, their addresses one base register plus
+    // immediates): row r is lrow0 + r inside the workgroup, its first strip at element loff0 + r*N, valid iff r < nvalid
+    const unsigned lrow0 = wave * (RPI * R) + rsel * R;
+    const unsigned loff0 = (lrow0 << LOG2N) + sub * 4;
+    const int nvalid = rows_dom - (int)(row0 + lrow0);
     {
         const float *src = p.state + (size_t)src_slot * p.slot_stride + (grow << LOG2N);
         const float *srcA = p.A + ((size_t)row0 << LOG2N);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            lrow[r] = wave * (RPI * R) + r * RPI + rsel;
-            rvalid[r] = (int)(row0 + lrow[r]) < rows_dom;
-            loff[r] = (lrow[r] << LOG2N) + sub * 4;
-            const unsigned o = rvalid[r] ? loff[r] : sub * 4;         // clamp to row 0: unconditional in-bounds load
+            const unsigned o = r < nvalid ? loff0 + r * N : sub * 4;  // clamp to row 0: unconditional in-bounds load
 #pragma unroll
             // streamed once per round: non-temporal, so that 100 MB per launch do not churn the caches
             for (int v = 0; v < V; ++v) h[r][v] = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(src + o + v * (LPR * 4)));
@@ -450,6 +472,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     __syncthreads();
     SSMV_TP(4);
 
+    // the per-row values of the lane's R adjacent rows out of a [rows_wg] LDS array (16-byte reads where R allows)
+    auto lane_rows = [&](const float *arr, float (&out)[R]) {
+        if constexpr (R % 4 == 0) {
+#pragma unroll
+            for (int j = 0; j < R / 4; ++j) {
+                const v4f t = *reinterpret_cast<const v4f *>(arr + lrow0 + 4 * j);
+                out[4 * j] = t.x; out[4 * j + 1] = t.y; out[4 * j + 2] = t.z; out[4 * j + 3] = t.w;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < R; ++r) out[r] = arr[lrow0 + r];
+        }
+    };
     // one recurrence step on the lane's strips: h <- decay*h + (dt*x) * B
     auto step = [&](int tt) {
         v4f Bv[V];
@@ -462,11 +497,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
 #pragma unroll
             for (int v = 0; v < V; ++v) Bv[v] *= dts;
         }
+        float xr[R], dr[DIAG ? R : 1];
+        lane_rows(sDtx + tt * rows_wg, xr);
+        if constexpr (DIAG) lane_rows(sDec + tt * rows_wg, dr);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const float dtx = sDtx[tt * rows_wg + lrow[r]];
+            const float dtx = xr[r];
             float dt2 = 0.f;
-            if constexpr (DIAG) dt2 = sDec[tt * rows_wg + lrow[r]];
+            if constexpr (DIAG) dt2 = dr[r];
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 v4f d4;
@@ -478,25 +516,77 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
                 } else {
                     d4 = v4f{dec, dec, dec, dec};
                 }
-                h[r][v].x = fmaf(d4.x, h[r][v].x, dtx * Bv[v].x);
-                h[r][v].y = fmaf(d4.y, h[r][v].y, dtx * Bv[v].y);
-                h[r][v].z = fmaf(d4.z, h[r][v].z, dtx * Bv[v].z);
-                h[r][v].w = fmaf(d4.w, h[r][v].w, dtx * Bv[v].w);
+                // decay in place, then one fma: no temporaries (the other order keeps 4*R*V products alive)
+                h[r][v] *= d4;
+                h[r][v].x = fmaf(dtx, Bv[v].x, h[r][v].x);
+                h[r][v].y = fmaf(dtx, Bv[v].y, h[r][v].y);
+                h[r][v].z = fmaf(dtx, Bv[v].z, h[r][v].z);
+                h[r][v].w = fmaf(dtx, Bv[v].w, h[r][v].w);
+            }
+        }
+    };
+    // Scaled form (scalar mode).  With alpha_t = exp(A * (dt_b + .. + dt_t)) accumulated from some base token b and
+    // g_t = h_t / alpha_t, the recurrence of Section 2.1 becomes g_t = g_(t-1) + (dt_t / alpha_t) x_t (x) B_t: ONE
+    // fma per state element and token instead of a multiply and an fma; y_t = alpha_t (C_t . g_t) and a snapshot is
+    // alpha_t g_t.  alpha_t / alpha_s <= 1 for s <= t, so a rounding error made at token s only shrinks.  So that
+    // 1/alpha cannot overflow, alpha is folded into the registers (and the base moved) before it would fall below
+    // 2^-64, and a single token that decays by more than that takes the plain two-operation step.
+    constexpr bool SC = !DIAG;
+    float L2 = 0.f;                                     // log2 alpha of the last token taken (0 in diag mode)
+    const float A2 = A_h * LOG2E;
+    auto fold_scale = [&]() {
+        const float al = __builtin_amdgcn_exp2f(L2);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int v = 0; v < V; ++v) h[r][v] *= al;
+        L2 = 0.f;
+    };
+    auto advance = [&](int tt) {
+        if constexpr (!SC) {
+            step(tt);
+        } else {
+            const float dts = sDtF[tt];
+            const float dl = dts * A2;
+            if (!(fabsf(L2 + dl) <= 64.f)) {            // rare; also taken for a NaN
+                fold_scale();
+                if (!(fabsf(dl) <= 64.f)) {
+                    step(tt);
+                    return;
+                }
+            }
+            L2 += dl;
+            const float sc = dts * __builtin_amdgcn_exp2f(-L2);
+            v4f Bv[V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) Bv[v] = *reinterpret_cast<const v4f *>(sB + tt * N + v * (LPR * 4) + sub * 4) * sc;
+            float xr[R];
+            lane_rows(sDtx + tt * rows_wg, xr);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    h[r][v].x = fmaf(xr[r], Bv[v].x, h[r][v].x);
+                    h[r][v].y = fmaf(xr[r], Bv[v].y, h[r][v].y);
+                    h[r][v].z = fmaf(xr[r], Bv[v].z, h[r][v].z);
+                    h[r][v].w = fmaf(xr[r], Bv[v].w, h[r][v].w);
+                }
             }
         }
     };
     auto store_state = [&](float *dst_base) {
         float *dst = dst_base + (grow << LOG2N);
+        const float al = SC ? __builtin_amdgcn_exp2f(L2) : 1.f;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            if (!rvalid[r]) continue;
+            if (r >= nvalid) continue;
 #pragma unroll
-            for (int v = 0; v < V; ++v) __builtin_nontemporal_store(h[r][v], reinterpret_cast<v4f *>(dst + loff[r] + v * (LPR * 4)));
+            for (int v = 0; v < V; ++v)
+                __builtin_nontemporal_store(SC ? h[r][v] * al : h[r][v], reinterpret_cast<v4f *>(dst + loff0 + r * N + v * (LPR * 4)));
         }
     };
-
     // (i) replay the pending tokens: no outputs
-    for (int s = 0; s < pd; ++s) step(s);
+    for (int s_ = 0; s_ < pd; ++s_) advance(s_);
     if (materialize) {
         store_state(p.h_out);
         return;
@@ -506,23 +596,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     // (iii) the k draft tokens
     SSMV_TP(5);
     for (int t = 0; t < k; ++t) {
-        step(pd + t);
+        advance(pd + t);
+        const float al = SC ? __builtin_amdgcn_exp2f(L2) : 1.f;
         v4f Cv[V];
 #pragma unroll
         for (int v = 0; v < V; ++v) Cv[v] = *reinterpret_cast<const v4f *>(sC + t * N + v * (LPR * 4) + sub * 4);
+        float acc[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            float acc = 0.f;
+            acc[r] = 0.f;
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                acc = fmaf(Cv[v].x, h[r][v].x, acc);
-                acc = fmaf(Cv[v].y, h[r][v].y, acc);
-                acc = fmaf(Cv[v].z, h[r][v].z, acc);
-                acc = fmaf(Cv[v].w, h[r][v].w, acc);
+                acc[r] = fmaf(Cv[v].x, h[r][v].x, acc[r]);
+                acc[r] = fmaf(Cv[v].y, h[r][v].y, acc[r]);
+                acc[r] = fmaf(Cv[v].z, h[r][v].z, acc[r]);
+                acc[r] = fmaf(Cv[v].w, h[r][v].w, acc[r]);
             }
-            acc = row_sum<LPR>(acc);
+        }
+        // the reduction over the row's lanes, one stage for all R rows at a time: a DPP operand must not have been
+        // written by the instruction just before it, and R independent chains fill those slots
+        row_sum_all<LPR, R>(acc);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if constexpr (SC) acc[r] *= al;
             // y = D*x + C.h : no-return LDS add by the row's first lane, nothing waits on it
-            if (sub == 0) __hip_atomic_fetch_add(&sY[t * rows_wg + lrow[r]], acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (sub == 0) __hip_atomic_fetch_add(&sY[t * rows_wg + lrow0 + r], acc[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     }
     // (iv) snapshot h_k (Algorithm 2), unless every accepted token is to stay pending

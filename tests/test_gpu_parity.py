@@ -146,6 +146,23 @@ def test_mixed_pending_counts_in_one_batch(fused):
 
 
 @FUSED
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("dt_scale", [60.0, 400.0, 4000.0])
+def test_strong_decay(dt_scale, io, fused):
+    """The scalar-mode kernel carries the state divided by the decay accumulated over the tokens of a launch.  With
+    dt*|A| of order 1 per token (x60) that scale has to be folded back every few tokens, with dt*|A| of tens (x400)
+    every token, and beyond 64*ln2 per token (x4000: the decay underflows to 0) the plain step has to take over;
+    k = 8 with up to 7 pending tokens gives launches of 15 tokens."""
+    from workload import round_to_io
+    wl = Workload("decay", "scalar", batch=3, nheads=4, headdim=32, dstate=64, k=8, rounds=8, io=io,
+                  accept="uniform", seed=21)
+    data = generate(wl)
+    for rd in data.rounds:
+        rd.dt[0] = round_to_io(rd.dt[0] * dt_scale, io)
+    run_parity(wl, data, fused=fused)
+
+
+@FUSED
 def test_k1_single_step_rounds(fused):
     wl = Workload("k1", "scalar", batch=2, nheads=2, headdim=64, dstate=64, k=1, rounds=10, io="f32",
                   accept="uniform", seed=12)
