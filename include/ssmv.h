@@ -169,8 +169,10 @@ int ssm_conv_verify_multistep(const ssmv_dims *dims, const ssmv_cache *cache, co
  *     call of a round has tok0 = 0 and is a verify as above; a later call, with tok0 = the number
  *     of tokens the round has been fed so far, continues from the state in the h_k slot, updates that
  *     slot in place, replays nothing, appends its k tokens to the round's window and conv ring, and sets
- *     last_k[b] = tok0 + k.  After the calls the slots, the window and the ring hold exactly what one
- *     call with all tok0+k tokens would have left, so ssm_commit_rollback applies unchanged.
+ *     last_k[b] = tok0 + k.  After the calls the window, the ring and the integers hold exactly what one
+ *     call with all tok0+k tokens would have left, the slots and the outputs the same up to fp32 rounding
+ *     (the rounding order inside a launch depends on how many tokens it holds), so ssm_commit_rollback
+ *     applies unchanged.
  *     tok0 + k <= kmax; not with SSMV_SNAP_HJ_ONLY (SSMV_EUNSUPPORTED); a later call is NOT idempotent.
  * Exactly one of x_raw (conv fused; needs conv_wgt) and xc is non-NULL.  Other arguments as above. */
 typedef struct ssmv_step_args {
