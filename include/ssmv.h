@@ -174,6 +174,12 @@ int ssm_conv_verify_multistep(const ssmv_dims *dims, const ssmv_cache *cache, co
  *     (the rounding order inside a launch depends on how many tokens it holds), so ssm_commit_rollback
  *     applies unchanged.
  *     tok0 + k <= kmax; not with SSMV_SNAP_HJ_ONLY (SSMV_EUNSUPPORTED); a later call is NOT idempotent.
+ *   - k_seq (device int32 [batch], or NULL): ragged draft counts.  Sequence b takes only the first
+ *     kb = clamp(k_seq[b], 1, k) of the k tokens given (at least one: last_k = 0 means "no verify"
+ *     to the commit; a sequence with nothing to verify passes one token and accepts none) (the arrays keep the stride k): its outputs
+ *     y[b][t >= kb] are written as zeros, its h_k slot holds the state after kb tokens, last_k[b] =
+ *     tok0 + kb, and ssm_commit_rollback then clamps accepted[b] to that.  Work for the tokens
+ *     not taken is skipped.
  * Exactly one of x_raw (conv fused; needs conv_wgt) and xc is non-NULL.  Other arguments as above. */
 typedef struct ssmv_step_args {
     const void *x_raw;      /* [batch][k][Cx] io_dtype, or NULL */
@@ -187,6 +193,7 @@ typedef struct ssmv_step_args {
     const void *z;          /* [batch][k][H*P] io_dtype or NULL */
     const float *A;         /* [H] or [H][N] fp32 */
     const float *D;         /* [H] fp32 */
+    const int32_t *k_seq;   /* [batch] int32 or NULL */
     void *y_out;            /* [batch][k][H*P] io_dtype */
     int32_t k;
     int32_t tok0;

@@ -272,6 +272,7 @@ static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const ssmv_ste
     if ((rc = check_ptr(a->D, "D")) != SSMV_OK) return rc;
     if ((rc = check_ptr(a->y_out, "y_out")) != SSMV_OK) return rc;
     if (a->z && !aligned16(a->z)) return fail(SSMV_EALIGN, "z is not 16-byte aligned");
+    if (a->k_seq && ((uintptr_t)a->k_seq & 3)) return fail(SSMV_EALIGN, "k_seq is not 4-byte aligned");
     if (a->dt_bias && ((uintptr_t)a->dt_bias & 3)) return fail(SSMV_EALIGN, "dt_bias is not 4-byte aligned");
     VerifyParams p{};
     fill_verify(p, d, c);
@@ -282,6 +283,7 @@ static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const ssmv_ste
     p.dt_softplus = a->dt_softplus;
     p.dt_bias = a->dt_bias;
     p.z = a->z;
+    p.k_seq = a->k_seq;
     p.pend_max = d->snapshot_mode == SSMV_SNAP_HJ_ONLY ? d->kmax : d->kmax - 1;
     p.write_hk = d->snapshot_mode != SSMV_SNAP_HJ_ONLY;
     p.lds_tokens = (a->tok0 > 0 ? 0 : p.pend_max) + k;

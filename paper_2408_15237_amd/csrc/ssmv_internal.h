@@ -26,6 +26,7 @@ struct VerifyParams {
     int dt_softplus;     // 1: dt <- softplus(dt + dt_bias) before use
     const float *dt_bias;  // [nheads] or null
     const void *z;       // gate input [batch][k][channels] or null
+    const int *k_seq;    // per-sequence draft counts [batch] or null
     int log2_rows_wg;    // rows_wg is a power of two
     // fused conv roll (x_raw != nullptr): ring append + width-4 conv computed while staging
     int ring_len, conv_act;

@@ -151,7 +151,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const int pd = min(max(p.pend[b], 0), p.pend_max) & (EXTRA ? p.pend_mask : ~0);
     const int src_slot = EXTRA ? (cur + p.src_add) % 3 : cur;
     const int par = p.win_par[0] & 1;
-    const int T = pd + k;
     SSMV_TP(1);
 
     // ---- state loads first: uniform base pointer + 32-bit lane offsets -------------------------------
@@ -177,6 +176,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             }
         }
     }
+
+    // (after the state loads have been issued: nothing they need depends on it)
+    // ragged drafts: sequence b takes only the first k_seq[b] of the k tokens given (the arrays keep the stride k)
+    int kb = k;
+    if constexpr (EXTRA) if (p.k_seq) kb = min(max(p.k_seq[b], 1), k);
+    const int T = pd + kb;
 
     // ---- LDS carve-up -------------------------------------------------------------------------------
     const int TL = p.lds_tokens;
@@ -390,7 +395,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     };
 
     // first pass: every thread issues its B, C, x (and dt) loads, then consumes them
-    const int nB = T << LOG2VN, nC = k << LOG2VN;
+    const int nB = T << LOG2VN, nC = kb << LOG2VN;
     const BReq qB = b_req(tid, nB), qC = b_req(tid, nC);
     const XReq qX = x_req(tid), qX2 = x_req(tid + nthreads);           // two x items per thread before any wait
     const uint4 fB = b_load(qB);
@@ -467,7 +472,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             if (t >= 0) sY[t * rows_wg + i] = Dv * xv;
         }
     }
-    if (!materialize && first_tile && hd == 0 && tid == 0) p.last_k[b] = t0 + k;
+    if (!materialize && first_tile && hd == 0 && tid == 0) p.last_k[b] = t0 + kb;
     SSMV_TP(3);
     __syncthreads();
     SSMV_TP(4);
@@ -595,7 +600,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     if (pd > 0) store_state(p.state + (size_t)((cur + 1) % 3) * p.slot_stride);
     // (iii) the k draft tokens
     SSMV_TP(5);
-    for (int t = 0; t < k; ++t) {
+    for (int t = 0; t < kb; ++t) {
         advance(pd + t);
         const float al = SC ? __builtin_amdgcn_exp2f(L2) : 1.f;
         v4f Cv[V];
@@ -635,8 +640,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             if (row0 + i < rows_dom) {
                 float yv[EV];
 #pragma unroll
-                for (int e = 0; e < EV; ++e) yv[e] = sY[t * rows_wg + i + e];
-                if (gated) {
+                for (int e = 0; e < EV; ++e) yv[e] = t < kb ? sY[t * rows_wg + i + e] : 0.f;    // tokens not taken: zeros
+                if (gated && t < kb) {
 #pragma unroll
                     for (int e = 0; e < EV; ++e) yv[e] *= sG[t * rows_wg + i + e];
                 }
@@ -647,8 +652,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         for (int idx = tid; idx < k * rows_wg; idx += nthreads) {
             const int t = idx / rows_wg, i = idx - t * rows_wg;
             if (row0 + i < rows_dom) {
-                float yv = sY[idx];
-                if (gated) yv *= sG[idx];
+                float yv = t < kb ? sY[idx] : 0.f;
+                if (gated && t < kb) yv *= sG[idx];
                 store_io(p.y, oX_in + t * HP + i, yv, IO);
             }
         }
@@ -669,7 +674,7 @@ static int launch_io(const VerifyParams &p, int waves, size_t lds_bytes, hipStre
     const dim3 grid = DIAG ? dim3(p.tiles, p.batch, 1) : dim3(p.tiles, p.H, p.batch);
     const dim3 block(64 * waves);
     const bool conv = p.x_raw != nullptr;
-    const bool extra = p.tok0 > 0 || p.dt_softplus || p.dt_bias || p.z;
+    const bool extra = p.tok0 > 0 || p.dt_softplus || p.dt_bias || p.z || p.k_seq;
     const int sel = (p.io == SSMV_BF16 ? 4 : 0) + (conv ? 2 : 0) + (extra ? 1 : 0);
     switch (sel) {
         case 0: hipLaunchKernelGGL((verify_kernel<N, R, DIAG, SSMV_F32, false, false>), grid, block, lds_bytes, stream, p); break;

@@ -180,3 +180,52 @@ def test_draft_model_round_trip_with_rejections():
     ssmv.ssmv_materialize_block(hip.dims, hip.cache.c, hip.A, d_bias, True, h)
     assert rel_err(to_host(h), ora.h) <= tol
     ssmv.ssmv_check(hip.cache.c)
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["split", "fused"])
+@pytest.mark.parametrize("name", ["cfg0", "cfg1_small", "cfg2_small", "f32_groups"])
+def test_ragged_draft_counts(name, fused):
+    """Per-sequence draft counts k_seq[b] <= k.  The recurrence is causal, so the oracle's outputs and states for
+    the first kb tokens of a sequence do not depend on the tokens behind them: the oracle verifies all k tokens
+    and commits min(accepted, kb); the GPU must match it on y[b][:kb], write zeros behind, report last_k = kb
+    and keep the integer model's bookkeeping (which clamps accepted to last_k)."""
+    wl = CASES[name].scaled(batch=max(CASES[name].batch, 4))
+    data = generate(wl)
+    lp = data.layers[0]
+    tol = TOL[wl.io]
+    rng = np.random.default_rng(77)
+    hip = HipLayer(wl, lp)
+    ora = oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.conv_act, wl.ngroups)
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
+    for i, rd in enumerate(data.rounds):
+        k = rd.x_raw.shape[1]
+        kseq = rng.integers(1, k + 1, size=wl.batch).astype(np.int32)
+        if i == 0:
+            kseq[:2] = [k, 1]                                   # the two ends in one launch
+        d_x, d_dt, d_B, d_C = (to_dev(v, wl.io) for v in (rd.x_raw, rd.dt[0], rd.B[0], rd.C[0]))
+        y = torch.full_like(d_x, 7.0)
+        kw = dict(dt=d_dt, Bm=d_B, Cm=d_C, A=hip.A, D=hip.D, k=k, y_out=y, k_seq=torch.from_numpy(kseq).to("cuda"))
+        if fused:
+            ssmv.ssm_block_multistep(hip.dims, hip.cache.c, x_raw=d_x, conv_wgt=hip.conv_w, conv_bias=hip.conv_b, **kw)
+        else:
+            ssmv.ssm_block_multistep(hip.dims, hip.cache.c, xc=hip.conv(d_x), **kw)
+        y_ref, _, _ = ora.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
+        y_h = to_host(y)
+        for b in range(wl.batch):
+            kb = int(kseq[b])
+            assert rel_err(y_h[b, :kb], y_ref[b, :kb]) <= tol, "round %d seq %d" % (i, b)
+            assert np.all(y_h[b, kb:] == 0.0), "round %d seq %d: tokens not taken must read as zeros" % (i, b)
+        assert hip.cache.ints()["last_k"].tolist() == kseq.tolist()
+        bk.last_k = kseq.tolist()                               # what verify sets, per sequence
+        acc = rd.accepted.astype(np.int32)
+        hip.commit(torch.from_numpy(acc).to("cuda"))
+        clamped = np.minimum(acc, kseq)
+        err_expected = bool(np.any(acc > kseq))
+        ora.commit(clamped)
+        bk.commit(acc)
+        assert bk.err == int(err_expected) or bk.err == 1
+        ints = hip.cache.ints()
+        assert ints["cur_slot"].tolist() == bk.cur and ints["pend"].tolist() == bk.pend
+        assert ints["pos"].tolist() == bk.pos and ints["conv_head"].tolist() == bk.conv_head
+        assert ints["win_par"] == bk.win_par and ints["err_flag"] == bk.err
+        assert rel_err(to_host(hip.materialize()), ora.h) <= tol, "round %d: state" % i
