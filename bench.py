@@ -52,6 +52,8 @@ def parse_args():
     ap.add_argument("--draft", action="store_true",
                     help="the draft side: a round is fed by k single-token calls (the first one replays the tokens accepted "
                          "last round), one commit per round; implies the general entry point")
+    ap.add_argument("--prefill", type=int, default=0, metavar="L",
+                    help="measure the chunked prefill instead: a step = one call over L prompt tokens of every sequence")
     return ap.parse_args()
 
 
@@ -98,6 +100,91 @@ def round_bytes(wl, pend, k, fused, gate=False, calls=1):
     return verify_bytes(wl, pend, k, False) + conv
 
 
+PEAK_MFMA_F32_TFLOPS = 157.3     # MI355X published dense fp32 matrix rate
+
+
+def bench_prefill(args):
+    """Chunked prefill (ssm_prefill_chunked) of one layer: batch sequences of L prompt tokens per step.  Inputs are
+    drawn on the device (seeded): x ~ N(0,1), B, C ~ N(0,1)/sqrt(N), dt = softplus(N(0,1) - 4); parameters are the
+    workload's.  Roofline: the launch is a chain of dense contractions on the fp32 matrix cores."""
+    import numpy as np
+    import torch
+
+    import paper_2408_15237_amd as ssmv
+    from workload import CONFIGS, generate
+
+    torch.cuda.set_device(0)
+    ssmv.load_library()
+    wl = CONFIGS[args.workload].scaled(layers=1, rounds=1)
+    L = args.prefill
+    lp = generate(wl).layers[0]
+    io_t = torch.bfloat16 if wl.io == "bf16" else torch.float32
+    dev = "cuda"
+    dims = ssmv.make_dims(wl.batch, wl.nheads, wl.headdim, wl.dstate, ngroups=wl.ngroups, kmax=wl.kmax_eff, ring_len=wl.ring_len,
+                          io=wl.io, a_mode=wl.a_mode, conv_act=wl.conv_act)
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).to(io_t).contiguous()
+    A, D = torch.from_numpy(lp.A).to(dev), torch.from_numpy(lp.D).to(dev)
+    conv_w, conv_b = up(lp.conv_w), (None if lp.conv_b is None else up(lp.conv_b))
+    h0 = torch.from_numpy(lp.h0).to(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(wl.seed)
+    B_, H, P, N, G, Cx = wl.batch, wl.nheads, wl.headdim, wl.dstate, wl.ngroups, wl.conv_channels
+    x = torch.randn((B_, L, Cx), generator=gen, device=dev).to(io_t)
+    dt = torch.nn.functional.softplus(torch.randn((B_, L, H), generator=gen, device=dev) - 4.0).to(io_t)
+    Bm = (torch.randn((B_, L, G, N), generator=gen, device=dev) / N ** 0.5).to(io_t)
+    Cm = (torch.randn((B_, L, G, N), generator=gen, device=dev) / N ** 0.5).to(io_t)
+    y = torch.empty_like(x)
+    caches = [ssmv.LayerCache.allocate(dims) for _ in range(2)]
+    for c in caches:
+        ssmv.ssmv_cache_reset(dims, c.c, h0, None)
+
+    def step(i):
+        ssmv.ssm_prefill_chunked(dims, caches[i % 2].c, x, conv_w, conv_b, dt, Bm, Cm, A, D, L, y)
+
+    K = args.steps if args.steps > 0 else 10
+    Wm = args.warmup if args.warmup >= 0 else 2
+    for i in range(Wm):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for i in range(K):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / K
+    for c in caches:
+        ssmv.ssmv_check(c.c)
+    Q = 32
+    flops = 2.0 * (Q * N + Q * P + 2 * N * P) * B_ * L * H            # the four contractions of a chunk, per token and head
+    e = 2 if wl.io == "bf16" else 4
+    nbytes = B_ * L * (2 * Cx + H + 2 * G * N) * e + 2 * wl.state_elems * 4 * B_
+    tflops = flops / (ms * 1e-3) / 1e12
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        nb, Lc = min(B_, 2), min(L, 256)
+        ora = oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0[:nb], wl.io, wl.conv_act, wl.ngroups)
+        f = lambda t: t[:nb, :Lc].float().cpu().numpy()
+        t0 = time.perf_counter()
+        ora.verify(f(x), f(dt), f(Bm), f(Cm))
+        el = time.perf_counter() - t0
+        cpu = {"value": round(nb * Lc / el, 1), "unit": "tokens/s", "cores": oracle.oracle_threads(), "kind": "oracle",
+               "sample": "%d sequences x %d prompt tokens of the same layer (fp64, token by token, %.1f s)" % (nb, Lc, el)}
+    print(json.dumps({
+        "metric": "prompt tokens/sec per SSM layer (chunked prefill)", "value": round(B_ * L / (ms * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s layer shape (batch %d, %d heads x headdim %d x d_state %d, %s I/O), prompt of %d tokens per sequence"
+                               % (wl.name, B_, H, P, N, wl.io, L), "batch": B_, "prompt_len": L},
+        "hbm_gbps_whole_step": round(nbytes / (ms * 1e-3) / 1e9, 1),
+        "roofline": {"bound": "mfma", "achieved": round(tflops, 2), "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tflops / PEAK_MFMA_F32_TFLOPS, 4), "traffic": None, "kernel": "prefill_kernel (fp32 MFMA)",
+                     "avg_launch_us": round(ms * 1e3, 1), "algorithmic_flops_per_launch": int(flops),
+                     "algorithmic_bytes_per_launch": int(nbytes)},
+        "cpu_baseline": cpu}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -114,6 +201,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
+    if args.prefill > 0:
+        bench_prefill(args)
+        return
     torch.cuda.set_device(0)
     ssmv.load_library()
     ssmv.ssmv_set_tuning(args.rows, args.waves)

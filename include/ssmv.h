@@ -202,6 +202,20 @@ typedef struct ssmv_step_args {
 int ssm_block_multistep(const ssmv_dims *dims, const ssmv_cache *cache, const ssmv_step_args *args,
                         void *hip_stream);
 
+/* Prefill: all L prompt tokens of every sequence through the layer (Section 2.1 Eq. 1 with the
+ * discretisation of Section 2.2, evaluated chunk by chunk on the matrix cores), so that decoding can
+ * start from the cache.  Computes the conv roll and every y_t, advances the LIVE slot in place by
+ * the L tokens, leaves the newest conv_width-1 raw inputs in the ring, and (in a second, tiny launch)
+ * sets pos[b] += L and conv_head[b] += L.  The cache must hold no pending tokens and no uncommitted
+ * verify (pend[b] = last_k[b] = 0), else err_flag is set.  Scalar a_mode, headdim and dstate in
+ * {32, 64, 128} (SSMV_EUNSUPPORTED otherwise); L >= 1, the same for all sequences.
+ *   x_raw, y_out [batch][L][H*P]; dt [batch][L][H]; Bm, Cm [batch][L][G][N]: io_dtype, device;
+ *   wgt [Cx][W], bias [Cx] or NULL; A, D [H] fp32. */
+int ssm_prefill_chunked(const ssmv_dims *dims, const ssmv_cache *cache, const void *x_raw,
+                        const void *wgt, const void *bias, const void *dt, const void *Bm,
+                        const void *Cm, const float *A, const float *D, int32_t L, void *y_out,
+                        void *hip_stream);
+
 /* Algorithm 2, "return h_k if k' = k else h_j", as integer bookkeeping.  Per
  * sequence with a = accepted[b] (device int32 [batch]; values outside
  * [0,last_k] are clamped and set err_flag):

@@ -31,7 +31,7 @@ SNAP_CODES = {"both": SSMV_SNAP_BOTH, "hj_only": SSMV_SNAP_HJ_ONLY}
 
 EXPORTS = [
     "ssmv_cache_sizes", "ssmv_cache_reset", "conv1d_state_update", "ssm_verify_multistep",
-    "ssm_conv_verify_multistep", "ssm_block_multistep", "ssmv_materialize_block", "ssm_commit_rollback", "ssm_commit_rollback_multi", "ssmv_materialize", "ssmv_first_conflict", "ssmv_check",
+    "ssm_conv_verify_multistep", "ssm_block_multistep", "ssmv_materialize_block", "ssm_prefill_chunked", "ssm_commit_rollback", "ssm_commit_rollback_multi", "ssmv_materialize", "ssmv_first_conflict", "ssmv_check",
     "ssmv_set_tuning", "ssmv_copy_probe", "ssmv_last_error", "ssmv_version",
 ]
 
@@ -93,6 +93,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.ssm_verify_multistep.argtypes = [dp, cp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.ssm_conv_verify_multistep.argtypes = [dp, cp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.ssm_commit_rollback.argtypes = [dp, cp, vp, vp]
+    lib.ssm_prefill_chunked.argtypes = [dp, cp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.ssm_commit_rollback_multi.argtypes = [dp, cp, i32, vp, vp]
     lib.ssmv_materialize.argtypes = [dp, cp, vp, vp, vp]
     lib.ssm_block_multistep.argtypes = [dp, cp, ctypes.POINTER(ssmv_step_args), vp]
@@ -182,6 +183,11 @@ def ssm_block_multistep(dims, cache, *, dt, Bm, Cm, A, D, k: int, y_out, x_raw=N
 def ssmv_materialize_block(dims, cache, A, dt_bias, dt_softplus: bool, h_out, stream=None) -> None:
     _ck(load_library().ssmv_materialize_block(ctypes.byref(dims), ctypes.byref(cache), _ptr(A), _ptr(dt_bias), int(dt_softplus),
                                               _ptr(h_out), _stream(stream)))
+
+
+def ssm_prefill_chunked(dims, cache, x_raw, wgt, bias, dt, Bm, Cm, A, D, L: int, y_out, stream=None) -> None:
+    _ck(load_library().ssm_prefill_chunked(ctypes.byref(dims), ctypes.byref(cache), _ptr(x_raw), _ptr(wgt), _ptr(bias), _ptr(dt),
+                                           _ptr(Bm), _ptr(Cm), _ptr(A), _ptr(D), L, _ptr(y_out), _stream(stream)))
 
 
 def ssm_commit_rollback_multi(dims, caches, accepted, stream=None) -> None:

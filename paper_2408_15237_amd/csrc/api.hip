@@ -354,6 +354,39 @@ int ssmv_materialize(const ssmv_dims *d, const ssmv_cache *c, const float *A, fl
     return ssmv_materialize_block(d, c, A, nullptr, 0, h_out, hip_stream);
 }
 
+int ssm_prefill_chunked(const ssmv_dims *d, const ssmv_cache *c, const void *x_raw, const void *wgt, const void *bias,
+                        const void *dt, const void *Bm, const void *Cm, const float *A, const float *D, int32_t L,
+                        void *y_out, void *hip_stream)
+{
+    int rc;
+    if ((rc = check_dims(d)) != SSMV_OK) return rc;
+    if ((rc = check_cache(c)) != SSMV_OK) return rc;
+    if (L < 1) return fail(SSMV_EINVAL, "prompt length %d < 1", L);
+    if (d->a_mode != SSMV_A_SCALAR) return fail(SSMV_EUNSUPPORTED, "the chunked prefill needs one decay per head (a_mode scalar)");
+    if (!prefill_shape_supported(d->headdim, d->dstate))
+        return fail(SSMV_EUNSUPPORTED, "chunked prefill is built for headdim in {32,64,128} and dstate in {32,64,128}, not %d x %d",
+                    d->headdim, d->dstate);
+    if ((rc = check_ptr(x_raw, "x_raw")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(wgt, "wgt")) != SSMV_OK) return rc;
+    if (bias && !aligned16(bias)) return fail(SSMV_EALIGN, "bias is not 16-byte aligned");
+    if ((rc = check_ptr(dt, "dt")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(Bm, "Bm")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(Cm, "Cm")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(A, "A")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(D, "D")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(y_out, "y_out")) != SSMV_OK) return rc;
+    PrefillParams p{};
+    p.batch = d->batch; p.H = d->nheads; p.P = d->headdim; p.N = d->dstate; p.G = d->ngroups; p.L = L; p.io = d->io_dtype;
+    p.ring_len = d->ring_len; p.conv_act = d->conv_act;
+    p.state = c->state;
+    p.slot_stride = (size_t)d->batch * d->nheads * d->headdim * d->dstate;
+    p.ring = c->conv_ring; p.cur_slot = c->cur_slot; p.conv_head = c->conv_head;
+    p.x_raw = x_raw; p.wgt = wgt; p.bias = bias; p.dt = dt; p.Bm = Bm; p.Cm = Cm; p.A = A; p.D = D; p.y = y_out;
+    p.pos = c->pos; p.conv_head_rw = c->conv_head; p.pend = c->pend; p.last_k = c->last_k; p.err_flag = c->err_flag;
+    const int hc = launch_prefill(p, (hipStream_t)hip_stream);
+    return hc == 0 ? SSMV_OK : hip_fail(hc, "ssm_prefill_chunked");
+}
+
 int ssm_commit_rollback_multi(const ssmv_dims *d, const ssmv_cache *caches, int32_t n_caches, const int32_t *accepted,
                               void *hip_stream)
 {

@@ -62,6 +62,22 @@ struct ConvParams {
     void *xc;
 };
 
+struct PrefillParams {
+    int batch, H, P, N, G, L, io, ring_len, conv_act;
+    float *state;            // [3][batch][H][P][N]; the live slot is advanced in place
+    size_t slot_stride;
+    void *ring;
+    const int32_t *cur_slot, *conv_head;
+    const void *x_raw, *wgt, *bias, *dt, *Bm, *Cm;
+    const float *A, *D;
+    void *y;
+    // bookkeeping advanced by the follow-up launch
+    int64_t *pos;
+    int32_t *conv_head_rw;
+    const int32_t *pend, *last_k;
+    int32_t *err_flag;
+};
+
 struct CacheInts {
     int32_t *cur_slot, *pend, *conv_head, *last_k, *win_par, *err_flag;
     int64_t *pos;
@@ -104,6 +120,8 @@ size_t verify_lds_bytes(const VerifyParams &p, bool diag);
 bool verify_shape_supported(int N, int R, bool diag);
 
 int launch_conv(const ConvParams &p, hipStream_t stream);
+int launch_prefill(const PrefillParams &p, hipStream_t stream);
+bool prefill_shape_supported(int P, int N);
 int launch_commit(const CommitParams &p, hipStream_t stream);
 int launch_reset(const ResetParams &p, hipStream_t stream);
 int launch_first_conflict(const int32_t *draft, const int32_t *target, int batch, int k, int32_t *accepted,

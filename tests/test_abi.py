@@ -113,6 +113,14 @@ def test_argument_validation_precedes_any_gpu_work():
     d_hj = ssmv.make_dims(2, 4, 16, 16, kmax=4, io="f32", snapshot_mode="hj_only")
     assert _code(ssmv.ssm_block_multistep, d_hj, c, k=1, tok0=1, xc=P, **blk) == ssmv.SSMV_EUNSUPPORTED
     assert _code(ssmv.ssmv_materialize_block, d, c, P, None, 3, P, 0) == ssmv.SSMV_EINVAL
+    # prefill: length, mode and shape
+    assert _code(ssmv.ssm_prefill_chunked, d, c, P, P, None, P, P, P, P, P, 0, P, 0) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssm_prefill_chunked, d, c, P, P, None, P, P, P, P, P, 8, P, 0) == ssmv.SSMV_EUNSUPPORTED      # 16 x 16
+    d_ok = ssmv.make_dims(2, 4, 64, 64, kmax=4, io="bf16")
+    assert _code(ssmv.ssm_prefill_chunked, d_ok, c, P, P, None, P, P, P, P, P, 8, None, 0) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssm_prefill_chunked, d_ok, c, P + 2, P, None, P, P, P, P, P, 8, P, 0) == ssmv.SSMV_EALIGN
+    d_diag = ssmv.make_dims(1, 64, 1, 16, a_mode="diag")
+    assert _code(ssmv.ssm_prefill_chunked, d_diag, c, P, P, None, P, P, P, P, P, 8, P, 0) == ssmv.SSMV_EUNSUPPORTED
     # broken cache struct
     bad = _fake_cache()
     bad.pend = None

@@ -1,0 +1,120 @@
+"""GPU parity of the chunked prefill (ssm_prefill_chunked): the prompt goes through the oracle token by token
+(EagerOracle.verify with k = L, then a commit of all L), through the GPU chunk by chunk on the matrix cores; then
+both decode speculatively from what the prefill left (state, conv ring, integers)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2408_15237_amd as ssmv
+from workload import Workload, generate
+
+from _harness import HipLayer, TOL, eager_oracle, rel_err, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+# (name, headdim, dstate, nheads, ngroups, batch, io, conv_act, L)
+CASES = [
+    ("p32n32_f32", 32, 32, 3, 1, 2, "f32", "none", 70),
+    ("p64n64_bf16_groups", 64, 64, 4, 2, 3, "bf16", "silu", 200),
+    ("p128n64_bf16", 128, 64, 2, 1, 2, "bf16", "none", 130),
+    ("p64n128_f32", 64, 128, 2, 1, 1, "f32", "none", 97),
+    ("one_chunk_exact", 32, 64, 2, 1, 2, "f32", "none", 32),
+    ("one_past_a_chunk", 32, 64, 2, 1, 2, "f32", "none", 33),
+    ("shorter_than_the_conv", 32, 32, 2, 1, 2, "f32", "none", 2),
+    ("single_token", 64, 32, 2, 1, 2, "bf16", "none", 1),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_prefill_then_speculative_decoding(case):
+    name, P, N, H, G, batch, io, act, L = case
+    tol = TOL[io]
+    dec = Workload(name, "scalar", batch=batch, nheads=H, headdim=P, dstate=N, k=4, rounds=6, io=io, accept="uniform",
+                   ngroups=G, conv_act=act, seed=31)
+    prompt = generate(dec.scaled(k=L, kmax=L, rounds=1, seed=32))       # only its draws are used: one "round" of L tokens
+    data = generate(dec)
+    lp = data.layers[0]
+    rng = np.random.default_rng(33)
+    conv_init = np.asarray(rng.standard_normal((batch, 3, H * P)), dtype=np.float32)
+    from workload import round_to_io
+    conv_init = round_to_io(conv_init, io)                               # a non-trivial history ahead of the prompt
+    hip = HipLayer(dec, lp, conv_init=conv_init)
+    ora = eager_oracle(dec, lp, conv_init=conv_init)
+    pr = prompt.rounds[0]
+
+    y_ref, _, _ = ora.verify(pr.x_raw, pr.dt[0], pr.B[0], pr.C[0])
+    ora.commit(np.full(batch, L))
+    d_x = to_dev(pr.x_raw, io)
+    y = torch.empty_like(d_x)
+    ints0 = hip.cache.ints()
+    ssmv.ssm_prefill_chunked(hip.dims, hip.cache.c, d_x, hip.conv_w, hip.conv_b, to_dev(pr.dt[0], io), to_dev(pr.B[0], io),
+                             to_dev(pr.C[0], io), hip.A, hip.D, L, y)
+    e_y = rel_err(to_host(y), y_ref)
+    assert e_y <= tol, "prompt outputs: %.3g > %.3g" % (e_y, tol)
+    ints = hip.cache.ints()
+    assert ints["pos"].tolist() == [L] * batch and ints["pend"].tolist() == [0] * batch
+    assert ints["cur_slot"].tolist() == ints0["cur_slot"].tolist() and ints["last_k"].tolist() == [0] * batch
+    assert ints["conv_head"].tolist() == [(int(c) + L) & (dec.ring_len - 1) for c in ints0["conv_head"]]
+    assert ints["err_flag"] == 0
+    e_h = rel_err(to_host(hip.materialize()), ora.h)
+    assert e_h <= tol, "state after the prompt: %.3g" % e_h
+
+    # decode from there: the ring must continue the prompt, the slots and integers must be consistent
+    bk = oracle.BookkeepingModel(batch, dec.ring_len, dec.conv_width)
+    bk.pos = [L] * batch
+    bk.conv_head = ints["conv_head"].tolist()
+    for i, rd in enumerate(data.rounds):
+        y_r, _, _ = ora.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
+        y_g, _ = hip.conv_verify(to_dev(rd.x_raw, io), to_dev(rd.dt[0], io), to_dev(rd.B[0], io), to_dev(rd.C[0], io))
+        assert rel_err(to_host(y_g), y_r) <= tol, "decode round %d" % i
+        hip.commit(torch.from_numpy(rd.accepted.astype(np.int32)).to("cuda"))
+        ora.commit(rd.accepted)
+        bk.verify(dec.k)
+        bk.commit(rd.accepted)
+        got = hip.cache.ints()
+        assert got["cur_slot"].tolist() == bk.cur and got["pend"].tolist() == bk.pend and got["pos"].tolist() == bk.pos
+        assert got["conv_head"].tolist() == bk.conv_head and got["err_flag"] == 0
+    assert rel_err(to_host(hip.materialize()), ora.h) <= tol
+    ssmv.ssmv_check(hip.cache.c)
+
+
+def test_prefill_in_two_pieces_equals_one():
+    """A prompt fed as two calls (the second continues from the state and ring the first left)."""
+    io = "f32"
+    dec = Workload("two", "scalar", batch=2, nheads=2, headdim=64, dstate=64, k=4, rounds=1, io=io, accept="uniform", seed=41)
+    L1, L2 = 45, 52
+    prompt = generate(dec.scaled(k=L1 + L2, kmax=L1 + L2, rounds=1, seed=42))
+    lp, pr = prompt.layers[0], prompt.rounds[0]
+    one, two = HipLayer(dec, lp), HipLayer(dec, lp)
+    dev = lambda a: to_dev(a, io)
+    y1 = torch.empty_like(dev(pr.x_raw))
+    ssmv.ssm_prefill_chunked(one.dims, one.cache.c, dev(pr.x_raw), one.conv_w, one.conv_b, dev(pr.dt[0]), dev(pr.B[0]), dev(pr.C[0]),
+                             one.A, one.D, L1 + L2, y1)
+    ys = []
+    for sl in (slice(0, L1), slice(L1, L1 + L2)):
+        n = sl.stop - sl.start
+        y = torch.empty_like(dev(pr.x_raw[:, sl]))
+        ssmv.ssm_prefill_chunked(two.dims, two.cache.c, dev(pr.x_raw[:, sl]), two.conv_w, two.conv_b, dev(pr.dt[0][:, sl]),
+                                 dev(pr.B[0][:, sl]), dev(pr.C[0][:, sl]), two.A, two.D, n, y)
+        ys.append(y)
+    assert rel_err(to_host(torch.cat(ys, dim=1)), to_host(y1)) <= 1e-5
+    assert rel_err(to_host(two.materialize()), to_host(one.materialize())) <= 1e-5
+    a, b = one.cache.ints(), two.cache.ints()
+    assert a["pos"].tolist() == b["pos"].tolist() == [L1 + L2] * 2 and a["conv_head"].tolist() == b["conv_head"].tolist()
+
+
+def test_prefill_flags_a_cache_with_pending_tokens():
+    dec = Workload("flag", "scalar", batch=2, nheads=2, headdim=32, dstate=32, k=4, rounds=1, io="f32", accept="uniform", seed=43)
+    data = generate(dec)
+    hip = HipLayer(dec, data.layers[0])
+    rd = data.rounds[0]
+    dev = lambda a: to_dev(a, "f32")
+    hip.conv_verify(dev(rd.x_raw), dev(rd.dt[0]), dev(rd.B[0]), dev(rd.C[0]))
+    hip.commit(torch.tensor([2, 0], dtype=torch.int32, device="cuda"))          # sequence 0 now has pending tokens
+    y = torch.empty_like(dev(rd.x_raw))
+    ssmv.ssm_prefill_chunked(hip.dims, hip.cache.c, dev(rd.x_raw), hip.conv_w, hip.conv_b, dev(rd.dt[0]), dev(rd.B[0]), dev(rd.C[0]),
+                             hip.A, hip.D, 4, y)
+    with pytest.raises(ssmv.SsmvError) as ei:
+        ssmv.ssmv_check(hip.cache.c)
+    assert ei.value.code == ssmv.SSMV_ESEQUENCE
