@@ -12,20 +12,26 @@
 // scan; the paper's own prefill uses the hardware-aware scan of its reference [Mamba]).  One workgroup of four
 // waves owns one (sequence, head); the state stays in LDS across the chunks, the chunk's X, B, C in LDS as fp32.
 // v_mfma_f32_32x32x2_f32 operands: A[i = lane%32][k = lane/32], B[k = lane/32][j = lane%32]; result register v of
-// a lane is D[8*(v/4) + 4*(lane/32) + v%4][lane%32].  Rows of the LDS arrays that are read with the lane as the
-// ROW index are padded by one float, so that the 32 lanes hit 32 banks.
+// a lane is D[8*(v/4) + 4*(lane/32) + v%4][lane%32]; v_mfma_f32_16x16x4_f32 (used for the Q x Q product, one
+// quadrant per wave): A[i = lane%16][k = lane/16], B[k = lane/16][j = lane%16], D[4*(lane/16) + v][lane%16].  Rows of
+// the LDS arrays that are read with the lane as the ROW index are padded by one float, so that the lanes hit
+// different banks.
+// The global loads of chunk c+1 are issued (as raw bits, unconditionally, from clamped addresses) right after the
+// barrier that ends the staging of chunk c and are decoded into LDS after chunk c's arithmetic: one chunk of
+// latency hiding for a kernel that would otherwise wait for memory once per chunk.
 #include "ssmv_internal.h"
 
 namespace ssmv {
 
 typedef float f16v __attribute__((ext_vector_type(16)));
+typedef float f4v __attribute__((ext_vector_type(4)));
 
 constexpr int kQ = 32;     // tokens per chunk
 
 template <int P, int N>
 __host__ __device__ constexpr size_t prefill_lds_floats()
 {
-    return (size_t)P * (N + 1) + (size_t)kQ * P + 2 * (size_t)kQ * (N + 1) + (size_t)kQ * (kQ + 1) + 2 * kQ;
+    return (size_t)P * (N + 1) + (size_t)kQ * P + 2 * (size_t)kQ * (N + 1) + (size_t)kQ * (kQ + 1) + 4 * kQ;
 }
 
 template <int P, int N, int IO>
@@ -49,6 +55,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
     float *sM = sC + Q * NP;                            // [Q][Q+1]
     float *sDt = sM + Q * QP;                           // [Q]
     float *sCum = sDt + Q;                              // [Q]  inclusive prefix of dt*A
+    float *sAt = sCum + Q;                              // [Q]  exp(cum_t): decay from the chunk's start to after token t
+    float *sW = sAt + Q;                                // [Q]  exp(cum_Q - cum_s) dt_s: weight of token s in the chunk's state update
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lk = lane >> 5;           // MFMA: row/column index and k index of this lane
@@ -76,88 +84,132 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
 #pragma unroll
     for (int w = 0; w < W; ++w) wgt[w] = load_io(p.wgt, (size_t)ch * W + w, IO);
     const float cbias = p.bias ? load_io(p.bias, ch, IO) : 0.f;
-    // raw conv input of global token tg for this channel: the ring for tokens before the prompt, zero past its end
-    auto raw_at = [&](int tg) {
-        if (tg >= L) return 0.f;
-        if (tg < 0) return load_io(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 + tg) & mask)) * HP + ch, IO);
-        return load_io(p.x_raw, ((size_t)b * L + tg) * HP + ch, IO);
+    // raw conv input of prompt token tg for this channel (bits), from a clamped address: a token before the prompt is
+    // replaced by the ring history below, one past the end is zeroed when it is used.  (One base pointer only: a
+    // select between two gets compiled into two loads and a select of their results, with a wait on the spot.)
+    auto raw_bits = [&](int tg) {
+        const int tc = tg < 0 ? 0 : (tg < L ? tg : L - 1);
+        return Vec::load_raw1(p.x_raw, ((size_t)b * L + tc) * HP + ch);
     };
-
-    const int n_chunks = (L + Q - 1) / Q;
-    for (int c = 0; c < n_chunks; ++c) {
-        const int t0 = c * Q;
-        // ---- staging ------------------------------------------------------------------------------
-        {
-            const int s0 = sg * QS;
-            float t1 = raw_at(t0 + s0 - 3), t2 = raw_at(t0 + s0 - 2), t3 = raw_at(t0 + s0 - 1);
+    // the W-1 raw inputs ahead of the prompt (newest last)
+    float hist[W - 1];
 #pragma unroll
-            for (int j = 0; j < QS; ++j) {
-                const int tg = t0 + s0 + j;
-                const float r = raw_at(tg);
-                // same fp32 order and rounding as conv1d_state_update
-                float acc = cbias;
-                acc = fmaf(wgt[0], t1, acc);
-                acc = fmaf(wgt[1], t2, acc);
-                acc = fmaf(wgt[2], t3, acc);
-                acc = fmaf(wgt[3], r, acc);
-                if (p.conv_act == SSMV_ACT_SILU) acc = acc / (1.f + expf(-acc));
-                if (IO == SSMV_BF16) acc = bf16_bits_to_f32(f32_to_bf16_bits(acc));
-                sX[(s0 + j) * P + pc] = tg < L ? acc : 0.f;
-                t1 = t2; t2 = t3; t3 = r;
-            }
+    for (int j = 0; j < W - 1; ++j)
+        hist[j] = load_io(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 - (W - 1) + j) & mask)) * HP + ch, IO);
+    constexpr int BI = (Q * (N / EV) + 255) / 256;      // 16-byte B (and C) vectors per thread and chunk
+    struct Fetch { uint32_t x[QS + W - 1]; uint4 bv[BI], cv[BI]; uint32_t dt; };
+    auto prefetch = [&](int c, Fetch &f) {
+        const int t0 = c * Q, s0 = sg * QS;
+#pragma unroll
+        for (int j = 0; j < QS + W - 1; ++j) f.x[j] = raw_bits(t0 + s0 - (W - 1) + j);
+#pragma unroll
+        for (int i = 0; i < BI; ++i) {
+            const int item = tid + i * 256;
+            const int s_ = item / (N / EV), n = (item % (N / EV)) * EV;
+            const int tg = t0 + (s_ < Q ? s_ : Q - 1);
+            const size_t o = ((size_t)b * L + (tg < L ? tg : L - 1)) * GN + (size_t)g * N + n;
+            f.bv[i] = Vec::load_raw(p.Bm, o);
+            f.cv[i] = Vec::load_raw(p.Cm, o);
         }
-        for (int item = tid; item < Q * (N / EV); item += 256) {
-            const int s = item / (N / EV), n = (item % (N / EV)) * EV;
-            const int tg = t0 + s;
-            float bv[EV], cv[EV];
-            if (tg < L) {
-                const size_t o = ((size_t)b * L + tg) * GN + (size_t)g * N + n;
-                Vec::load(p.Bm, o, bv);
-                Vec::load(p.Cm, o, cv);
-            } else {
+        const int tq = t0 + (tid & (Q - 1));
+        f.dt = Vec::load_raw1(p.dt, ((size_t)b * L + (tq < L ? tq : L - 1)) * H + hd);
+    };
+    auto consume = [&](int c, const Fetch &f) {
+        const int t0 = c * Q, s0 = sg * QS;
+        float tap[W - 1];
 #pragma unroll
-                for (int e = 0; e < EV; ++e) bv[e] = cv[e] = 0.f;
-            }
+        for (int j = 0; j < W - 1; ++j) {
+            const int tg = t0 + s0 - (W - 1) + j;       // < 0 only in the first chunk: -(W-1)+j, i.e. hist[j]
+            tap[j] = tg < 0 ? hist[j] : Vec::decode1(f.x[j]);
+        }
+        float t1 = tap[0], t2 = tap[1], t3 = tap[2];
 #pragma unroll
-            for (int e = 0; e < EV; ++e) {
-                sB[s * NP + n + e] = bv[e];
-                sC[s * NP + n + e] = cv[e];
+        for (int j = 0; j < QS; ++j) {
+            const int tg = t0 + s0 + j;
+            const float r = Vec::decode1(f.x[j + W - 1]);
+            // same fp32 order and rounding as conv1d_state_update
+            float acc = cbias;
+            acc = fmaf(wgt[0], t1, acc);
+            acc = fmaf(wgt[1], t2, acc);
+            acc = fmaf(wgt[2], t3, acc);
+            acc = fmaf(wgt[3], r, acc);
+            if (p.conv_act == SSMV_ACT_SILU) acc = acc / (1.f + expf(-acc));
+            if (IO == SSMV_BF16) acc = bf16_bits_to_f32(f32_to_bf16_bits(acc));
+            sX[(s0 + j) * P + pc] = tg < L ? acc : 0.f;
+            t1 = t2; t2 = t3; t3 = r;
+        }
+#pragma unroll
+        for (int i = 0; i < BI; ++i) {
+            const int item = tid + i * 256;
+            if (item < Q * (N / EV)) {
+                const int s_ = item / (N / EV), n = (item % (N / EV)) * EV;
+                const bool live = t0 + s_ < L;
+                float bv[EV], cv[EV];
+                Vec::decode(f.bv[i], bv);
+                Vec::decode(f.cv[i], cv);
+#pragma unroll
+                for (int e = 0; e < EV; ++e) {
+                    sB[s_ * NP + n + e] = live ? bv[e] : 0.f;
+                    sC[s_ * NP + n + e] = live ? cv[e] : 0.f;
+                }
             }
         }
         if (tid < Q) {
-            const int tg = t0 + tid;
-            const float d = tg < L ? load_io(p.dt, ((size_t)b * L + tg) * H + hd, IO) : 0.f;   // padding: no decay, no input
+            const float d = t0 + tid < L ? Vec::decode1(f.dt) : 0.f;                         // padding: no decay, no input
             float v = d * A_h;
 #pragma unroll
             for (int off = 1; off < Q; off <<= 1) {
                 const float u = __shfl_up(v, off, 64);
                 if (tid >= off) v += u;
             }
+            const float cq = __shfl(v, Q - 1, 64);
             sDt[tid] = d;
             sCum[tid] = v;
+            sAt[tid] = expf(v);
+            sW[tid] = expf(cq - v) * d;
         }
-        __syncthreads();
+    };
 
-        // ---- G = C B^T, masked and scaled into M (wave 0); Y <- diag(exp(cum)) C h^T (every wave its tile) ----
-        if (wave == 0) {
-            f16v gacc = {0};
-            for (int kk = 0; kk < N / 2; ++kk) {
-                const int n = 2 * kk + lk;
-                gacc = __builtin_amdgcn_mfma_f32_32x32x2f32(sC[li * NP + n], sB[li * NP + n], gacc, 0, 0, 0);
-            }
-            const float cs = sCum[li], ds = sDt[li];
+    const int n_chunks = (L + Q - 1) / Q;
+    Fetch fetch;
+    prefetch(0, fetch);
+    for (int c = 0; c < n_chunks; ++c) {
+        const int t0 = c * Q;
+        consume(c, fetch);
+        __syncthreads();
+        if (c + 1 < n_chunks) prefetch(c + 1, fetch);
+        __builtin_amdgcn_sched_barrier(0);              // the loads stay here, a whole chunk of arithmetic ahead of their use
+
+        // ---- G = C B^T, one 16x16 quadrant per wave, masked and scaled into M; Y <- diag(exp(cum)) C h^T -----------
+        {
+            const int qi = wave >> 1, qj = wave & 1;        // rows t in [16 qi, +16), columns s in [16 qj, +16)
+            const int l16 = lane & 15, k4 = lane >> 4;
+            const int srow = qj * 16 + l16;
+            if (qj <= qi) {                                 // the upper-right quadrant is all s > t
+                f4v gacc = {0};
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int t = 8 * (v / 4) + 4 * lk + (v % 4);
-                const bool keep = li <= t;
-                const float dec = expf(keep ? sCum[t] - cs : 0.f);
-                sM[t * QP + li] = keep ? gacc[v] * dec * ds : 0.f;
+                for (int kk = 0; kk < N / 4; ++kk) {
+                    const int n = 4 * kk + k4;
+                    gacc = __builtin_amdgcn_mfma_f32_16x16x4f32(sC[(qi * 16 + l16) * NP + n], sB[srow * NP + n], gacc, 0, 0, 0);
+                }
+                const float cs = sCum[srow], ds = sDt[srow];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int t = qi * 16 + 4 * k4 + v;
+                    const bool keep = srow <= t;
+                    const float dec = expf(keep ? sCum[t] - cs : 0.f);
+                    sM[t * QP + srow] = keep ? gacc[v] * dec * ds : 0.f;
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) sM[(qi * 16 + 4 * k4 + v) * QP + srow] = 0.f;
             }
         }
         f16v yacc = {0};
         if (wave < TP) {
-            const float at = expf(sCum[li]);
+            const float at = sAt[li];
             const float *hrow = sH + (wave * 32 + li) * NP;
+#pragma unroll
             for (int kk = 0; kk < N / 2; ++kk) {
                 const int n = 2 * kk + lk;
                 yacc = __builtin_amdgcn_mfma_f32_32x32x2f32(sC[li * NP + n] * at, hrow[n], yacc, 0, 0, 0);
@@ -168,26 +220,49 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
         // ---- Y += M X, + D X, store ------------------------------------------------------------------
         if (wave < TP) {
             const int pcol = wave * 32 + li;
+#pragma unroll
             for (int kk = 0; kk < Q / 2; ++kk) {
                 const int s = 2 * kk + lk;
                 yacc = __builtin_amdgcn_mfma_f32_32x32x2f32(sM[li * QP + s], sX[s * P + pcol], yacc, 0, 0, 0);
             }
+            // bf16 outputs go through LDS (the C rows are free between the second and third barrier of a chunk) so
+            // that a lane writes two 16-byte pieces of a token's row instead of sixteen 2-byte elements
+            constexpr bool VIA_LDS = IO == SSMV_BF16 && (size_t)Q * NP * sizeof(float) >= 4u * 32u * 32u * sizeof(uint16_t);
+            if constexpr (VIA_LDS) {
+                uint16_t *tile = reinterpret_cast<uint16_t *>(sC) + wave * (32 * 32);      // [t][32 columns of this wave]
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int t = 8 * (v / 4) + 4 * lk + (v % 4);
-                if (t0 + t < L) store_io(p.y, ((size_t)b * L + t0 + t) * HP + hd * P + pcol, fmaf(D_h, sX[t * P + pcol], yacc[v]), IO);
+                for (int v = 0; v < 16; ++v) {
+                    const int t = 8 * (v / 4) + 4 * lk + (v % 4);
+                    tile[t * 32 + li] = f32_to_bf16_bits(fmaf(D_h, sX[t * P + pcol], yacc[v]));
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int idx = lane + 64 * i, t = idx >> 2, part = idx & 3;
+                    const uint4 v16 = *reinterpret_cast<const uint4 *>(tile + t * 32 + part * 8);
+                    if (t0 + t < L)
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.y) + ((size_t)b * L + t0 + t) * HP + hd * P + wave * 32 + part * 8) = v16;
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int t = 8 * (v / 4) + 4 * lk + (v % 4);
+                    if (t0 + t < L) store_io(p.y, ((size_t)b * L + t0 + t) * HP + hd * P + pcol, fmaf(D_h, sX[t * P + pcol], yacc[v]), IO);
+                }
             }
         }
         // ---- h <- exp(cum_Q) h + (diag(w) X)^T B, tile by tile ---------------------------------------------
         {
-            const float cq = sCum[Q - 1];
-            const float aq = expf(cq);
+            const float aq = sAt[Q - 1];
             for (int tile = wave; tile < TP * TN; tile += 4) {
                 const int tp = tile / TN, tn = tile % TN;
                 f16v sacc = {0};
+#pragma unroll
                 for (int kk = 0; kk < Q / 2; ++kk) {
                     const int s = 2 * kk + lk;
-                    const float ws = expf(cq - sCum[s]) * sDt[s];
+                    const float ws = sW[s];
                     sacc = __builtin_amdgcn_mfma_f32_32x32x2f32(sX[s * P + tp * 32 + li] * ws, sB[s * NP + tn * 32 + li], sacc, 0, 0, 0);
                 }
 #pragma unroll
@@ -208,7 +283,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
     }
     if (tid < P) {
         for (int tg = (L - (W - 1) > 0 ? L - (W - 1) : 0); tg < L; ++tg)
-            store_io(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 + tg) & mask)) * HP + ch, raw_at(tg), IO);
+            Vec::store_raw1(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 + tg) & mask)) * HP + ch, raw_bits(tg));
     }
 }
 
