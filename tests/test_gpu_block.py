@@ -41,6 +41,7 @@ CASES = {
     "cfg2_small": CONFIGS["cfg2"].scaled(nheads=192, rounds=10),
     "f32_groups": CONFIGS["cfg0"].scaled(io="f32", ngroups=2, nheads=4, batch=5, k=3, kmax=5, rounds=10),
     "ragged_rows": CONFIGS["cfg0"].scaled(headdim=24, dstate=32, batch=3, rounds=8),
+    "cfg1_full": CONFIGS["cfg1"].scaled(rounds=8),              # the 8B-shaped layer at its full size, every element
 }
 
 

@@ -118,3 +118,34 @@ def test_prefill_flags_a_cache_with_pending_tokens():
     with pytest.raises(ssmv.SsmvError) as ei:
         ssmv.ssmv_check(hip.cache.c)
     assert ei.value.code == ssmv.SSMV_ESEQUENCE
+
+
+def test_prefill_full_layer_shape_sampled():
+    """The bench's launch shape (cfg3 layer: 32 heads x 128 x 64, bf16 I/O, 2048 prompt tokens) at batch 4; the oracle
+    runs the token-by-token scan on sampled (sequence, head) pairs - they are independent recurrences."""
+    from workload import CONFIGS, round_to_io
+    from _harness import slice_workload
+    io = "bf16"
+    L = 2048
+    dec = CONFIGS["cfg3"].scaled(batch=4, rounds=1)
+    lp = generate(dec).layers[0]
+    rng = np.random.default_rng(51)
+    B_, H, P, N = dec.batch, dec.nheads, dec.headdim, dec.dstate
+    x = round_to_io(rng.standard_normal((B_, L, H * P), dtype=np.float32), io)
+    dt = round_to_io(np.logaddexp(0, rng.standard_normal((B_, L, H), dtype=np.float32) - 4.0), io)
+    Bm = round_to_io(rng.standard_normal((B_, L, 1, N), dtype=np.float32) / np.sqrt(N), io)
+    Cm = round_to_io(rng.standard_normal((B_, L, 1, N), dtype=np.float32) / np.sqrt(N), io)
+    hip = HipLayer(dec, lp)
+    y = torch.empty((B_, L, H * P), dtype=torch.bfloat16, device="cuda")
+    ssmv.ssm_prefill_chunked(hip.dims, hip.cache.c, to_dev(x, io), hip.conv_w, hip.conv_b, to_dev(dt, io), to_dev(Bm, io),
+                             to_dev(Cm, io), hip.A, hip.D, L, y)
+    seqs, heads = [0, 3], [0, 13, 31]
+    ch = np.concatenate([np.arange(h * P, (h + 1) * P) for h in heads])
+    ora = oracle.EagerOracle("scalar", lp.A[heads], lp.D[heads], lp.conv_w[ch], lp.conv_b[ch], lp.h0[seqs][:, heads], io)
+    y_ref, _, _ = ora.verify(x[seqs][:, :, ch], dt[seqs][:, :, heads], Bm[seqs], Cm[seqs])
+    ora.commit(np.full(len(seqs), L))
+    e_y = rel_err(to_host(y)[seqs][:, :, ch], y_ref)
+    e_h = rel_err(to_host(hip.materialize())[seqs][:, heads], ora.h)
+    print("prefill cfg3 shape, L=2048: y error %.3g, state error %.3g" % (e_y, e_h))
+    assert e_y <= TOL[io] and e_h <= TOL[io]
+    assert hip.cache.ints()["pos"].tolist() == [L] * B_ and hip.cache.ints()["err_flag"] == 0
