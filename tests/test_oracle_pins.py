@@ -317,3 +317,34 @@ def test_eager_oracle_block_pieces_compose_with_the_plain_scan():
     y_ref, snap_ref = oracle.scan_tokens("scalar", d["h0"], oracle.round_io(d["x"], "f32"), dt, d["B"], d["C"], d["A"], d["D"])
     np.testing.assert_allclose(snap, snap_ref, rtol=1e-12, atol=1e-14)       # the gate leaves the state alone
     np.testing.assert_allclose(y, y_ref * z / (1 + np.exp(-z)), rtol=1e-12, atol=1e-14)
+
+
+# ---- hand-worked examples stored as text fixtures -------------------------------------------------------
+
+def _read_fixture(name):
+    import os
+    out = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", name)):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, val = line.split(":", 1)
+        out[key.strip()] = [[float(v) for v in part.split()] for part in val.split("|")]
+    return out
+
+
+def test_hand_worked_examples():
+    f = _read_fixture("recurrence_halving_decay.txt")
+    k = len(f["dt"][0])
+    A = np.array([f["A_over_ln2"][0][0] * np.log(2.0)])
+    Bm = np.tile(np.array(f["B"][0]), (1, k, 1, 1))
+    Cm = np.tile(np.array(f["C"][0]), (1, k, 1, 1))
+    y, snap = oracle.scan_tokens("scalar", np.array(f["h0"][0]).reshape(1, 1, 1, 2), np.array(f["x"][0]).reshape(1, k, 1),
+                                 np.array(f["dt"][0]).reshape(1, k, 1), Bm, Cm, A, np.array(f["D"][0]))
+    np.testing.assert_allclose(y.reshape(-1), f["y"][0], rtol=1e-13)
+    np.testing.assert_allclose(snap[1:].reshape(k, 2), np.array(f["h_after"]), rtol=1e-13)
+    np.testing.assert_allclose(snap[0].reshape(-1), f["h0"][0], rtol=0)
+    c = _read_fixture("conv_width4.txt")
+    raw = np.array(c["history"][0] + c["x"][0]).reshape(1, -1, 1)
+    xc = oracle.conv_causal(raw, np.array(c["taps"][0]).reshape(1, 4), np.array(c["bias"][0]), "none", "f32")
+    np.testing.assert_allclose(xc.reshape(-1), c["xc"][0], rtol=0, atol=0)
