@@ -132,13 +132,21 @@ int launch_copy_probe(const void *src, void *dst0, void *dst1, size_t n_bytes, h
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
 
-// round-to-nearest-even; NaN stays NaN
+// round-to-nearest-even; NaN stays NaN.  One v_cvt_pk_bf16_f32 on gfx950.
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    const __bf16 r = static_cast<__bf16>(f);
+    return __builtin_bit_cast(uint16_t, r);
+}
+
+// two values into one 32-bit word (first in the low half): one instruction
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef float f2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 b2_t __attribute__((ext_vector_type(2)));
+    const f2_t v = {lo, hi};
+    const b2_t r = __builtin_convertvector(v, b2_t);
+    return __builtin_bit_cast(uint32_t, r);
 }
 
 __device__ __forceinline__ float load_io(const void *base, size_t idx, int io)
@@ -218,7 +226,7 @@ struct IoVec<SSMV_BF16> {
     {
         uint32_t w[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16_bits(v[2 * i]) | ((uint32_t)f32_to_bf16_bits(v[2 * i + 1]) << 16);
+        for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
         return make_uint4(w[0], w[1], w[2], w[3]);
     }
     static __device__ __forceinline__ uint32_t load_raw1(const void *base, size_t idx) { return reinterpret_cast<const uint16_t *>(base)[idx]; }
@@ -238,7 +246,7 @@ struct IoVec<SSMV_BF16> {
     {
         uint32_t w[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16_bits(v[2 * i]) | ((uint32_t)f32_to_bf16_bits(v[2 * i + 1]) << 16);
+        for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
         *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(base) + idx) = make_uint4(w[0], w[1], w[2], w[3]);
     }
 };
@@ -274,7 +282,7 @@ struct XVec<SSMV_BF16, 2> {
     }
     static __device__ __forceinline__ Raw encode(const float (&v)[2])
     {
-        return (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
+        return pack_bf16x2(v[0], v[1]);
     }
 };
 
