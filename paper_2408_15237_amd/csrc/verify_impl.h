@@ -78,7 +78,7 @@ __host__ __device__ constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v
 // LDS plan (floats).  T = lds_tokens.
 //   sB   [T][N]        B of every token (pending first, then drafts)
 //   sC   [k][N]        C of the drafts
-//   sDec [T]           scalar mode: exp(dt*A) per token, then dt [T] behind it
+//   sDec               scalar mode: dt per token [T]; diag mode: dt per (token,row) [T][rows_wg]
 //   sDt  [T][rows_wg]  diag mode: dt per (token,row)
 //   sDtx [T][rows_wg]  diag mode: dt*x per (token,row); scalar mode: x (dt is one number per token and is
 //                      folded into B in the step instead, so the x items never wait for or touch dt)
@@ -88,7 +88,7 @@ template <bool DIAG>
 __host__ __device__ inline size_t verify_lds_floats(int T, int k, int N, int rows_wg, bool gated)
 {
     size_t n = (size_t)T * N + (size_t)k * N + (size_t)T * rows_wg + (size_t)k * rows_wg;
-    n += DIAG ? (size_t)T * rows_wg : 2 * (size_t)((T + 3) & ~3);
+    n += DIAG ? (size_t)T * rows_wg : (size_t)((T + 3) & ~3);
     if (gated) n += (size_t)k * rows_wg;
     return n;
 }
@@ -188,8 +188,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     float *sB = lds;
     float *sC = sB + TL * N;
     float *sDec = sC + k * N;                                          // scalar: [T]; diag: sDt [T][rows_wg]
-    float *sDtF = sDec + ((TL + 3) & ~3);                              // scalar: dt [T]
-    float *sDtx = sDec + (DIAG ? TL * rows_wg : 2 * ((TL + 3) & ~3));
+    float *sDtF = sDec;                                                // scalar: dt [T]
+    float *sDtx = sDec + (DIAG ? TL * rows_wg : ((TL + 3) & ~3));
     float *sY = sDtx + TL * rows_wg;
     float *sG = sY + k * rows_wg;                                      // only with a gate
 
@@ -390,7 +390,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     auto dec_use = [&](int tt, uint32_t raw) {
         if (tt >= pd && first_tile && !materialize) Vec::store_raw1(winDt_out, oDt_wout + (tt - pd) * H, raw);
         const float d = dt_fix(Vec::decode1(raw), dtb_h);
-        sDec[tt] = expf(d * A_h);
         sDtF[tt] = d;
     };
 
@@ -497,7 +496,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         for (int v = 0; v < V; ++v) Bv[v] = *reinterpret_cast<const v4f *>(sB + tt * N + v * (LPR * 4) + sub * 4);
         float dec = 0.f;
         if constexpr (!DIAG) {
-            dec = sDec[tt];
+            dec = expf(sDtF[tt] * A_h);                  // only the rare plain step of scalar mode gets here
             const float dts = sDtF[tt];
 #pragma unroll
             for (int v = 0; v < V; ++v) Bv[v] *= dts;
