@@ -66,6 +66,10 @@ int check_dims(const ssmv_dims *d)
         if (d->dstate > 64) return fail(SSMV_EUNSUPPORTED, "diag mode supports dstate <= 64 (got %d)", d->dstate);
     }
     if (d->batch > 65535) return fail(SSMV_EUNSUPPORTED, "batch %d > 65535", d->batch);
+    // the kernels multiply token indices with these row lengths on the 24-bit multiplier
+    if (d->conv_channels >= (1 << 22) || (long)d->ngroups * d->dstate >= (1 << 22) || d->nheads >= (1 << 22))
+        return fail(SSMV_EUNSUPPORTED, "a token row of 2^22 elements or more (channels %d, groups*dstate %ld, heads %d)",
+                    d->conv_channels, (long)d->ngroups * d->dstate, d->nheads);
     if (d->a_mode == SSMV_A_SCALAR && d->nheads > 65535) return fail(SSMV_EUNSUPPORTED, "nheads %d > 65535 in scalar mode", d->nheads);
     if ((double)d->batch * d->kmax * d->nheads * d->headdim >= 2.0e9 || (double)d->batch * d->ring_len * d->nheads * d->headdim >= 2.0e9)
         return fail(SSMV_EUNSUPPORTED, "token tensors beyond 2^31 elements");

@@ -218,6 +218,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const size_t oB_win = tok_win * GN + (size_t)g * N, oB_in = tok_in * GN + (size_t)g * N;
     const size_t oX_win = tok_win * HP + ch0, oX_in = tok_in * HP + ch0;
     const size_t oDt_win = tok_win * H + dth0, oDt_in = tok_in * H + dth0;
+    // Lane-varying strides are multiplied with the 24-bit multiplier (full rate; the 32-bit one runs at a quarter):
+    // token indices are < 32 and the host refuses row lengths of 2^22 elements or more.
+    auto m24 = [](int a, int b_) { return __mul24(a, b_); };
+    const size_t ring_b = (size_t)b * p.ring_len * HP + ch0;            // this sequence's ring rows, this workgroup's channels
+    const int ring_mask = p.ring_len - 1;
     const size_t oB_wout = oB_win + (size_t)t0 * GN, oX_wout = oX_win + (size_t)t0 * HP, oDt_wout = oDt_win + (size_t)t0 * H;
     // optional softplus(dt + dt_bias) ahead of the discretisation (Section 2.2: dt is the positive step)
     const float dtb_h = (EXTRA && !DIAG && p.dt_bias) ? p.dt_bias[hd] : 0.f;
@@ -276,12 +281,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     auto b_load = [&](const BReq &q) {                   // B of token tt (pending window or this round's input)
         uint4 r = make_uint4(0, 0, 0, 0);
         const bool old = q.tt < pd;
-        if (q.on) r = Vec::load_raw(old ? winB : p.Bm, (old ? oB_win + q.tt * GN : oB_in + (q.tt - pd) * GN) + q.n);
+        if (q.on) r = Vec::load_raw(old ? winB : p.Bm, (old ? oB_win + m24(q.tt, GN) : oB_in + m24(q.tt - pd, GN)) + q.n);
         return r;
     };
     auto c_load = [&](const BReq &q) {
         uint4 r = make_uint4(0, 0, 0, 0);
-        if (q.on) r = Vec::load_raw(p.Cm, oB_in + q.tt * GN + q.n);
+        if (q.on) r = Vec::load_raw(p.Cm, oB_in + m24(q.tt, GN) + q.n);
         return r;
     };
     // (scalar mode: the x items carry no dt - it is one number per token, handled by dec_load/dec_use below)
@@ -297,26 +302,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         // the [batch][k][channels] layout.  Two exclusive branches with a load each would share registers and
         // make the second wait for the first.
         const bool fresh = CONV && !old;
-        r.x = XV::load(fresh ? p.x_raw : (old ? winX : p.xc), (old ? oX_win + q.tt * HP : oX_in + t * HP) + q.i);
+        r.x = XV::load(fresh ? p.x_raw : (old ? winX : p.xc), (old ? oX_win + m24(q.tt, HP) : oX_in + m24(t, HP)) + q.i);
         if (fresh) {
             // older taps from earlier inputs of the round or the ring
 #pragma unroll
             for (int w = 0; w < W - 1; ++w) {
                 const int j = t - (W - 1) + w;           // position relative to the round's first token
                 const bool from_ring = j < 0;
-                const size_t ring_row = (size_t)b * p.ring_len + ((conv_head + 1 + j) & (p.ring_len - 1));
-                r.tap[w] = XV::load(from_ring ? p.ring : p.x_raw, (from_ring ? ring_row * HP + ch0 : oX_in + j * HP) + q.i);
+                r.tap[w] = XV::load(from_ring ? p.ring : p.x_raw,
+                                    (from_ring ? ring_b + m24((conv_head + 1 + j) & ring_mask, HP) : oX_in + m24(j, HP)) + q.i);
             }
             r.wv = Vec::load_raw(p.wgt, (size_t)(ch0 + q.i) * W);           // XW channels x W taps = 16 bytes
             r.bias = p.bias ? XV::load(p.bias, ch0 + q.i) : XV::zero();
         }
-        if constexpr (DIAG) r.dt = XV::load(old ? winDt : p.dt, (old ? oDt_win + q.tt * H : oDt_in + t * H) + q.i);
-        if (gated && !old) r.z = XV::load(p.z, oX_in + t * HP + q.i);
+        if constexpr (DIAG) r.dt = XV::load(old ? winDt : p.dt, (old ? oDt_win + m24(q.tt, H) : oDt_in + m24(t, H)) + q.i);
+        if (gated && !old) r.z = XV::load(p.z, oX_in + m24(t, HP) + q.i);
         return r;
     };
     auto b_use = [&](const BReq &q, uint4 raw) {
         if (!q.on) return;
-        if (q.tt >= pd && writes_B) Vec::store_raw(winB_out, oB_wout + (q.tt - pd) * GN + q.n, raw);
+        if (q.tt >= pd && writes_B) Vec::store_raw(winB_out, oB_wout + m24(q.tt - pd, GN) + q.n, raw);
         float v[EV];
         Vec::decode(raw, v);
 #pragma unroll
@@ -342,7 +347,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             for (int w = 0; w < W - 1; ++w) XV::decode(r.tap[w], tap[w]);
             Vec::decode(r.wv, wv);                       // wgt[channel c][tap] sits at [c*W + tap]
             XV::decode(r.bias, bias);
-            XV::store(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 + t) & (p.ring_len - 1))) * HP + ch0 + q.i, r.x);
+            XV::store(p.ring, ring_b + m24((conv_head + 1 + t) & ring_mask, HP) + q.i, r.x);
 #pragma unroll
             for (int e = 0; e < XW; ++e) {
                 float s = bias[e];
@@ -368,27 +373,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             float zv[XW];
             XV::decode(r.z, zv);
 #pragma unroll
-            for (int e = 0; e < XW; ++e) sG[t * rows_wg + q.i + e] = silu(zv[e]);
+            for (int e = 0; e < XW; ++e) sG[(t << p.log2_rows_wg) + q.i + e] = silu(zv[e]);
         }
 #pragma unroll
         for (int e = 0; e < XW; ++e) Dv[e] = DIAG ? p.D[row0 + q.i + e] : D_h;
         if (t >= 0 && !materialize) {
-            XV::store(winX_out, oX_wout + t * HP + q.i, xbits);
-            if (DIAG) XV::store(winDt_out, oDt_wout + t * H + q.i, r.dt);      // the raw dt: replay applies dt_fix again
+            XV::store(winX_out, oX_wout + m24(t, HP) + q.i, xbits);
+            if (DIAG) XV::store(winDt_out, oDt_wout + m24(t, H) + q.i, r.dt);      // the raw dt: replay applies dt_fix again
         }
 #pragma unroll
         for (int e = 0; e < XW; ++e) {
-            sDtx[q.tt * rows_wg + q.i + e] = dtv[e] * xv[e];
-            if (DIAG) sDec[q.tt * rows_wg + q.i + e] = dtv[e];             // A carries the log2(e) factor
-            if (t >= 0) sY[t * rows_wg + q.i + e] = Dv[e] * xv[e];
+            sDtx[(q.tt << p.log2_rows_wg) + q.i + e] = dtv[e] * xv[e];
+            if (DIAG) sDec[(q.tt << p.log2_rows_wg) + q.i + e] = dtv[e];             // A carries the log2(e) factor
+            if (t >= 0) sY[(t << p.log2_rows_wg) + q.i + e] = Dv[e] * xv[e];
         }
     };
     auto dec_load = [&](int tt) {                        // scalar mode: dt of token tt for the decay factor
         const bool old = tt < pd || T == 0;
-        return Vec::load_raw1(old ? winDt : p.dt, old ? oDt_win + tt * H : oDt_in + (tt - pd) * H);
+        return Vec::load_raw1(old ? winDt : p.dt, old ? oDt_win + m24(tt, H) : oDt_in + m24(tt - pd, H));
     };
     auto dec_use = [&](int tt, uint32_t raw) {
-        if (tt >= pd && first_tile && !materialize) Vec::store_raw1(winDt_out, oDt_wout + (tt - pd) * H, raw);
+        if (tt >= pd && first_tile && !materialize) Vec::store_raw1(winDt_out, oDt_wout + m24(tt - pd, H), raw);
         const float d = dt_fix(Vec::decode1(raw), dtb_h);
         sDtF[tt] = d;
     };
@@ -644,7 +649,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
 #pragma unroll
                     for (int e = 0; e < EV; ++e) yv[e] *= sG[t * rows_wg + i + e];
                 }
-                Vec::store_raw(p.y, oX_in + t * HP + i, Vec::encode(yv));
+                Vec::store_raw(p.y, oX_in + m24(t, HP) + i, Vec::encode(yv));
             }
         }
     } else {
