@@ -216,6 +216,31 @@ int ssm_prefill_chunked(const ssmv_dims *dims, const ssmv_cache *cache, const vo
                         const void *Cm, const float *A, const float *D, int32_t L, void *y_out,
                         void *hip_stream);
 
+/* The general form of the prefill: the block pieces of ssm_block_multistep (dt <- softplus(dt +
+ * dt_bias); y <- y * z * sigmoid(z) in fp32 ahead of the rounding of y) and prompts of different
+ * lengths.  seq_len (device int32 [batch], or NULL = all L): sequence b feeds its first
+ * clamp(seq_len[b], 0, L) tokens; the arrays keep the token stride L, outputs behind a sequence's
+ * length are not written, its pos and conv_head advance by its own length, and a sequence of
+ * length 0 is left untouched. */
+typedef struct ssmv_prefill_args {
+    const void *x_raw;      /* [batch][L][Cx] io_dtype */
+    const void *conv_wgt;   /* [Cx][W] io_dtype */
+    const void *conv_bias;  /* [Cx] io_dtype or NULL */
+    const void *dt;         /* [batch][L][H] io_dtype */
+    const float *dt_bias;   /* [H] fp32 or NULL */
+    const void *Bm;         /* [batch][L][G][N] io_dtype */
+    const void *Cm;         /* [batch][L][G][N] io_dtype */
+    const void *z;          /* [batch][L][H*P] io_dtype or NULL */
+    const float *A;         /* [H] fp32 */
+    const float *D;         /* [H] fp32 */
+    const int32_t *seq_len; /* [batch] int32 or NULL */
+    void *y_out;            /* [batch][L][H*P] io_dtype */
+    int32_t L;
+    int32_t dt_softplus;
+} ssmv_prefill_args;
+int ssm_prefill_block(const ssmv_dims *dims, const ssmv_cache *cache, const ssmv_prefill_args *args,
+                      void *hip_stream);
+
 /* Algorithm 2, "return h_k if k' = k else h_j", as integer bookkeeping.  Per
  * sequence with a = accepted[b] (device int32 [batch]; values outside
  * [0,last_k] are clamped and set err_flag):

@@ -31,7 +31,7 @@ SNAP_CODES = {"both": SSMV_SNAP_BOTH, "hj_only": SSMV_SNAP_HJ_ONLY}
 
 EXPORTS = [
     "ssmv_cache_sizes", "ssmv_cache_reset", "conv1d_state_update", "ssm_verify_multistep",
-    "ssm_conv_verify_multistep", "ssm_block_multistep", "ssmv_materialize_block", "ssm_prefill_chunked", "ssm_commit_rollback", "ssm_commit_rollback_multi", "ssmv_materialize", "ssmv_first_conflict", "ssmv_check",
+    "ssm_conv_verify_multistep", "ssm_block_multistep", "ssmv_materialize_block", "ssm_prefill_chunked", "ssm_prefill_block", "ssm_commit_rollback", "ssm_commit_rollback_multi", "ssmv_materialize", "ssmv_first_conflict", "ssmv_check",
     "ssmv_set_tuning", "ssmv_copy_probe", "ssmv_last_error", "ssmv_version",
 ]
 
@@ -40,6 +40,12 @@ class ssmv_step_args(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in (
         "x_raw", "xc", "conv_wgt", "conv_bias", "dt", "dt_bias", "Bm", "Cm", "z", "A", "D", "k_seq", "y_out")] + [
         (n, ctypes.c_int32) for n in ("k", "tok0", "dt_softplus")]
+
+
+class ssmv_prefill_args(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in (
+        "x_raw", "conv_wgt", "conv_bias", "dt", "dt_bias", "Bm", "Cm", "z", "A", "D", "seq_len", "y_out")] + [
+        (n, ctypes.c_int32) for n in ("L", "dt_softplus")]
 
 
 class SsmvError(RuntimeError):
@@ -94,6 +100,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.ssm_conv_verify_multistep.argtypes = [dp, cp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.ssm_commit_rollback.argtypes = [dp, cp, vp, vp]
     lib.ssm_prefill_chunked.argtypes = [dp, cp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.ssm_prefill_block.argtypes = [dp, cp, ctypes.POINTER(ssmv_prefill_args), vp]
     lib.ssm_commit_rollback_multi.argtypes = [dp, cp, i32, vp, vp]
     lib.ssmv_materialize.argtypes = [dp, cp, vp, vp, vp]
     lib.ssm_block_multistep.argtypes = [dp, cp, ctypes.POINTER(ssmv_step_args), vp]
@@ -188,6 +195,13 @@ def ssmv_materialize_block(dims, cache, A, dt_bias, dt_softplus: bool, h_out, st
 def ssm_prefill_chunked(dims, cache, x_raw, wgt, bias, dt, Bm, Cm, A, D, L: int, y_out, stream=None) -> None:
     _ck(load_library().ssm_prefill_chunked(ctypes.byref(dims), ctypes.byref(cache), _ptr(x_raw), _ptr(wgt), _ptr(bias), _ptr(dt),
                                            _ptr(Bm), _ptr(Cm), _ptr(A), _ptr(D), L, _ptr(y_out), _stream(stream)))
+
+
+def ssm_prefill_block(dims, cache, *, x_raw, conv_wgt, dt, Bm, Cm, A, D, L: int, y_out, conv_bias=None, dt_bias=None,
+                      dt_softplus: bool = False, z=None, seq_len=None, stream=None) -> None:
+    a = ssmv_prefill_args(_ptr(x_raw), _ptr(conv_wgt), _ptr(conv_bias), _ptr(dt), _ptr(dt_bias), _ptr(Bm), _ptr(Cm), _ptr(z), _ptr(A),
+                          _ptr(D), _ptr(seq_len), _ptr(y_out), L, int(dt_softplus))
+    _ck(load_library().ssm_prefill_block(ctypes.byref(dims), ctypes.byref(cache), ctypes.byref(a), _stream(stream)))
 
 
 def ssm_commit_rollback_multi(dims, caches, accepted, stream=None) -> None:

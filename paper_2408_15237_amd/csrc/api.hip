@@ -358,37 +358,52 @@ int ssmv_materialize(const ssmv_dims *d, const ssmv_cache *c, const float *A, fl
     return ssmv_materialize_block(d, c, A, nullptr, 0, h_out, hip_stream);
 }
 
-int ssm_prefill_chunked(const ssmv_dims *d, const ssmv_cache *c, const void *x_raw, const void *wgt, const void *bias,
-                        const void *dt, const void *Bm, const void *Cm, const float *A, const float *D, int32_t L,
-                        void *y_out, void *hip_stream)
+int ssm_prefill_block(const ssmv_dims *d, const ssmv_cache *c, const ssmv_prefill_args *a, void *hip_stream)
 {
     int rc;
     if ((rc = check_dims(d)) != SSMV_OK) return rc;
     if ((rc = check_cache(c)) != SSMV_OK) return rc;
-    if (L < 1) return fail(SSMV_EINVAL, "prompt length %d < 1", L);
+    if (!a) return fail(SSMV_EINVAL, "args is NULL");
+    if (a->L < 1) return fail(SSMV_EINVAL, "prompt length %d < 1", a->L);
+    if (a->dt_softplus != 0 && a->dt_softplus != 1) return fail(SSMV_EINVAL, "dt_softplus %d not in {0,1}", a->dt_softplus);
     if (d->a_mode != SSMV_A_SCALAR) return fail(SSMV_EUNSUPPORTED, "the chunked prefill needs one decay per head (a_mode scalar)");
     if (!prefill_shape_supported(d->headdim, d->dstate))
         return fail(SSMV_EUNSUPPORTED, "chunked prefill is built for headdim in {32,64,128} and dstate in {32,64,128}, not %d x %d",
                     d->headdim, d->dstate);
-    if ((rc = check_ptr(x_raw, "x_raw")) != SSMV_OK) return rc;
-    if ((rc = check_ptr(wgt, "wgt")) != SSMV_OK) return rc;
-    if (bias && !aligned16(bias)) return fail(SSMV_EALIGN, "bias is not 16-byte aligned");
-    if ((rc = check_ptr(dt, "dt")) != SSMV_OK) return rc;
-    if ((rc = check_ptr(Bm, "Bm")) != SSMV_OK) return rc;
-    if ((rc = check_ptr(Cm, "Cm")) != SSMV_OK) return rc;
-    if ((rc = check_ptr(A, "A")) != SSMV_OK) return rc;
-    if ((rc = check_ptr(D, "D")) != SSMV_OK) return rc;
-    if ((rc = check_ptr(y_out, "y_out")) != SSMV_OK) return rc;
+    if ((double)d->batch * a->L * d->conv_channels >= 9.0e18) return fail(SSMV_EUNSUPPORTED, "prompt tensors too large");
+    if ((rc = check_ptr(a->x_raw, "x_raw")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(a->conv_wgt, "wgt")) != SSMV_OK) return rc;
+    if (a->conv_bias && !aligned16(a->conv_bias)) return fail(SSMV_EALIGN, "bias is not 16-byte aligned");
+    if ((rc = check_ptr(a->dt, "dt")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(a->Bm, "Bm")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(a->Cm, "Cm")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(a->A, "A")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(a->D, "D")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(a->y_out, "y_out")) != SSMV_OK) return rc;
+    if (a->z && !aligned16(a->z)) return fail(SSMV_EALIGN, "z is not 16-byte aligned");
+    if (a->dt_bias && ((uintptr_t)a->dt_bias & 3)) return fail(SSMV_EALIGN, "dt_bias is not 4-byte aligned");
+    if (a->seq_len && ((uintptr_t)a->seq_len & 3)) return fail(SSMV_EALIGN, "seq_len is not 4-byte aligned");
     PrefillParams p{};
-    p.batch = d->batch; p.H = d->nheads; p.P = d->headdim; p.N = d->dstate; p.G = d->ngroups; p.L = L; p.io = d->io_dtype;
+    p.batch = d->batch; p.H = d->nheads; p.P = d->headdim; p.N = d->dstate; p.G = d->ngroups; p.L = a->L; p.io = d->io_dtype;
     p.ring_len = d->ring_len; p.conv_act = d->conv_act;
+    p.dt_softplus = a->dt_softplus; p.dt_bias = a->dt_bias; p.z = a->z; p.seq_len = a->seq_len;
     p.state = c->state;
     p.slot_stride = (size_t)d->batch * d->nheads * d->headdim * d->dstate;
     p.ring = c->conv_ring; p.cur_slot = c->cur_slot; p.conv_head = c->conv_head;
-    p.x_raw = x_raw; p.wgt = wgt; p.bias = bias; p.dt = dt; p.Bm = Bm; p.Cm = Cm; p.A = A; p.D = D; p.y = y_out;
+    p.x_raw = a->x_raw; p.wgt = a->conv_wgt; p.bias = a->conv_bias; p.dt = a->dt; p.Bm = a->Bm; p.Cm = a->Cm; p.A = a->A; p.D = a->D;
+    p.y = a->y_out;
     p.pos = c->pos; p.conv_head_rw = c->conv_head; p.pend = c->pend; p.last_k = c->last_k; p.err_flag = c->err_flag;
     const int hc = launch_prefill(p, (hipStream_t)hip_stream);
-    return hc == 0 ? SSMV_OK : hip_fail(hc, "ssm_prefill_chunked");
+    return hc == 0 ? SSMV_OK : hip_fail(hc, "ssm_prefill_block");
+}
+
+int ssm_prefill_chunked(const ssmv_dims *d, const ssmv_cache *c, const void *x_raw, const void *wgt, const void *bias,
+                        const void *dt, const void *Bm, const void *Cm, const float *A, const float *D, int32_t L,
+                        void *y_out, void *hip_stream)
+{
+    ssmv_prefill_args a{};
+    a.x_raw = x_raw; a.conv_wgt = wgt; a.conv_bias = bias; a.dt = dt; a.Bm = Bm; a.Cm = Cm; a.A = A; a.D = D; a.L = L; a.y_out = y_out;
+    return ssm_prefill_block(d, c, &a, hip_stream);
 }
 
 int ssm_commit_rollback_multi(const ssmv_dims *d, const ssmv_cache *caches, int32_t n_caches, const int32_t *accepted,

@@ -61,13 +61,18 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lk = lane >> 5;           // MFMA: row/column index and k index of this lane
     const int hd = blockIdx.x, b = blockIdx.y;
-    const int H = p.H, G = p.G, L = p.L;
+    const int H = p.H, G = p.G;
+    const int Ls = p.L;                                 // token stride of the arrays
+    const int L = p.seq_len ? min(max(p.seq_len[b], 0), Ls) : Ls;     // this sequence's prompt length
+    if (L == 0) return;                                 // nothing to feed: state, ring and outputs stay as they are
     const int HP = H * P, GN = G * N;
     const int g = hd / (H / G);
     const int cur = (int)((unsigned)p.cur_slot[b] % 3u);
     const int mask = p.ring_len - 1;
     const int conv_head = p.conv_head[b] & mask;
     const float A_h = p.A[hd], D_h = p.D[hd];
+    const float dtb_h = p.dt_bias ? p.dt_bias[hd] : 0.f;
+    const bool gated = p.z != nullptr;
     float *state = p.state + (size_t)cur * p.slot_stride + ((size_t)b * H + hd) * P * N;
 
     // state -> LDS
@@ -89,7 +94,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
     // select between two gets compiled into two loads and a select of their results, with a wait on the spot.)
     auto raw_bits = [&](int tg) {
         const int tc = tg < 0 ? 0 : (tg < L ? tg : L - 1);
-        return Vec::load_raw1(p.x_raw, ((size_t)b * L + tc) * HP + ch);
+        return Vec::load_raw1(p.x_raw, ((size_t)b * Ls + tc) * HP + ch);
     };
     // the W-1 raw inputs ahead of the prompt (newest last)
     float hist[W - 1];
@@ -107,12 +112,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
             const int item = tid + i * 256;
             const int s_ = item / (N / EV), n = (item % (N / EV)) * EV;
             const int tg = t0 + (s_ < Q ? s_ : Q - 1);
-            const size_t o = ((size_t)b * L + (tg < L ? tg : L - 1)) * GN + (size_t)g * N + n;
+            const size_t o = ((size_t)b * Ls + (tg < L ? tg : L - 1)) * GN + (size_t)g * N + n;
             f.bv[i] = Vec::load_raw(p.Bm, o);
             f.cv[i] = Vec::load_raw(p.Cm, o);
         }
         const int tq = t0 + (tid & (Q - 1));
-        f.dt = Vec::load_raw1(p.dt, ((size_t)b * L + (tq < L ? tq : L - 1)) * H + hd);
+        f.dt = Vec::load_raw1(p.dt, ((size_t)b * Ls + (tq < L ? tq : L - 1)) * H + hd);
     };
     auto consume = [&](int c, const Fetch &f) {
         const int t0 = c * Q, s0 = sg * QS;
@@ -155,7 +160,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
             }
         }
         if (tid < Q) {
-            const float d = t0 + tid < L ? Vec::decode1(f.dt) : 0.f;                         // padding: no decay, no input
+            float d = Vec::decode1(f.dt) + dtb_h;
+            if (p.dt_softplus) d = softplus_fast(d);
+            if (t0 + tid >= L) d = 0.f;                                                      // padding: no decay, no input
             float v = d * A_h;
 #pragma unroll
             for (int off = 1; off < Q; off <<= 1) {
@@ -220,6 +227,27 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
         // ---- Y += M X, + D X, store ------------------------------------------------------------------
         if (wave < TP) {
             const int pcol = wave * 32 + li;
+            constexpr bool VIA_LDS = IO == SSMV_BF16 && (size_t)Q * NP * sizeof(float) >= 4u * 32u * 32u * sizeof(uint16_t);
+            // gate inputs of the elements this lane will store, requested ahead of the matrix products
+            uint4 zv16[2];
+            float zs[VIA_LDS ? 1 : 16];
+            if (gated) {
+                if constexpr (VIA_LDS) {
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const int idx = lane + 64 * i, t = idx >> 2, part = idx & 3;
+                        const int tc = t0 + t < L ? t0 + t : L - 1;
+                        zv16[i] = Vec::load_raw(p.z, ((size_t)b * Ls + tc) * HP + hd * P + wave * 32 + part * 8);
+                    }
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int t = 8 * (v / 4) + 4 * lk + (v % 4);
+                        const int tc = t0 + t < L ? t0 + t : L - 1;
+                        zs[v] = load_io(p.z, ((size_t)b * Ls + tc) * HP + hd * P + pcol, IO);
+                    }
+                }
+            }
 #pragma unroll
             for (int kk = 0; kk < Q / 2; ++kk) {
                 const int s = 2 * kk + lk;
@@ -227,29 +255,49 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
             }
             // bf16 outputs go through LDS (the C rows are free between the second and third barrier of a chunk) so
             // that a lane writes two 16-byte pieces of a token's row instead of sixteen 2-byte elements
-            constexpr bool VIA_LDS = IO == SSMV_BF16 && (size_t)Q * NP * sizeof(float) >= 4u * 32u * 32u * sizeof(uint16_t);
             if constexpr (VIA_LDS) {
                 uint16_t *tile = reinterpret_cast<uint16_t *>(sC) + wave * (32 * 32);      // [t][32 columns of this wave]
+                auto wave_sync = [] {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                };
+                float gf[16];
+                if (gated) {
+                    // the gate inputs arrived as 16-byte row pieces; through the tile they reach the lanes that hold
+                    // the matching outputs, so that the gate is applied in fp32 ahead of the one rounding of y
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const int idx = lane + 64 * i;
+                        *reinterpret_cast<uint4 *>(tile + (idx >> 2) * 32 + (idx & 3) * 8) = zv16[i];
+                    }
+                    wave_sync();
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) gf[v] = silu_fast(bf16_bits_to_f32(tile[(8 * (v / 4) + 4 * lk + (v % 4)) * 32 + li]));
+                    wave_sync();
+                }
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int t = 8 * (v / 4) + 4 * lk + (v % 4);
-                    tile[t * 32 + li] = f32_to_bf16_bits(fmaf(D_h, sX[t * P + pcol], yacc[v]));
+                    float yv = fmaf(D_h, sX[t * P + pcol], yacc[v]);
+                    if (gated) yv *= gf[v];
+                    tile[t * 32 + li] = f32_to_bf16_bits(yv);
                 }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                wave_sync();
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
                     const int idx = lane + 64 * i, t = idx >> 2, part = idx & 3;
                     const uint4 v16 = *reinterpret_cast<const uint4 *>(tile + t * 32 + part * 8);
                     if (t0 + t < L)
-                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.y) + ((size_t)b * L + t0 + t) * HP + hd * P + wave * 32 + part * 8) = v16;
+                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.y) + ((size_t)b * Ls + t0 + t) * HP + hd * P + wave * 32 + part * 8) = v16;
                 }
             } else {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int t = 8 * (v / 4) + 4 * lk + (v % 4);
-                    if (t0 + t < L) store_io(p.y, ((size_t)b * L + t0 + t) * HP + hd * P + pcol, fmaf(D_h, sX[t * P + pcol], yacc[v]), IO);
+                    float yv = fmaf(D_h, sX[t * P + pcol], yacc[v]);
+                    if (gated) yv *= silu_fast(zs[v]);
+                    if (t0 + t < L) store_io(p.y, ((size_t)b * Ls + t0 + t) * HP + hd * P + pcol, yv, IO);
                 }
             }
         }
@@ -288,11 +336,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
 }
 
 // pos += L, conv_head += L; a prefill on a cache with pending tokens or an uncommitted verify is a sequencing error
-__global__ void prefill_finish_kernel(int batch, int L, int ring_len, int64_t *pos, int32_t *conv_head, const int32_t *pend,
-                                      const int32_t *last_k, int32_t *err_flag)
+__global__ void prefill_finish_kernel(int batch, int Ls, const int32_t *seq_len, int ring_len, int64_t *pos, int32_t *conv_head,
+                                      const int32_t *pend, const int32_t *last_k, int32_t *err_flag)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= batch) return;
+    const int L = seq_len ? min(max(seq_len[b], 0), Ls) : Ls;
     if (pend[b] != 0 || last_k[b] != 0) *err_flag = 1;
     pos[b] += L;
     conv_head[b] = (conv_head[b] + L) & (ring_len - 1);
@@ -342,7 +391,7 @@ int launch_prefill(const PrefillParams &p, hipStream_t stream)
         default: return (int)hipErrorInvalidConfiguration;
     }
     if (rc != 0) return rc;
-    hipLaunchKernelGGL(prefill_finish_kernel, dim3((p.batch + 63) / 64), dim3(64), 0, stream, p.batch, p.L, p.ring_len, p.pos,
+    hipLaunchKernelGGL(prefill_finish_kernel, dim3((p.batch + 63) / 64), dim3(64), 0, stream, p.batch, p.L, p.seq_len, p.ring_len, p.pos,
                        p.conv_head_rw, p.pend, p.last_k, p.err_flag);
     return (int)hipGetLastError();
 }

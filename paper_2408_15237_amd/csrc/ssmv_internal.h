@@ -63,7 +63,11 @@ struct ConvParams {
 };
 
 struct PrefillParams {
-    int batch, H, P, N, G, L, io, ring_len, conv_act;
+    int batch, H, P, N, G, L, io, ring_len, conv_act;   // L: token stride of the arrays = longest prompt
+    int dt_softplus;         // 1: dt <- softplus(dt + dt_bias)
+    const float *dt_bias;    // [H] or null
+    const void *z;           // gate input [batch][L][H*P] or null
+    const int32_t *seq_len;  // [batch] or null: prompt length per sequence (<= L)
     float *state;            // [3][batch][H][P][N]; the live slot is advanced in place
     size_t slot_stride;
     void *ring;
@@ -161,6 +165,21 @@ __device__ __forceinline__ void store_io(void *base, size_t idx, float v, int io
         reinterpret_cast<uint16_t *>(base)[idx] = f32_to_bf16_bits(v);
     else
         reinterpret_cast<float *>(base)[idx] = v;
+}
+
+// softplus and SiLU on the hardware exp2/log2/rcp (about 1 ulp each); log(1+t) by its series where 1+t would lose the
+// low bits of t
+__device__ __forceinline__ float softplus_fast(float d)
+{
+    if (d > 20.f) return d;
+    const float t = __builtin_amdgcn_exp2f(d * 1.4426950408889634f);
+    const float series = t * (1.f - t * (0.5f - t * (0.33333334f - t * (0.25f - t * 0.2f))));
+    return t < 0.0625f ? series : __builtin_amdgcn_logf(1.f + t) * 0.6931471805599453f;
+}
+
+__device__ __forceinline__ float silu_fast(float z)
+{
+    return z * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-z * 1.4426950408889634f));
 }
 
 // ---- 16-byte vector access in the I/O storage type -------------------------------------------------

@@ -226,21 +226,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const size_t oB_wout = oB_win + (size_t)t0 * GN, oX_wout = oX_win + (size_t)t0 * HP, oDt_wout = oDt_win + (size_t)t0 * H;
     // optional softplus(dt + dt_bias) ahead of the discretisation (Section 2.2: dt is the positive step)
     const float dtb_h = (EXTRA && !DIAG && p.dt_bias) ? p.dt_bias[hd] : 0.f;
-    // softplus and SiLU on the hardware exp2/log2/rcp (about 1 ulp each); log(1+t) by its series where 1+t would
-    // lose the low bits of t
     auto dt_fix = [&](float d, float bias) {
         if constexpr (EXTRA) {
             d += bias;
-            if (p.dt_softplus && d <= 20.f) {
-                const float t = __builtin_amdgcn_exp2f(d * LOG2E);
-                const float series = t * (1.f - t * (0.5f - t * (0.33333334f - t * (0.25f - t * 0.2f))));
-                d = t < 0.0625f ? series : __builtin_amdgcn_logf(1.f + t) * 0.6931471805599453f;
-            }
+            if (p.dt_softplus) d = softplus_fast(d);
         }
         return d;
     };
     const bool gated = EXTRA && p.z != nullptr;
-    auto silu = [&](float zv) { return zv * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-zv * LOG2E)); };
+    auto silu = [&](float zv) { return silu_fast(zv); };
     auto dt_bias_of = [&](int row) { return (EXTRA && p.dt_bias) ? p.dt_bias[row] : 0.f; };   // diag mode: per channel
     const float D_h = DIAG ? 0.f : p.D[hd];
     const float A_h = DIAG ? 0.f : p.A[hd];

@@ -119,6 +119,10 @@ def test_argument_validation_precedes_any_gpu_work():
     d_ok = ssmv.make_dims(2, 4, 64, 64, kmax=4, io="bf16")
     assert _code(ssmv.ssm_prefill_chunked, d_ok, c, P, P, None, P, P, P, P, P, 8, None, 0) == ssmv.SSMV_EINVAL
     assert _code(ssmv.ssm_prefill_chunked, d_ok, c, P + 2, P, None, P, P, P, P, P, 8, P, 0) == ssmv.SSMV_EALIGN
+    pf = dict(x_raw=P, conv_wgt=P, dt=P, Bm=P, Cm=P, A=P, D=P, y_out=P, stream=0)
+    assert _code(ssmv.ssm_prefill_block, d_ok, c, L=8, dt_softplus=2, **pf) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssm_prefill_block, d_ok, c, L=8, z=P + 4, **pf) == ssmv.SSMV_EALIGN
+    assert _code(ssmv.ssm_prefill_block, d_ok, c, L=8, seq_len=P + 2, **pf) == ssmv.SSMV_EALIGN
     d_diag = ssmv.make_dims(1, 64, 1, 16, a_mode="diag")
     assert _code(ssmv.ssm_prefill_chunked, d_diag, c, P, P, None, P, P, P, P, P, 8, P, 0) == ssmv.SSMV_EUNSUPPORTED
     # broken cache struct

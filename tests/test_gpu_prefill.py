@@ -149,3 +149,61 @@ def test_prefill_full_layer_shape_sampled():
     print("prefill cfg3 shape, L=2048: y error %.3g, state error %.3g" % (e_y, e_h))
     assert e_y <= TOL[io] and e_h <= TOL[io]
     assert hip.cache.ints()["pos"].tolist() == [L] * B_ and hip.cache.ints()["err_flag"] == 0
+
+
+BLOCK_CASES = [
+    ("bf16_via_lds", 64, 64, 3, 1, 3, "bf16", 150),
+    ("f32_direct", 32, 32, 2, 1, 2, "f32", 75),
+    ("bf16_small_n", 128, 32, 2, 1, 2, "bf16", 90),       # C rows too small for the output tile: element-wise stores
+]
+
+
+@pytest.mark.parametrize("case", BLOCK_CASES, ids=[c[0] for c in BLOCK_CASES])
+def test_prefill_with_block_pieces_and_ragged_lengths(case):
+    """softplus(dt + dt_bias), the SiLU gate and per-sequence prompt lengths.  Each sequence is its own oracle run of
+    its own length (the oracle commits a whole batch with one k); outputs behind a sequence's length stay untouched."""
+    from workload import round_to_io
+    name, P, N, H, G, batch, io, L = case
+    tol = TOL[io]
+    dec = Workload(name, "scalar", batch=batch, nheads=H, headdim=P, dstate=N, k=4, rounds=3, io=io, accept="uniform", ngroups=G, seed=61)
+    prompt = generate(dec.scaled(k=L, kmax=L, rounds=1, seed=62))
+    data = generate(dec)
+    lp, pr = data.layers[0], prompt.rounds[0]
+    rng = np.random.default_rng(63)
+    bias = rng.uniform(-0.5, 0.5, size=H).astype(np.float32)
+    dt_raw = round_to_io(rng.standard_normal((batch, L, H)) - 4.0, io)
+    z = round_to_io(rng.standard_normal((batch, L, H * P)), io)
+    lens = np.array([L, 0, 37][:batch] if batch >= 3 else [L - 5, 1], dtype=np.int32)
+    hip = HipLayer(dec, lp)
+    d_bias = torch.from_numpy(bias).to("cuda")
+    y = torch.full((batch, L, H * P), 7.0, dtype=torch.bfloat16 if io == "bf16" else torch.float32, device="cuda")
+    ssmv.ssm_prefill_block(hip.dims, hip.cache.c, x_raw=to_dev(pr.x_raw, io), conv_wgt=hip.conv_w, conv_bias=hip.conv_b,
+                           dt=to_dev(dt_raw, io), dt_bias=d_bias, dt_softplus=True, Bm=to_dev(pr.B[0], io), Cm=to_dev(pr.C[0], io),
+                           z=to_dev(z, io), A=hip.A, D=hip.D, L=L, y_out=y, seq_len=torch.from_numpy(lens).to("cuda"))
+    y_h = to_host(y)
+    h_g = to_host(hip.materialize())
+    oras = []
+    for b in range(batch):
+        n = int(lens[b])
+        ora = oracle.EagerOracle("scalar", lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0[b:b + 1], io, dec.conv_act, G,
+                                 dt_bias=bias, dt_softplus=True)
+        if n > 0:
+            y_ref, _, _ = ora.verify(pr.x_raw[b:b + 1, :n], dt_raw[b:b + 1, :n], pr.B[0][b:b + 1, :n], pr.C[0][b:b + 1, :n], z=z[b:b + 1, :n])
+            ora.commit([n])
+            assert rel_err(y_h[b, :n], y_ref[0]) <= tol, "sequence %d" % b
+        assert np.all(y_h[b, n:] == 7.0), "sequence %d: outputs behind its length were written" % b
+        assert rel_err(h_g[b:b + 1], ora.h) <= tol, "sequence %d: state" % b
+        oras.append(ora)
+    ints = hip.cache.ints()
+    assert ints["pos"].tolist() == lens.tolist() and ints["err_flag"] == 0
+    assert ints["conv_head"].tolist() == [(2 + int(n)) & (dec.ring_len - 1) for n in lens]
+    # decode one round from there through the general call
+    rd = data.rounds[0]
+    ex_dt = round_to_io(rng.standard_normal((batch, dec.k, H)) - 4.0, io)
+    y_g = torch.empty_like(to_dev(rd.x_raw, io))
+    ssmv.ssm_block_multistep(hip.dims, hip.cache.c, x_raw=to_dev(rd.x_raw, io), conv_wgt=hip.conv_w, conv_bias=hip.conv_b,
+                             dt=to_dev(ex_dt, io), dt_bias=d_bias, dt_softplus=True, Bm=to_dev(rd.B[0], io), Cm=to_dev(rd.C[0], io),
+                             A=hip.A, D=hip.D, k=dec.k, y_out=y_g)
+    for b in range(batch):
+        y_r, _, _ = oras[b].verify(rd.x_raw[b:b + 1], ex_dt[b:b + 1], rd.B[0][b:b + 1], rd.C[0][b:b + 1])
+        assert rel_err(to_host(y_g)[b:b + 1], y_r) <= tol, "decode after prefill, sequence %d" % b
