@@ -269,6 +269,15 @@ int ssmv_materialize(const ssmv_dims *dims, const ssmv_cache *cache, const float
 int ssmv_materialize_block(const ssmv_dims *dims, const ssmv_cache *cache, const float *A,
                            const float *dt_bias, int32_t dt_softplus, float *h_out, void *hip_stream);
 
+/* The norm that follows the recurrence in a Mamba-2 block (outside the verify launch: it reduces over
+ * all heads of a token, i.e. across that launch's workgroups): per token row and per group of
+ * group_size adjacent channels,  g = y * z * sigmoid(z)  (g = y when z is NULL, e.g. because the
+ * verify launch already applied the gate),  out = g * rsqrt(mean(g^2) + eps) * weight,  fp32
+ * arithmetic, out rounded to io_dtype.  y, z, out [rows][channels] io_dtype device (out may be y);
+ * weight [channels] fp32 device.  group_size a multiple of 8 (bf16) or 4 (fp32), at most 8192 / 4096. */
+int ssmv_gated_rmsnorm(const void *y, const void *z, const float *weight, int32_t rows, int32_t channels,
+                       int32_t group_size, float eps, int32_t io_dtype, void *out, void *hip_stream);
+
 /* FirstConflict of Algorithm 2: accepted[b] = length of the longest prefix on
  * which draft[b][.] and target[b][.] agree.  draft, target [batch][k] and
  * accepted [batch]: int32, device. */

@@ -5,5 +5,5 @@ bench.py's cpu_baseline leg.  The product package never imports this.
 """
 from .reference import (  # noqa: F401
     EagerOracle, BookkeepingModel, LazyMirror, first_conflict,
-    conv_causal, scan_tokens, round_io, oracle_threads, softplus, step_size, silu_gate,
+    conv_causal, scan_tokens, round_io, oracle_threads, softplus, step_size, silu_gate, rmsnorm_gated,
 )

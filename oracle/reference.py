@@ -125,6 +125,16 @@ def silu_gate(y, z) -> np.ndarray:
     return y * z / (1.0 + np.exp(-z))
 
 
+def rmsnorm_gated(y, z, weight, group_size: int, eps: float) -> np.ndarray:
+    """The norm behind the recurrence in a Mamba-2 block: g = y * silu(z) (g = y when z is None); per row and per
+    group of `group_size` adjacent channels out = g / sqrt(mean(g^2) + eps) * weight."""
+    g = _c(y) if z is None else silu_gate(y, z)
+    rows, ch = g.reshape(-1, g.shape[-1]).shape
+    gg = g.reshape(rows, ch // group_size, group_size)
+    ms = np.mean(gg * gg, axis=-1, keepdims=True)
+    return (gg / np.sqrt(ms + eps)).reshape(g.shape) * _c(weight)
+
+
 def first_conflict(draft, target) -> np.ndarray:
     """Length of the longest prefix on which draft and target agree (Algorithm 2, FirstConflict)."""
     draft = np.asarray(draft)

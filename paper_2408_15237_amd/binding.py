@@ -31,7 +31,7 @@ SNAP_CODES = {"both": SSMV_SNAP_BOTH, "hj_only": SSMV_SNAP_HJ_ONLY}
 
 EXPORTS = [
     "ssmv_cache_sizes", "ssmv_cache_reset", "conv1d_state_update", "ssm_verify_multistep",
-    "ssm_conv_verify_multistep", "ssm_block_multistep", "ssmv_materialize_block", "ssm_prefill_chunked", "ssm_prefill_block", "ssm_commit_rollback", "ssm_commit_rollback_multi", "ssmv_materialize", "ssmv_first_conflict", "ssmv_check",
+    "ssm_conv_verify_multistep", "ssm_block_multistep", "ssmv_materialize_block", "ssm_prefill_chunked", "ssm_prefill_block", "ssm_commit_rollback", "ssm_commit_rollback_multi", "ssmv_materialize", "ssmv_first_conflict", "ssmv_gated_rmsnorm", "ssmv_check",
     "ssmv_set_tuning", "ssmv_copy_probe", "ssmv_last_error", "ssmv_version",
 ]
 
@@ -106,6 +106,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.ssm_block_multistep.argtypes = [dp, cp, ctypes.POINTER(ssmv_step_args), vp]
     lib.ssmv_materialize_block.argtypes = [dp, cp, vp, vp, i32, vp, vp]
     lib.ssmv_first_conflict.argtypes = [vp, vp, i32, i32, vp, vp]
+    lib.ssmv_gated_rmsnorm.argtypes = [vp, vp, vp, i32, i32, i32, ctypes.c_float, i32, vp, vp]
     lib.ssmv_check.argtypes = [cp, vp]
     lib.ssmv_set_tuning.argtypes = [i32, i32]
     lib.ssmv_copy_probe.argtypes = [vp, vp, vp, sz, vp]
@@ -221,6 +222,11 @@ def ssmv_materialize(dims, cache, A, h_out, stream=None) -> None:
 
 def ssmv_first_conflict(draft, target, batch: int, k: int, accepted, stream=None) -> None:
     _ck(load_library().ssmv_first_conflict(_ptr(draft), _ptr(target), batch, k, _ptr(accepted), _stream(stream)))
+
+
+def ssmv_gated_rmsnorm(y, z, weight, rows: int, channels: int, group_size: int, eps: float, io, out, stream=None) -> None:
+    _ck(load_library().ssmv_gated_rmsnorm(_ptr(y), _ptr(z), _ptr(weight), rows, channels, group_size, eps,
+                                          IO_CODES[io] if isinstance(io, str) else io, _ptr(out), _stream(stream)))
 
 
 def ssmv_check(cache, stream=None) -> None:

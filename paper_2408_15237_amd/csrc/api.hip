@@ -459,6 +459,26 @@ int ssmv_check(const ssmv_cache *c, void *hip_stream)
     return SSMV_OK;
 }
 
+int ssmv_gated_rmsnorm(const void *y, const void *z, const float *weight, int32_t rows, int32_t channels, int32_t group_size,
+                       float eps, int32_t io_dtype, void *out, void *hip_stream)
+{
+    int rc;
+    if (io_dtype != SSMV_F32 && io_dtype != SSMV_BF16) return fail(SSMV_EINVAL, "io_dtype %d", io_dtype);
+    const int ev = io_dtype == SSMV_BF16 ? 8 : 4;
+    if (rows < 1 || rows > 65535 * 32 || channels < 1 || group_size < 1 || channels % group_size != 0)
+        return fail(SSMV_EINVAL, "rows %d, channels %d, group_size %d", rows, channels, group_size);
+    if (channels / group_size > 65535) return fail(SSMV_EUNSUPPORTED, "more than 65535 groups");
+    if (group_size % ev != 0 || group_size > 256 * 4 * ev)
+        return fail(SSMV_EUNSUPPORTED, "group_size %d must be a multiple of %d and at most %d", group_size, ev, 256 * 4 * ev);
+    if (!(eps >= 0.f)) return fail(SSMV_EINVAL, "eps must be >= 0");
+    if ((rc = check_ptr(y, "y")) != SSMV_OK) return rc;
+    if (z && !aligned16(z)) return fail(SSMV_EALIGN, "z is not 16-byte aligned");
+    if ((rc = check_ptr(weight, "weight")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(out, "out")) != SSMV_OK) return rc;
+    const int hc = launch_gated_rmsnorm(y, z, weight, rows, channels, group_size, eps, io_dtype, out, (hipStream_t)hip_stream);
+    return hc == 0 ? SSMV_OK : hip_fail(hc, "ssmv_gated_rmsnorm");
+}
+
 int ssmv_copy_probe(const void *src, void *dst0, void *dst1, size_t n_bytes, void *hip_stream)
 {
     int rc;

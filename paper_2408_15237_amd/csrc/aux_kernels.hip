@@ -232,6 +232,63 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const copy_v4f *__restr
     }
 }
 
+// Gated RMS norm of a Mamba-2 block: g = y * z * sigmoid(z) (or y without z); out = g * rsqrt(mean_group(g^2) + eps) * w.
+// One workgroup per (token row, group); a thread takes 16-byte vectors of the group, the sum of squares goes
+// through DPP row reductions, one LDS slot per wave, and a second pass over the values kept in registers.
+template <int IO>
+__global__ __launch_bounds__(256) void gated_rmsnorm_kernel(const void *y, const void *z, const float *weight, int channels,
+                                                            int group, float eps, void *out)
+{
+    using Vec = IoVec<IO>;
+    constexpr int EV = Vec::EV;
+    constexpr int MAXV = 4;                              // vectors per thread: groups of up to 256*4*EV channels
+    __shared__ float partial[4];
+    const int row = blockIdx.x, grp = blockIdx.y, tid = threadIdx.x;
+    const size_t base = (size_t)row * channels + (size_t)grp * group;
+    const int nvec = group / EV;
+    float g[MAXV][EV];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        const int v = tid + i * 256;
+        if (v < nvec) {
+            Vec::load(y, base + (size_t)v * EV, g[i]);
+            if (z) {
+                float zv[EV];
+                Vec::load(z, base + (size_t)v * EV, zv);
+#pragma unroll
+                for (int e = 0; e < EV; ++e) g[i][e] *= silu_fast(zv[e]);
+            }
+#pragma unroll
+            for (int e = 0; e < EV; ++e) ss = fmaf(g[i][e], g[i][e], ss);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if ((tid & 63) == 0) partial[tid >> 6] = ss;
+    __syncthreads();
+    const float scale = rsqrtf((partial[0] + partial[1] + partial[2] + partial[3]) / (float)group + eps);
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        const int v = tid + i * 256;
+        if (v < nvec) {
+            float o[EV];
+#pragma unroll
+            for (int e = 0; e < EV; ++e) o[e] = g[i][e] * scale * weight[(size_t)grp * group + (size_t)v * EV + e];
+            Vec::store(out, base + (size_t)v * EV, o);
+        }
+    }
+}
+
+int launch_gated_rmsnorm(const void *y, const void *z, const float *weight, int rows, int channels, int group, float eps, int io,
+                         void *out, hipStream_t stream)
+{
+    const dim3 grid(rows, channels / group), block(256);
+    if (io == SSMV_BF16) hipLaunchKernelGGL(gated_rmsnorm_kernel<SSMV_BF16>, grid, block, 0, stream, y, z, weight, channels, group, eps, out);
+    else hipLaunchKernelGGL(gated_rmsnorm_kernel<SSMV_F32>, grid, block, 0, stream, y, z, weight, channels, group, eps, out);
+    return (int)hipGetLastError();
+}
+
 int launch_copy_probe(const void *src, void *dst0, void *dst1, size_t n_bytes, hipStream_t stream)
 {
     const size_t n16 = n_bytes / 16;

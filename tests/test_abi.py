@@ -134,6 +134,12 @@ def test_argument_validation_precedes_any_gpu_work():
     assert _code(ssmv.ssmv_materialize, d, bad, P, P, 0) == ssmv.SSMV_EALIGN
     assert _code(ssmv.ssm_commit_rollback, d, c, None, 0) == ssmv.SSMV_EINVAL
     assert _code(ssmv.ssmv_cache_reset, d, bad, None, None, 0) == ssmv.SSMV_EALIGN
+    # gated norm
+    assert _code(ssmv.ssmv_gated_rmsnorm, P, None, P, 4, 64, 48, 1e-5, "bf16", P, 0) == ssmv.SSMV_EINVAL         # 64 % 48
+    assert _code(ssmv.ssmv_gated_rmsnorm, P, None, P, 4, 64, 4, 1e-5, "bf16", P, 0) == ssmv.SSMV_EUNSUPPORTED    # group < one vector
+    assert _code(ssmv.ssmv_gated_rmsnorm, P, None, P, 0, 64, 64, 1e-5, "bf16", P, 0) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssmv_gated_rmsnorm, P, P + 4, P, 4, 64, 64, 1e-5, "bf16", P, 0) == ssmv.SSMV_EALIGN
+    assert _code(ssmv.ssmv_gated_rmsnorm, P, None, None, 4, 64, 64, 1e-5, "f32", P, 0) == ssmv.SSMV_EINVAL
     # helpers
     assert _code(ssmv.ssmv_first_conflict, None, P, 2, 2, P, 0) == ssmv.SSMV_EINVAL
     assert _code(ssmv.ssmv_first_conflict, P, P, 0, 2, P, 0) == ssmv.SSMV_EINVAL

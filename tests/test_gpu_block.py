@@ -230,3 +230,19 @@ def test_ragged_draft_counts(name, fused):
         assert ints["pos"].tolist() == bk.pos and ints["conv_head"].tolist() == bk.conv_head
         assert ints["win_par"] == bk.win_par and ints["err_flag"] == bk.err
         assert rel_err(to_host(hip.materialize()), ora.h) <= tol, "round %d: state" % i
+
+
+@pytest.mark.parametrize("io,channels,group,gate", [("bf16", 4096, 4096, True), ("bf16", 4096, 512, False), ("f32", 192, 64, True),
+                                                     ("bf16", 8192, 8192, True), ("f32", 96, 4, False)])
+def test_gated_rmsnorm(io, channels, group, gate):
+    from workload import round_to_io
+    rng = np.random.default_rng(91)
+    rows = 37
+    y = round_to_io(rng.standard_normal((rows, channels)) * 3, io)
+    z = round_to_io(rng.standard_normal((rows, channels)), io) if gate else None
+    w = rng.standard_normal(channels).astype(np.float32)
+    out = torch.empty_like(to_dev(y, io))
+    ssmv.ssmv_gated_rmsnorm(to_dev(y, io), None if z is None else to_dev(z, io), torch.from_numpy(w).to("cuda"), rows, channels, group,
+                            1e-5, io, out)
+    ref = oracle.rmsnorm_gated(y, z, w, group, 1e-5)
+    assert rel_err(to_host(out), ref) <= (1e-5 if io == "f32" else TOL[io])

@@ -348,3 +348,23 @@ def test_hand_worked_examples():
     raw = np.array(c["history"][0] + c["x"][0]).reshape(1, -1, 1)
     xc = oracle.conv_causal(raw, np.array(c["taps"][0]).reshape(1, 4), np.array(c["bias"][0]), "none", "f32")
     np.testing.assert_allclose(xc.reshape(-1), c["xc"][0], rtol=0, atol=0)
+
+
+def test_rmsnorm_gated_library_and_invariants():
+    r = np.random.default_rng(8)
+    y, z, w = r.standard_normal((3, 5, 64)), r.standard_normal((3, 5, 64)), r.standard_normal(64)
+    # one group: torch's rms_norm on the gated values
+    g = torch.from_numpy(y) * torch.nn.functional.silu(torch.from_numpy(z))
+    ref = torch.nn.functional.rms_norm(g, (64,), torch.from_numpy(w), eps=1e-5).numpy()
+    np.testing.assert_allclose(oracle.rmsnorm_gated(y, z, w, 64, 1e-5), ref, rtol=1e-12, atol=1e-14)
+    # groups are normalised one by one
+    ref4 = torch.nn.functional.rms_norm(g.reshape(3, 5, 4, 16), (16,), None, eps=1e-5).reshape(3, 5, 64).numpy() * w
+    np.testing.assert_allclose(oracle.rmsnorm_gated(y, z, w, 16, 1e-5), ref4, rtol=1e-12, atol=1e-14)
+    # without eps the output does not depend on the scale of y and has unit mean square per group (weight 1)
+    out = oracle.rmsnorm_gated(y, None, np.ones(64), 16, 0.0)
+    np.testing.assert_allclose(oracle.rmsnorm_gated(7.5 * y, None, np.ones(64), 16, 0.0), out, rtol=1e-12)
+    np.testing.assert_allclose(np.mean(out.reshape(3, 5, 4, 16) ** 2, axis=-1), 1.0, rtol=1e-12)
+    # planted mistakes: mean over the whole row instead of the group; variance (mean removed) instead of mean square
+    assert not np.allclose(oracle.rmsnorm_gated(y, z, w, 64, 1e-5), ref4)
+    gv = g.numpy().reshape(3, 5, 4, 16)
+    assert not np.allclose((gv / np.sqrt(gv.var(axis=-1, keepdims=True) + 1e-5)).reshape(3, 5, 64) * w, ref4)
