@@ -179,7 +179,7 @@ int ssm_conv_verify_multistep(const ssmv_dims *dims, const ssmv_cache *cache, co
  *     to the commit; a sequence with nothing to verify passes one token and accepts none) (the arrays keep the stride k): its outputs
  *     y[b][t >= kb] are written as zeros, its h_k slot holds the state after kb tokens, last_k[b] =
  *     tok0 + kb, and ssm_commit_rollback then clamps accepted[b] to that.  Work for the tokens
- *     not taken is skipped.
+ *     not taken is skipped.  Not together with tok0 > 0 (SSMV_EUNSUPPORTED).
  * Exactly one of x_raw (conv fused; needs conv_wgt) and xc is non-NULL.  Other arguments as above. */
 typedef struct ssmv_step_args {
     const void *x_raw;      /* [batch][k][Cx] io_dtype, or NULL */

@@ -260,6 +260,8 @@ static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const ssmv_ste
     if (a->tok0 < 0 || a->tok0 + k > d->kmax) return fail(SSMV_EINVAL, "tok0 %d + k %d outside [0, kmax=%d]", a->tok0, k, d->kmax);
     if (a->tok0 > 0 && d->snapshot_mode == SSMV_SNAP_HJ_ONLY)
         return fail(SSMV_EUNSUPPORTED, "a round fed by several calls needs the h_k slot (not with SSMV_SNAP_HJ_ONLY)");
+    if (a->tok0 > 0 && a->k_seq)
+        return fail(SSMV_EUNSUPPORTED, "ragged draft counts in a round fed by several calls (a sequence's window entries would not be contiguous)");
     if (a->dt_softplus != 0 && a->dt_softplus != 1) return fail(SSMV_EINVAL, "dt_softplus %d not in {0,1}", a->dt_softplus);
     if ((a->x_raw != nullptr) == (a->xc != nullptr)) return fail(SSMV_EINVAL, "exactly one of x_raw and xc must be given");
     if (a->x_raw) {

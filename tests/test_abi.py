@@ -108,6 +108,7 @@ def test_argument_validation_precedes_any_gpu_work():
     assert _code(ssmv.ssm_block_multistep, d, c, k=4, x_raw=P, **blk) == ssmv.SSMV_EINVAL          # no conv weights
     assert _code(ssmv.ssm_block_multistep, d, c, k=2, tok0=3, xc=P, **blk) == ssmv.SSMV_EINVAL
     assert _code(ssmv.ssm_block_multistep, d, c, k=1, tok0=-1, xc=P, **blk) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssm_block_multistep, d, c, k=1, tok0=1, xc=P, k_seq=P, **blk) == ssmv.SSMV_EUNSUPPORTED
     assert _code(ssmv.ssm_block_multistep, d, c, k=1, xc=P, dt_softplus=2, **blk) == ssmv.SSMV_EINVAL
     assert _code(ssmv.ssm_block_multistep, d, c, k=1, xc=P, z=P + 2, **blk) == ssmv.SSMV_EALIGN
     d_hj = ssmv.make_dims(2, 4, 16, 16, kmax=4, io="f32", snapshot_mode="hj_only")
