@@ -372,7 +372,9 @@ int ssm_prefill_block(const ssmv_dims *d, const ssmv_cache *c, const ssmv_prefil
     if (!prefill_shape_supported(d->headdim, d->dstate))
         return fail(SSMV_EUNSUPPORTED, "chunked prefill is built for headdim in {32,64,128} and dstate in {32,64,128}, not %d x %d",
                     d->headdim, d->dstate);
-    if ((double)d->batch * a->L * d->conv_channels >= 9.0e18) return fail(SSMV_EUNSUPPORTED, "prompt tensors too large");
+    // the kernel addresses a sequence's tokens with 32-bit element offsets formed on the 24-bit multiplier
+    if (a->L >= (1 << 24) || (double)a->L * d->conv_channels >= 2147483648.0)
+        return fail(SSMV_EUNSUPPORTED, "a prompt of %d tokens x %d channels does not fit 32-bit offsets: feed it in pieces", a->L, d->conv_channels);
     if ((rc = check_ptr(a->x_raw, "x_raw")) != SSMV_OK) return rc;
     if ((rc = check_ptr(a->conv_wgt, "wgt")) != SSMV_OK) return rc;
     if (a->conv_bias && !aligned16(a->conv_bias)) return fail(SSMV_EALIGN, "bias is not 16-byte aligned");

@@ -25,6 +25,7 @@ namespace ssmv {
 
 typedef float f16v __attribute__((ext_vector_type(16)));
 typedef float f4v __attribute__((ext_vector_type(4)));
+typedef float v4f_t __attribute__((ext_vector_type(4)));
 
 constexpr int kQ = 32;     // tokens per chunk
 
@@ -92,9 +93,20 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
     // raw conv input of prompt token tg for this channel (bits), from a clamped address: a token before the prompt is
     // replaced by the ring history below, one past the end is zeroed when it is used.  (One base pointer only: a
     // select between two gets compiled into two loads and a select of their results, with a wait on the spot.)
+    // Addresses: a base pointer per sequence that is uniform over the workgroup plus a 32-bit element offset from the
+    // 24-bit multiplier (the host refuses prompts whose tensors would not fit), so that no load needs 64-bit or
+    // quarter-rate integer arithmetic.
+    constexpr size_t ES = IO == SSMV_BF16 ? 2 : 4;
+    const char *x_b = reinterpret_cast<const char *>(p.x_raw) + (size_t)b * Ls * HP * ES;
+    const char *z_b = reinterpret_cast<const char *>(p.z) + (size_t)b * Ls * HP * ES;
+    char *y_b = reinterpret_cast<char *>(p.y) + (size_t)b * Ls * HP * ES;
+    const char *B_b = reinterpret_cast<const char *>(p.Bm) + ((size_t)b * Ls * GN + (size_t)g * N) * ES;
+    const char *C_b = reinterpret_cast<const char *>(p.Cm) + ((size_t)b * Ls * GN + (size_t)g * N) * ES;
+    const char *dt_b = reinterpret_cast<const char *>(p.dt) + ((size_t)b * Ls * H + hd) * ES;
+    auto off = [](int token, int stride, int rest) { return (size_t)(unsigned)(__umul24(token, stride) + rest); };
     auto raw_bits = [&](int tg) {
         const int tc = tg < 0 ? 0 : (tg < L ? tg : L - 1);
-        return Vec::load_raw1(p.x_raw, ((size_t)b * Ls + tc) * HP + ch);
+        return Vec::load_raw1(x_b, off(tc, HP, ch));
     };
     // the W-1 raw inputs ahead of the prompt (newest last)
     float hist[W - 1];
@@ -112,12 +124,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
             const int item = tid + i * 256;
             const int s_ = item / (N / EV), n = (item % (N / EV)) * EV;
             const int tg = t0 + (s_ < Q ? s_ : Q - 1);
-            const size_t o = ((size_t)b * Ls + (tg < L ? tg : L - 1)) * GN + (size_t)g * N + n;
-            f.bv[i] = Vec::load_raw(p.Bm, o);
-            f.cv[i] = Vec::load_raw(p.Cm, o);
+            const size_t o = off(tg < L ? tg : L - 1, GN, n);
+            f.bv[i] = Vec::load_raw(B_b, o);
+            f.cv[i] = Vec::load_raw(C_b, o);
         }
         const int tq = t0 + (tid & (Q - 1));
-        f.dt = Vec::load_raw1(p.dt, ((size_t)b * Ls + (tq < L ? tq : L - 1)) * H + hd);
+        f.dt = Vec::load_raw1(dt_b, off(tq < L ? tq : L - 1, H, 0));
     };
     auto consume = [&](int c, const Fetch &f) {
         const int t0 = c * Q, s0 = sg * QS;
@@ -212,6 +224,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
                 for (int v = 0; v < 4; ++v) sM[(qi * 16 + 4 * k4 + v) * QP + srow] = 0.f;
             }
         }
+        // The output tile is accumulated TRANSPOSED (rows = the wave's 32 channels, columns = the chunk's tokens): a lane
+        // then holds, for its token, runs of four adjacent channels, which leave as 8- or 16-byte stores and meet the
+        // gate inputs and the skip term in the same shape, with no trip through LDS.
         f16v yacc = {0};
         if (wave < TP) {
             const float at = sAt[li];
@@ -219,86 +234,40 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
 #pragma unroll
             for (int kk = 0; kk < N / 2; ++kk) {
                 const int n = 2 * kk + lk;
-                yacc = __builtin_amdgcn_mfma_f32_32x32x2f32(sC[li * NP + n] * at, hrow[n], yacc, 0, 0, 0);
+                yacc = __builtin_amdgcn_mfma_f32_32x32x2f32(hrow[n], sC[li * NP + n] * at, yacc, 0, 0, 0);
             }
         }
         __syncthreads();     // M is complete; nobody reads the old state any more
 
-        // ---- Y += M X, + D X, store ------------------------------------------------------------------
+        // ---- Y^T += X^T M^T, + D X, gate, store ---------------------------------------------------------
         if (wave < TP) {
-            const int pcol = wave * 32 + li;
-            constexpr bool VIA_LDS = IO == SSMV_BF16 && (size_t)Q * NP * sizeof(float) >= 4u * 32u * 32u * sizeof(uint16_t);
-            // gate inputs of the elements this lane will store, requested ahead of the matrix products
-            uint4 zv16[2];
-            float zs[VIA_LDS ? 1 : 16];
-            if (gated) {
-                if constexpr (VIA_LDS) {
+            const int t = li;                                   // this lane's token within the chunk
+            const bool live = t0 + t < L;
+            const int tc = live ? t0 + t : L - 1;
+            using QV = XVec<IO, 4>;                             // four adjacent channels in the I/O type
+            typename QV::Raw zraw[4];
+            if (gated) {                                        // requested ahead of the matrix products
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        const int idx = lane + 64 * i, t = idx >> 2, part = idx & 3;
-                        const int tc = t0 + t < L ? t0 + t : L - 1;
-                        zv16[i] = Vec::load_raw(p.z, ((size_t)b * Ls + tc) * HP + hd * P + wave * 32 + part * 8);
-                    }
-                } else {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int t = 8 * (v / 4) + 4 * lk + (v % 4);
-                        const int tc = t0 + t < L ? t0 + t : L - 1;
-                        zs[v] = load_io(p.z, ((size_t)b * Ls + tc) * HP + hd * P + pcol, IO);
-                    }
-                }
+                for (int q = 0; q < 4; ++q) zraw[q] = QV::load(z_b, off(tc, HP, hd * P + wave * 32 + 8 * q + 4 * lk));
             }
 #pragma unroll
             for (int kk = 0; kk < Q / 2; ++kk) {
-                const int s = 2 * kk + lk;
-                yacc = __builtin_amdgcn_mfma_f32_32x32x2f32(sM[li * QP + s], sX[s * P + pcol], yacc, 0, 0, 0);
+                const int s_ = 2 * kk + lk;
+                yacc = __builtin_amdgcn_mfma_f32_32x32x2f32(sX[s_ * P + wave * 32 + li], sM[li * QP + s_], yacc, 0, 0, 0);
             }
-            // bf16 outputs go through LDS (the C rows are free between the second and third barrier of a chunk) so
-            // that a lane writes two 16-byte pieces of a token's row instead of sixteen 2-byte elements
-            if constexpr (VIA_LDS) {
-                uint16_t *tile = reinterpret_cast<uint16_t *>(sC) + wave * (32 * 32);      // [t][32 columns of this wave]
-                auto wave_sync = [] {
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                };
-                float gf[16];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int pl = wave * 32 + 8 * q + 4 * lk;      // first of the four channels (inside the head)
+                const v4f_t xs = *reinterpret_cast<const v4f_t *>(sX + t * P + pl);
+                float yv[4] = {fmaf(D_h, xs.x, yacc[4 * q + 0]), fmaf(D_h, xs.y, yacc[4 * q + 1]), fmaf(D_h, xs.z, yacc[4 * q + 2]),
+                               fmaf(D_h, xs.w, yacc[4 * q + 3])};
                 if (gated) {
-                    // the gate inputs arrived as 16-byte row pieces; through the tile they reach the lanes that hold
-                    // the matching outputs, so that the gate is applied in fp32 ahead of the one rounding of y
+                    float zf[4];
+                    QV::decode(zraw[q], zf);
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        const int idx = lane + 64 * i;
-                        *reinterpret_cast<uint4 *>(tile + (idx >> 2) * 32 + (idx & 3) * 8) = zv16[i];
-                    }
-                    wave_sync();
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) gf[v] = silu_fast(bf16_bits_to_f32(tile[(8 * (v / 4) + 4 * lk + (v % 4)) * 32 + li]));
-                    wave_sync();
+                    for (int e = 0; e < 4; ++e) yv[e] *= silu_fast(zf[e]);
                 }
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int t = 8 * (v / 4) + 4 * lk + (v % 4);
-                    float yv = fmaf(D_h, sX[t * P + pcol], yacc[v]);
-                    if (gated) yv *= gf[v];
-                    tile[t * 32 + li] = f32_to_bf16_bits(yv);
-                }
-                wave_sync();
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const int idx = lane + 64 * i, t = idx >> 2, part = idx & 3;
-                    const uint4 v16 = *reinterpret_cast<const uint4 *>(tile + t * 32 + part * 8);
-                    if (t0 + t < L)
-                        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(p.y) + ((size_t)b * Ls + t0 + t) * HP + hd * P + wave * 32 + part * 8) = v16;
-                }
-            } else {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int t = 8 * (v / 4) + 4 * lk + (v % 4);
-                    float yv = fmaf(D_h, sX[t * P + pcol], yacc[v]);
-                    if (gated) yv *= silu_fast(zs[v]);
-                    if (t0 + t < L) store_io(p.y, ((size_t)b * Ls + t0 + t) * HP + hd * P + pcol, yv, IO);
-                }
+                if (live) QV::store(y_b, off(t0 + t, HP, hd * P + pl), QV::encode(yv));
             }
         }
         // ---- h <- exp(cum_Q) h + (diag(w) X)^T B, tile by tile ---------------------------------------------

@@ -308,6 +308,31 @@ struct XVec<SSMV_BF16, 2> {
 };
 
 template <>
+struct XVec<SSMV_BF16, 4> {                                 // four bf16 values: 8 bytes
+    using Raw = uint2;
+    static __device__ __forceinline__ Raw zero() { return make_uint2(0u, 0u); }
+    static __device__ __forceinline__ Raw load(const void *base, size_t idx)
+    {
+        return *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(base) + idx);
+    }
+    static __device__ __forceinline__ void store(void *base, size_t idx, Raw r)
+    {
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(base) + idx) = r;
+    }
+    static __device__ __forceinline__ void decode(Raw r, float (&v)[4])
+    {
+        v[0] = __uint_as_float(r.x << 16);
+        v[1] = __uint_as_float(r.x & 0xffff0000u);
+        v[2] = __uint_as_float(r.y << 16);
+        v[3] = __uint_as_float(r.y & 0xffff0000u);
+    }
+    static __device__ __forceinline__ Raw encode(const float (&v)[4])
+    {
+        return make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+    }
+};
+
+template <>
 struct XVec<SSMV_F32, 1> {
     using Raw = uint32_t;
     static __device__ __forceinline__ Raw zero() { return 0u; }
