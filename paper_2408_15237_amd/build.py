@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libssmv.so")
-SOURCES = ["api.hip", "aux_kernels.hip", "verify_scalar.hip", "verify_diag.hip", "prefill.hip"]
+SOURCES = ["api.hip", "aux_kernels.hip", "verify_scalar.hip", "verify_diag.hip", "prefill.hip", "prefill_bf16.hip"]
 HEADERS = [os.path.join(CSRC, "ssmv_internal.h"), os.path.join(CSRC, "verify_impl.h"),
            os.path.join(ROOT, "include", "ssmv.h")]
 

@@ -353,11 +353,15 @@ bool prefill_shape_supported(int P, int N)
 int launch_prefill(const PrefillParams &p, hipStream_t stream)
 {
     int rc;
-    switch (p.P) {
-        case 32: rc = launch_p<32>(p, stream); break;
-        case 64: rc = launch_p<64>(p, stream); break;
-        case 128: rc = launch_p<128>(p, stream); break;
-        default: return (int)hipErrorInvalidConfiguration;
+    if (p.io == SSMV_BF16) {
+        rc = launch_prefill_bf16(p, stream);
+    } else {
+        switch (p.P) {
+            case 32: rc = launch_p<32>(p, stream); break;
+            case 64: rc = launch_p<64>(p, stream); break;
+            case 128: rc = launch_p<128>(p, stream); break;
+            default: return (int)hipErrorInvalidConfiguration;
+        }
     }
     if (rc != 0) return rc;
     hipLaunchKernelGGL(prefill_finish_kernel, dim3((p.batch + 63) / 64), dim3(64), 0, stream, p.batch, p.L, p.seq_len, p.ring_len, p.pos,

@@ -1,0 +1,418 @@
+// Chunked prefill for bf16 tensors on the bf16 matrix cores (v_mfma_f32_32x32x16_bf16, 16 times the fp32 MFMA rate).
+// Same evaluation of Section 2.1 Eq. 1 (discretisation of Section 2.2) as prefill.hip, chunk by chunk:
+//   G = C B^T,  M_ts = G_ts exp(cum_t - cum_s) dt_s (s <= t) + [s = t] D,
+//   Y = M X + diag(exp(cum_t)) C h^T,   h <- exp(cum_Q) h + X^T diag(w) B,   w_s = exp(cum_Q - cum_s) dt_s,
+// with the operands arranged so that fp32 accuracy survives the 8-bit mantissa of the multiplier inputs:
+//   * B, C and the conv output X ARE bf16 (the tensors' storage type; the conv output is rounded to it by
+//     definition), so they enter exactly;
+//   * every fp32 operand (the state h, the masked matrix M, the weighted rows w_s B_s) is split into a bf16 head
+//     and a bf16 tail, v = hi + lo + O(2^-17 |v|), and contributes two products into the same fp32 accumulator.
+// One workgroup owns one (sequence, head); wave w owns the 32 channels [32 w, 32 w + 32).  The state lives in the
+// accumulator registers for the whole prompt, TRANSPOSED (tile rows = state index n, columns = channel p): in that
+// shape the registers of a lane (its channel, 16 of the 32 n of a tile) are directly the k-slots of the A operand of
+// h C^T, so the state never visits LDS; the result tile comes out as [channel][token], a lane holding runs of four
+// adjacent channels of its token, which leave as 8-byte stores.  G^T (32 x 32) is computed by every wave for itself:
+// its result registers are, after masking and scaling, directly the B operand of M X (no LDS round trip, no barrier).
+// Operand layout (checked on the hardware): A[i = lane%32][k = 8 (lane/32) + j], B[k = 8 (lane/32) + j][col = lane%32],
+// j = 0..7 the elements of the lane's 16-byte operand; result register v of a lane is row 8 (v/4) + 4 (lane/32) + v%4,
+// column lane%32.  Registers 8 st .. 8 st + 7 of a result tile, used as the operand of step st of a following
+// product, are therefore rows 16 st + 8 (j/4) + 4 (lane/32) + j%4.  Rows of such tiles (the tokens s of G^T, the n of
+// a state tile) are stored under the permutation "swap bits 2 and 3" of the row index: then those eight registers
+// hold the CONSECUTIVE indices 16 st + 8 (lane/32) + j, and the other operand of that product is one 16-byte LDS
+// read, the same read that another product needs anyway (C for G^T and for h C^T; X for M X and for the update).
+// LDS rows are padded by 16 bytes: a row stride that is an odd multiple of 16 bytes spreads 16-byte reads of
+// consecutive rows over all banks.
+#include "ssmv_internal.h"
+
+namespace ssmv {
+
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+
+namespace {
+
+constexpr int kQ = 32;      // tokens per chunk
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <int P, int N>
+struct PfLds {              // byte offsets of the LDS arrays (bf16 unless said)
+    static constexpr int XS = kQ * 2 + 16;                 // row stride of the arrays indexed [..][token]
+    static constexpr int NS = N * 2 + 16;                  // row stride of the arrays indexed [token][n]
+    static constexpr int NW = P / 32;                      // waves
+    static constexpr int oX = 0;                           // [P][Q]  conv output x_s
+    static constexpr int oB = oX + P * XS;                 // [Q][N]
+    static constexpr int oC = oB + kQ * NS;                // [Q][N]
+    static constexpr int oBh = oC + kQ * NS;               // [N][Q]  head of w_s B_s, transposed
+    static constexpr int oBl = oBh + N * XS;               // [N][Q]  tail of w_s B_s, transposed
+    static constexpr int oCum = oBl + N * XS;              // fp32 [NW][Q]  log2 e times the inclusive prefix of dt*A (a copy per wave)
+    static constexpr int oDt = oCum + NW * kQ * 4;         // fp32 [NW][Q]  dt
+    static constexpr int oW = oDt + NW * kQ * 4;           // fp32 [NW][Q]  exp(cum_Q - cum_s) dt_s
+    static constexpr int total = oW + NW * kQ * 4;
+};
+
+// two fp32 values -> packed bf16 heads and packed bf16 tails (first value in the low half)
+__device__ __forceinline__ void split2(float a, float b, uint32_t &hi, uint32_t &lo)
+{
+    hi = pack_bf16x2(a, b);
+    lo = pack_bf16x2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
+}
+
+__device__ __forceinline__ bf8 as_bf8(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    const uint4 u = make_uint4(a, b, c, d);
+    return __builtin_bit_cast(bf8, u);
+}
+__device__ __forceinline__ bf8 as_bf8(uint4 u) { return __builtin_bit_cast(bf8, u); }
+
+__device__ __forceinline__ f16v mfma(bf8 a, bf8 b, f16v c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+
+__device__ __forceinline__ int swap23(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
+
+}  // namespace
+
+template <int P, int N>
+__global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(2))) void prefill_bf16_kernel(const PrefillParams p)
+{
+    constexpr int Q = kQ;
+    constexpr int W = SSMV_CONV_WIDTH;
+    constexpr int NT = 2 * P;            // threads: one wave per 32 channels
+    constexpr int TN = N / 32;
+    constexpr int QS = Q / 2;            // consecutive tokens one thread convolves per chunk (two threads per channel)
+    using Ld = PfLds<P, N>;
+    constexpr int XS = Ld::XS, NS = Ld::NS;
+    using Vec = IoVec<SSMV_BF16>;
+    constexpr int EV = Vec::EV;
+    static_assert(P % 32 == 0 && P <= 128 && N % 32 == 0 && W == 4, "tile shapes");
+
+    extern __shared__ float4 lds_raw[];
+    char *lds = reinterpret_cast<char *>(lds_raw);
+    char *sX = lds + Ld::oX, *sB = lds + Ld::oB, *sC = lds + Ld::oC, *sBh = lds + Ld::oBh, *sBl = lds + Ld::oBl;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lh = lane >> 5;           // MFMA: row/column index and k half of this lane
+    const int lperm = swap23(li);
+    float *sCum = reinterpret_cast<float *>(lds + Ld::oCum) + wave * Q;
+    float *sDt = reinterpret_cast<float *>(lds + Ld::oDt) + wave * Q;
+    float *sW = reinterpret_cast<float *>(lds + Ld::oW) + wave * Q;
+    const int hd = blockIdx.x, b = blockIdx.y;
+    const int H = p.H, G = p.G;
+    const int Ls = p.L;                                 // token stride of the arrays
+    const int L = p.seq_len ? min(max(p.seq_len[b], 0), Ls) : Ls;     // this sequence's prompt length
+    if (L == 0) return;                                 // nothing to feed: state, ring and outputs stay as they are
+    const int HP = H * P, GN = G * N;
+    const int g = hd / (H / G);
+    const int cur = (int)((unsigned)p.cur_slot[b] % 3u);
+    const int mask = p.ring_len - 1;
+    const int conv_head = p.conv_head[b] & mask;
+    const float A2_h = p.A[hd] * kLog2e, D_h = p.D[hd];
+    const float dtb_h = p.dt_bias ? p.dt_bias[hd] : 0.f;
+    const bool gated = p.z != nullptr, silu = p.conv_act == SSMV_ACT_SILU;
+    float *state = p.state + (size_t)cur * p.slot_stride + ((size_t)b * H + hd) * P * N;
+
+    // state -> accumulator registers, transposed tiles [n][p]: register 4 q + e of tile tn holds
+    // h[p = 32 wave + li][n = 32 tn + 16 (q/2) + 8 lh + 4 (q%2) + e]
+    f16v hacc[TN];
+    const size_t srow = (size_t)(wave * 32 + li) * N + 8 * lh;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 v = *reinterpret_cast<const float4 *>(state + srow + 32 * tn + 16 * (q / 2) + 4 * (q % 2));
+            hacc[tn][4 * q + 0] = v.x; hacc[tn][4 * q + 1] = v.y; hacc[tn][4 * q + 2] = v.z; hacc[tn][4 * q + 3] = v.w;
+        }
+    // Register v = 4 q + e of G^T is token s = 16 (q/2) + 8 lh + 4 (q%2) + e against this lane's token t = li: the
+    // causal mask, and the skip term D on the diagonal.
+    float dadd[16];
+    bool keep[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int s = 16 * (v / 8) + 8 * lh + 4 * ((v / 4) % 2) + v % 4;
+        keep[v] = s <= li;
+        dadd[v] = s == li ? D_h : 0.f;
+    }
+    // this thread's conv channel: weights and bias stay in registers for the whole prompt
+    const int pc = tid % P;
+    const int sg = P >= 64 ? __builtin_amdgcn_readfirstlane(tid / P) : tid / P;      // uniform over a wave when P >= 64
+    const unsigned ch = hd * P + pc;
+    float wgt[W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) wgt[w] = load_io(p.wgt, (size_t)ch * W + w, SSMV_BF16);
+    const float cbias = p.bias ? load_io(p.bias, ch, SSMV_BF16) : 0.f;
+    // One base pointer per tensor that is uniform over the workgroup plus an element offset; tokens are clamped into
+    // the prompt, so every load is unconditional: a token before the prompt is replaced by the ring history, tokens past
+    // its end carry dt = 0 and thereby weight 0 everywhere (their rows of X, B, C are the last token's: finite).
+    const uint16_t *x_b = reinterpret_cast<const uint16_t *>(p.x_raw) + (size_t)b * Ls * HP;
+    const char *z_b = reinterpret_cast<const char *>(p.z) + (size_t)b * Ls * HP * 2;
+    char *y_b = reinterpret_cast<char *>(p.y) + (size_t)b * Ls * HP * 2;
+    const uint16_t *B_b = reinterpret_cast<const uint16_t *>(p.Bm) + (size_t)b * Ls * GN + (size_t)g * N;
+    const uint16_t *C_b = reinterpret_cast<const uint16_t *>(p.Cm) + (size_t)b * Ls * GN + (size_t)g * N;
+    const uint16_t *dt_b = reinterpret_cast<const uint16_t *>(p.dt) + (size_t)b * Ls * H + hd;
+    auto off = [](int token, int stride, int rest) { return (size_t)(unsigned)(__umul24(token, stride) + rest); };
+    auto clampL = [&](int tg) { return tg < 0 ? 0 : (tg < L ? tg : L - 1); };
+    auto raw_bits = [&](int tg) { return (uint32_t)(x_b + (size_t)clampL(tg) * HP)[ch]; };    // uniform row pointer, 32-bit lane offset
+    // the W-1 raw inputs ahead of the prompt (newest last)
+    float hist[W - 1];
+#pragma unroll
+    for (int j = 0; j < W - 1; ++j)
+        hist[j] = load_io(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 - (W - 1) + j) & mask)) * HP + ch, SSMV_BF16);
+
+    constexpr int NV = N / EV;                          // 16-byte vectors per token of B (and of C)
+    constexpr int BI = (Q * NV + NT - 1) / NT;          // of them per thread and chunk
+    constexpr int UI = (4 * N + NT - 1) / NT;           // (n, eight tokens) units of the transposed B per thread and chunk
+    struct Fetch { uint32_t x[QS + W - 1]; uint4 bv[BI], cv[BI]; uint32_t bt[UI][8]; uint32_t dt; };
+    auto prefetch = [&](int c, Fetch &f) {
+        const int t0 = c * Q, s0 = sg * QS;
+#pragma unroll
+        for (int j = 0; j < QS + W - 1; ++j) f.x[j] = raw_bits(t0 + s0 - (W - 1) + j);
+#pragma unroll
+        for (int i = 0; i < BI; ++i) {
+            const int item = tid + i * NT;
+            const int s_ = item / NV, n = (item % NV) * EV;
+            const size_t o = off(clampL(t0 + (s_ < Q ? s_ : Q - 1)), GN, n);
+            f.bv[i] = Vec::load_raw(B_b, o);
+            f.cv[i] = Vec::load_raw(C_b, o);
+        }
+#pragma unroll
+        for (int i = 0; i < UI; ++i) {
+            const int u = tid + i * NT;
+            const unsigned n = u % N;
+            const int oct = N >= 64 ? __builtin_amdgcn_readfirstlane(u / N) : u / N;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) f.bt[i][j] = (B_b + (size_t)clampL(t0 + 8 * (oct & 3) + j) * GN)[n];
+        }
+        f.dt = dt_b[off(clampL(t0 + li), H, 0)];
+    };
+    // Per chunk, of this lane's token t = li: log2 e * cum_t and exp(cum_t); and exp(cum_Q) (the same in every lane).
+    float cum_t, at_t, aq;
+    auto consume = [&](int c, const Fetch &f) {
+        const int t0 = c * Q, s0 = sg * QS;
+        // ---- dt, its prefix sums and the decay factors: every wave for itself (32 tokens, both halves alike) ----
+        {
+            float d = Vec::decode1(f.dt) + dtb_h;
+            if (p.dt_softplus) d = softplus_fast(d);
+            if (t0 + li >= L) d = 0.f;                  // padding: no decay, no input
+            float v = d * A2_h;
+#pragma unroll
+            for (int o = 1; o < Q; o <<= 1) {
+                const float u = __shfl_up(v, o, 32);
+                if (li >= o) v += u;
+            }
+            const float cq = __shfl(v, Q - 1, 32);
+            cum_t = v;
+            at_t = __builtin_amdgcn_exp2f(v);
+            aq = __builtin_amdgcn_exp2f(cq);
+            if (lh == 0) {
+                sCum[li] = v;
+                sDt[li] = d;
+                sW[li] = __builtin_amdgcn_exp2f(cq - v) * d;
+            }
+            __builtin_amdgcn_wave_barrier();            // the wave's own LDS traffic stays in program order
+        }
+        // ---- conv of this thread's QS tokens, rows [p][token] ----
+        {
+            float tap[W - 1];
+#pragma unroll
+            for (int j = 0; j < W - 1; ++j) {
+                const int tg = t0 + s0 - (W - 1) + j;   // < 0 only in the first chunk: -(W-1)+j, i.e. hist[j]
+                tap[j] = tg < 0 ? hist[j] : Vec::decode1(f.x[j]);
+            }
+            float t1 = tap[0], t2 = tap[1], t3 = tap[2];
+            float xv[QS];
+#pragma unroll
+            for (int j = 0; j < QS; ++j) {
+                const float r = Vec::decode1(f.x[j + W - 1]);
+                // same fp32 order and rounding as conv1d_state_update
+                float acc = cbias;
+                acc = fmaf(wgt[0], t1, acc);
+                acc = fmaf(wgt[1], t2, acc);
+                acc = fmaf(wgt[2], t3, acc);
+                acc = fmaf(wgt[3], r, acc);
+                xv[j] = acc;
+                t1 = t2; t2 = t3; t3 = r;
+            }
+            if (silu) {
+#pragma unroll
+                for (int j = 0; j < QS; ++j) xv[j] = xv[j] / (1.f + expf(-xv[j]));
+            }
+            uint32_t xr[QS / 2];
+#pragma unroll
+            for (int j2 = 0; j2 < QS / 2; ++j2) xr[j2] = pack_bf16x2(xv[2 * j2], xv[2 * j2 + 1]);     // the rounding to the storage type
+            const int o = pc * XS + s0 * 2;
+#pragma unroll
+            for (int v = 0; v < QS / 8; ++v)
+                *reinterpret_cast<uint4 *>(sX + o + 16 * v) = make_uint4(xr[4 * v], xr[4 * v + 1], xr[4 * v + 2], xr[4 * v + 3]);
+        }
+        // ---- B and C as they are (bits) ----
+#pragma unroll
+        for (int i = 0; i < BI; ++i) {
+            const int item = tid + i * NT;
+            if (item < Q * NV) {
+                const int s_ = item / NV, n = (item % NV) * EV;
+                *reinterpret_cast<uint4 *>(sB + s_ * NS + n * 2) = f.bv[i];
+                *reinterpret_cast<uint4 *>(sC + s_ * NS + n * 2) = f.cv[i];
+            }
+        }
+        // ---- w_s B_s transposed, head and tail: eight tokens of one n per unit ----
+#pragma unroll
+        for (int i = 0; i < UI; ++i) {
+            const int u = tid + i * NT;
+            if (u < 4 * N) {
+                const int n = u % N;
+                const int oct = N >= 64 ? __builtin_amdgcn_readfirstlane(u / N) : u / N;
+                const float4 w0 = *reinterpret_cast<const float4 *>(sW + 8 * oct), w1 = *reinterpret_cast<const float4 *>(sW + 8 * oct + 4);
+                const float wv[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+                uint32_t bh[4], bl[4];
+#pragma unroll
+                for (int j2 = 0; j2 < 4; ++j2)
+                    split2(wv[2 * j2] * Vec::decode1(f.bt[i][2 * j2]), wv[2 * j2 + 1] * Vec::decode1(f.bt[i][2 * j2 + 1]), bh[j2], bl[j2]);
+                *reinterpret_cast<uint4 *>(sBh + n * XS + oct * 16) = make_uint4(bh[0], bh[1], bh[2], bh[3]);
+                *reinterpret_cast<uint4 *>(sBl + n * XS + oct * 16) = make_uint4(bl[0], bl[1], bl[2], bl[3]);
+            }
+        }
+    };
+
+    const int n_chunks = (L + Q - 1) / Q;
+    const int prow = wave * 32 + li;                    // this lane's channel (inside the head) as an operand row
+    Fetch fetch;
+    prefetch(0, fetch);
+    for (int c = 0; c < n_chunks; ++c) {
+        const int t0 = c * Q;
+        consume(c, fetch);
+        __syncthreads();
+        if (c + 1 < n_chunks) prefetch(c + 1, fetch);
+        __builtin_amdgcn_sched_barrier(0);              // the loads stay here, a whole chunk of arithmetic ahead of their use
+
+        const int t = li;                               // this lane's token within the chunk
+        const bool live = t0 + t < L;
+        using QV = XVec<SSMV_BF16, 4>;                  // four adjacent channels
+        typename QV::Raw zraw[4];
+        if (gated) {                                    // requested ahead of the matrix products
+            const int tc = live ? t0 + t : L - 1;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) zraw[q] = QV::load(z_b, off(tc, HP, hd * P + wave * 32 + 8 * q + 4 * lh));
+        }
+        // C of this lane's token, all of it: the B operand of G^T and of h C^T
+        uint4 cop[N / 16];
+#pragma unroll
+        for (int st = 0; st < N / 16; ++st) cop[st] = *reinterpret_cast<const uint4 *>(sC + t * NS + (16 * st + 8 * lh) * 2);
+        // ---- G^T = B C^T (rows s, permuted; columns t), then M^T: masked, decayed, scaled, D on the diagonal ----
+        uint32_t mhi[8], mlo[8];
+        {
+            f16v gacc = {0};
+#pragma unroll
+            for (int st = 0; st < N / 16; ++st)
+                gacc = mfma(as_bf8(*reinterpret_cast<const uint4 *>(sB + lperm * NS + (16 * st + 8 * lh) * 2)), as_bf8(cop[st]), gacc);
+#pragma unroll
+            for (int o = 0; o < 2; ++o) {                   // tokens s = 16 o + 8 lh + [0, 8): registers 8 o .. 8 o + 7
+                const float4 c0 = *reinterpret_cast<const float4 *>(sCum + 16 * o + 8 * lh), c1 = *reinterpret_cast<const float4 *>(sCum + 16 * o + 8 * lh + 4);
+                const float4 d0 = *reinterpret_cast<const float4 *>(sDt + 16 * o + 8 * lh), d1 = *reinterpret_cast<const float4 *>(sDt + 16 * o + 8 * lh + 4);
+                const float csv[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w}, dsv[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+                float m[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int v = 8 * o + j;
+                    const float dec = __builtin_amdgcn_exp2f(cum_t - csv[j]) * dsv[j];      // may overflow where s > t: selected away
+                    m[j] = keep[v] ? fmaf(gacc[v], dec, dadd[v]) : 0.f;
+                }
+#pragma unroll
+                for (int j2 = 0; j2 < 4; ++j2) split2(m[2 * j2], m[2 * j2 + 1], mhi[4 * o + j2], mlo[4 * o + j2]);
+            }
+        }
+        // ---- Y^T = h C^T, scaled by exp(cum_t): the state registers are the A operand ----
+        f16v yacc = {0};
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+                uint32_t ah[4], al[4];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) split2(hacc[tn][8 * st + 2 * d], hacc[tn][8 * st + 2 * d + 1], ah[d], al[d]);
+                const bf8 cb = as_bf8(cop[2 * tn + st]);
+                yacc = mfma(as_bf8(ah[0], ah[1], ah[2], ah[3]), cb, yacc);
+                yacc = mfma(as_bf8(al[0], al[1], al[2], al[3]), cb, yacc);
+            }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) yacc[v] *= at_t;
+        // ---- Y^T += X^T M^T;  h^T <- exp(cum_Q) h^T + (diag(w) B)^T X: X is the A operand of one, the B operand of the other ----
+        uint4 xop[2];
+#pragma unroll
+        for (int st = 0; st < 2; ++st) xop[st] = *reinterpret_cast<const uint4 *>(sX + prow * XS + (16 * st + 8 * lh) * 2);
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            yacc = mfma(as_bf8(xop[st]), as_bf8(mhi[4 * st], mhi[4 * st + 1], mhi[4 * st + 2], mhi[4 * st + 3]), yacc);
+            yacc = mfma(as_bf8(xop[st]), as_bf8(mlo[4 * st], mlo[4 * st + 1], mlo[4 * st + 2], mlo[4 * st + 3]), yacc);
+        }
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) hacc[tn][v] *= aq;
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+                const int o = (32 * tn + lperm) * XS + (16 * st + 8 * lh) * 2;
+                hacc[tn] = mfma(as_bf8(*reinterpret_cast<const uint4 *>(sBh + o)), as_bf8(xop[st]), hacc[tn]);
+                hacc[tn] = mfma(as_bf8(*reinterpret_cast<const uint4 *>(sBl + o)), as_bf8(xop[st]), hacc[tn]);
+            }
+        }
+        // ---- gate, store ----
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int pl = wave * 32 + 8 * q + 4 * lh;      // first of the four channels (inside the head)
+            float yv[4] = {yacc[4 * q + 0], yacc[4 * q + 1], yacc[4 * q + 2], yacc[4 * q + 3]};
+            if (gated) {
+                float zf[4];
+                QV::decode(zraw[q], zf);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) yv[e] *= silu_fast(zf[e]);
+            }
+            if (live) QV::store(y_b, off(t0 + t, HP, hd * P + pl), QV::encode(yv));
+        }
+        __syncthreads();     // the next chunk overwrites X, B, C
+    }
+
+    // ---- state back in place; the newest W-1 raw inputs into the ring behind conv_head -----------------------
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<float4 *>(state + srow + 32 * tn + 16 * (q / 2) + 4 * (q % 2)) =
+                make_float4(hacc[tn][4 * q + 0], hacc[tn][4 * q + 1], hacc[tn][4 * q + 2], hacc[tn][4 * q + 3]);
+    if (tid < P) {
+        for (int tg = (L - (W - 1) > 0 ? L - (W - 1) : 0); tg < L; ++tg)
+            Vec::store_raw1(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 + tg) & mask)) * HP + ch, raw_bits(tg));
+    }
+}
+
+template <int P, int N>
+static int launch_pn(const PrefillParams &p, hipStream_t stream)
+{
+    const size_t lds = PfLds<P, N>::total;
+    const dim3 grid(p.H, p.batch), block(2 * P);
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<P, N>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return (int)e;
+    hipLaunchKernelGGL((prefill_bf16_kernel<P, N>), grid, block, lds, stream, p);
+    return (int)hipGetLastError();
+}
+
+template <int P>
+static int launch_p(const PrefillParams &p, hipStream_t stream)
+{
+    switch (p.N) {
+        case 32: return launch_pn<P, 32>(p, stream);
+        case 64: return launch_pn<P, 64>(p, stream);
+        case 128: return launch_pn<P, 128>(p, stream);
+        default: return (int)hipErrorInvalidConfiguration;
+    }
+}
+
+// the main kernel only; the caller appends the bookkeeping launch
+int launch_prefill_bf16(const PrefillParams &p, hipStream_t stream)
+{
+    switch (p.P) {
+        case 32: return launch_p<32>(p, stream);
+        case 64: return launch_p<64>(p, stream);
+        case 128: return launch_p<128>(p, stream);
+        default: return (int)hipErrorInvalidConfiguration;
+    }
+}
+
+}  // namespace ssmv

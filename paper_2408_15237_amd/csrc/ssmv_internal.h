@@ -125,6 +125,7 @@ bool verify_shape_supported(int N, int R, bool diag);
 
 int launch_conv(const ConvParams &p, hipStream_t stream);
 int launch_prefill(const PrefillParams &p, hipStream_t stream);
+int launch_prefill_bf16(const PrefillParams &p, hipStream_t stream);      // bf16 tensors: the main kernel only
 bool prefill_shape_supported(int P, int N);
 int launch_commit(const CommitParams &p, hipStream_t stream);
 int launch_reset(const ResetParams &p, hipStream_t stream);
