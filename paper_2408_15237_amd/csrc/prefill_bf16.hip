@@ -22,6 +22,8 @@
 // read, the same read that another product needs anyway (C for G^T and for h C^T; X for M X and for the update).
 // LDS rows are padded by 16 bytes: a row stride that is an odd multiple of 16 bytes spreads 16-byte reads of
 // consecutive rows over all banks.
+#include <type_traits>
+
 #include "ssmv_internal.h"
 
 namespace ssmv {
@@ -44,7 +46,9 @@ struct PfLds {              // byte offsets of the LDS arrays (bf16 unless said)
     static constexpr int oC = oB + kQ * NS;                // [Q][N]
     static constexpr int oBh = oC + kQ * NS;               // [N][Q]  head of w_s B_s, transposed
     static constexpr int oBl = oBh + N * XS;               // [N][Q]  tail of w_s B_s, transposed
-    static constexpr int oCum = oBl + N * XS;              // fp32 [NW][Q]  log2 e times the inclusive prefix of dt*A (a copy per wave)
+    static constexpr int oMh = oBl + N * XS;               // [Q][Q]  head of M^T, rows t
+    static constexpr int oMl = oMh + kQ * XS;              // [Q][Q]  tail of M^T
+    static constexpr int oCum = oMl + kQ * XS;              // fp32 [NW][Q]  log2 e times the inclusive prefix of dt*A (a copy per wave)
     static constexpr int oDt = oCum + NW * kQ * 4;         // fp32 [NW][Q]  dt
     static constexpr int oW = oDt + NW * kQ * 4;           // fp32 [NW][Q]  exp(cum_Q - cum_s) dt_s
     static constexpr int total = oW + NW * kQ * 4;
@@ -66,6 +70,23 @@ __device__ __forceinline__ bf8 as_bf8(uint4 u) { return __builtin_bit_cast(bf8, 
 
 __device__ __forceinline__ f16v mfma(bf8 a, bf8 b, f16v c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
 
+// inclusive prefix sums over lanes 0..31 and, separately, over lanes 32..63 (rows of 16 lanes: shifts inside a row,
+// then the first row's total into the second); a lane shifted in from outside its row contributes 0
+template <int CTRL, int ROWS>
+__device__ __forceinline__ float dpp_or_zero(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROWS, 0xf, false));
+}
+__device__ __forceinline__ float prefix32(float v)
+{
+    v += dpp_or_zero<0x111, 0xf>(v);     // row_shr:1
+    v += dpp_or_zero<0x112, 0xf>(v);     // row_shr:2
+    v += dpp_or_zero<0x114, 0xf>(v);     // row_shr:4
+    v += dpp_or_zero<0x118, 0xf>(v);     // row_shr:8
+    v += dpp_or_zero<0x142, 0xa>(v);     // row_bcast:15 into rows 1 and 3
+    return v;
+}
+
 __device__ __forceinline__ int swap23(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
 
 }  // namespace
@@ -86,11 +107,12 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(2))) void
 
     extern __shared__ float4 lds_raw[];
     char *lds = reinterpret_cast<char *>(lds_raw);
-    char *sX = lds + Ld::oX, *sB = lds + Ld::oB, *sC = lds + Ld::oC, *sBh = lds + Ld::oBh, *sBl = lds + Ld::oBl;
+    char *sX = lds + Ld::oX, *sB = lds + Ld::oB, *sC = lds + Ld::oC, *sBh = lds + Ld::oBh, *sBl = lds + Ld::oBl, *sMh = lds + Ld::oMh, *sMl = lds + Ld::oMl;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lh = lane >> 5;           // MFMA: row/column index and k half of this lane
     const int lperm = swap23(li);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     float *sCum = reinterpret_cast<float *>(lds + Ld::oCum) + wave * Q;
     float *sDt = reinterpret_cast<float *>(lds + Ld::oDt) + wave * Q;
     float *sW = reinterpret_cast<float *>(lds + Ld::oW) + wave * Q;
@@ -120,15 +142,16 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(2))) void
             const float4 v = *reinterpret_cast<const float4 *>(state + srow + 32 * tn + 16 * (q / 2) + 4 * (q % 2));
             hacc[tn][4 * q + 0] = v.x; hacc[tn][4 * q + 1] = v.y; hacc[tn][4 * q + 2] = v.z; hacc[tn][4 * q + 3] = v.w;
         }
-    // Register v = 4 q + e of G^T is token s = 16 (q/2) + 8 lh + 4 (q%2) + e against this lane's token t = li: the
-    // causal mask, and the skip term D on the diagonal.
-    float dadd[16];
-    bool keep[16];
+    // Every wave computes G^T whole (rows s, columns t = li) and finishes the 16 / (waves) of its registers that are its
+    // share of M^T: register 4 q + e is token s = 8 q + 4 lh + e.  The causal mask, and the skip term D on the diagonal:
+    constexpr int RW = 4 / Ld::NW;                       // register quads per wave
+    float dadd[4 * RW];
+    bool keep[4 * RW];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int s = 16 * (v / 8) + 8 * lh + 4 * ((v / 4) % 2) + v % 4;
-        keep[v] = s <= li;
-        dadd[v] = s == li ? D_h : 0.f;
+    for (int r = 0; r < 4 * RW; ++r) {
+        const int s = 8 * (RW * wave + r / 4) + 4 * lh + r % 4;
+        keep[r] = s <= li;
+        dadd[r] = s == li ? D_h : 0.f;
     }
     // this thread's conv channel: weights and bias stay in registers for the whole prompt
     const int pc = tid % P;
@@ -160,15 +183,24 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(2))) void
     constexpr int BI = (Q * NV + NT - 1) / NT;          // of them per thread and chunk
     constexpr int UI = (4 * N + NT - 1) / NT;           // (n, eight tokens) units of the transposed B per thread and chunk
     struct Fetch { uint32_t x[QS + W - 1]; uint4 bv[BI], cv[BI]; uint32_t bt[UI][8]; uint32_t dt; };
-    auto prefetch = [&](int c, Fetch &f) {
+    // FAST: a chunk that lies inside the prompt and is not its first needs no clamping of token indices
+    auto prefetch_as = [&](int c, Fetch &f, auto fast_tag) {
+        constexpr bool FAST = decltype(fast_tag)::value;
+        auto tok = [&](int tg) { return FAST ? tg : clampL(tg); };
         const int t0 = c * Q, s0 = sg * QS;
+        if constexpr (FAST) {                               // uniform row pointer stepped from token to token, 32-bit lane offset
+            const uint16_t *xr = x_b + (size_t)(t0 + s0 - (W - 1)) * HP;
 #pragma unroll
-        for (int j = 0; j < QS + W - 1; ++j) f.x[j] = raw_bits(t0 + s0 - (W - 1) + j);
+            for (int j = 0; j < QS + W - 1; ++j, xr += HP) f.x[j] = xr[ch];
+        } else {
+#pragma unroll
+            for (int j = 0; j < QS + W - 1; ++j) f.x[j] = (x_b + (size_t)clampL(t0 + s0 - (W - 1) + j) * HP)[ch];
+        }
 #pragma unroll
         for (int i = 0; i < BI; ++i) {
             const int item = tid + i * NT;
             const int s_ = item / NV, n = (item % NV) * EV;
-            const size_t o = off(clampL(t0 + (s_ < Q ? s_ : Q - 1)), GN, n);
+            const size_t o = off(tok(t0 + (s_ < Q ? s_ : Q - 1)), GN, n);
             f.bv[i] = Vec::load_raw(B_b, o);
             f.cv[i] = Vec::load_raw(C_b, o);
         }
@@ -177,10 +209,24 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(2))) void
             const int u = tid + i * NT;
             const unsigned n = u % N;
             const int oct = N >= 64 ? __builtin_amdgcn_readfirstlane(u / N) : u / N;
+            if constexpr (FAST) {
+                const uint16_t *br = B_b + (size_t)(t0 + 8 * (oct & 3)) * GN;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) f.bt[i][j] = (B_b + (size_t)clampL(t0 + 8 * (oct & 3) + j) * GN)[n];
+                for (int j = 0; j < 8; ++j, br += GN) f.bt[i][j] = br[n];
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) f.bt[i][j] = (B_b + (size_t)clampL(t0 + 8 * (oct & 3) + j) * GN)[n];
+            }
         }
-        f.dt = dt_b[off(clampL(t0 + li), H, 0)];
+        f.dt = dt_b[off(tok(t0 + li), H, 0)];
+    };
+    auto prefetch = [&](int c, Fetch &f) {
+        if (c > 0 && (c + 1) * Q <= L) {
+            prefetch_as(c, f, std::true_type{});
+            asm volatile("" ::: "memory");              // keeps the two sets of loads apart (merged, they would need selected addresses)
+        } else {
+            prefetch_as(c, f, std::false_type{});
+        }
     };
     // Per chunk, of this lane's token t = li: log2 e * cum_t and exp(cum_t); and exp(cum_Q) (the same in every lane).
     float cum_t, at_t, aq;
@@ -192,12 +238,8 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(2))) void
             if (p.dt_softplus) d = softplus_fast(d);
             if (t0 + li >= L) d = 0.f;                  // padding: no decay, no input
             float v = d * A2_h;
-#pragma unroll
-            for (int o = 1; o < Q; o <<= 1) {
-                const float u = __shfl_up(v, o, 32);
-                if (li >= o) v += u;
-            }
-            const float cq = __shfl(v, Q - 1, 32);
+            v = prefix32(v);
+            const float cq = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), Q - 1));
             cum_t = v;
             at_t = __builtin_amdgcn_exp2f(v);
             aq = __builtin_amdgcn_exp2f(cq);
@@ -295,27 +337,48 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(2))) void
         uint4 cop[N / 16];
 #pragma unroll
         for (int st = 0; st < N / 16; ++st) cop[st] = *reinterpret_cast<const uint4 *>(sC + t * NS + (16 * st + 8 * lh) * 2);
-        // ---- G^T = B C^T (rows s, permuted; columns t), then M^T: masked, decayed, scaled, D on the diagonal ----
-        uint32_t mhi[8], mlo[8];
+        // ---- G^T = B C^T, then this wave's share of M^T: masked, decayed, scaled, D on the diagonal; head and tail to LDS ----
         {
             f16v gacc = {0};
 #pragma unroll
             for (int st = 0; st < N / 16; ++st)
-                gacc = mfma(as_bf8(*reinterpret_cast<const uint4 *>(sB + lperm * NS + (16 * st + 8 * lh) * 2)), as_bf8(cop[st]), gacc);
+                gacc = mfma(as_bf8(*reinterpret_cast<const uint4 *>(sB + li * NS + (16 * st + 8 * lh) * 2)), as_bf8(cop[st]), gacc);
+            // registers 4 q .. 4 q + 3 of G^T -> M^T for tokens s = 8 q + 4 lh + [0, 4); r = the quad's index within the wave's share
+            auto finish = [&](int q, int r, float g0, float g1, float g2, float g3) {
+                const int s0 = 8 * q + 4 * lh;
+                const float4 cs = *reinterpret_cast<const float4 *>(sCum + s0), ds = *reinterpret_cast<const float4 *>(sDt + s0);
+                const float csv[4] = {cs.x, cs.y, cs.z, cs.w}, dsv[4] = {ds.x, ds.y, ds.z, ds.w}, g4[4] = {g0, g1, g2, g3};
+                float m[4];
 #pragma unroll
-            for (int o = 0; o < 2; ++o) {                   // tokens s = 16 o + 8 lh + [0, 8): registers 8 o .. 8 o + 7
-                const float4 c0 = *reinterpret_cast<const float4 *>(sCum + 16 * o + 8 * lh), c1 = *reinterpret_cast<const float4 *>(sCum + 16 * o + 8 * lh + 4);
-                const float4 d0 = *reinterpret_cast<const float4 *>(sDt + 16 * o + 8 * lh), d1 = *reinterpret_cast<const float4 *>(sDt + 16 * o + 8 * lh + 4);
-                const float csv[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w}, dsv[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
-                float m[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int v = 8 * o + j;
-                    const float dec = __builtin_amdgcn_exp2f(cum_t - csv[j]) * dsv[j];      // may overflow where s > t: selected away
-                    m[j] = keep[v] ? fmaf(gacc[v], dec, dadd[v]) : 0.f;
+                for (int e = 0; e < 4; ++e) {
+                    const float dec = __builtin_amdgcn_exp2f(cum_t - csv[e]) * dsv[e];      // may overflow where s > t: selected away
+                    m[e] = keep[4 * r + e] ? fmaf(g4[e], dec, dadd[4 * r + e]) : 0.f;
                 }
+                uint2 mh, ml;
+                split2(m[0], m[1], mh.x, ml.x);
+                split2(m[2], m[3], mh.y, ml.y);
+                *reinterpret_cast<uint2 *>(sMh + t * XS + s0 * 2) = mh;
+                *reinterpret_cast<uint2 *>(sMl + t * XS + s0 * 2) = ml;
+            };
+            // the wave's quads: a uniform branch, so that no register is indexed by a variable
+            if constexpr (RW == 4) {
 #pragma unroll
-                for (int j2 = 0; j2 < 4; ++j2) split2(m[2 * j2], m[2 * j2 + 1], mhi[4 * o + j2], mlo[4 * o + j2]);
+                for (int r = 0; r < 4; ++r) finish(r, r, gacc[4 * r], gacc[4 * r + 1], gacc[4 * r + 2], gacc[4 * r + 3]);
+            } else if constexpr (RW == 2) {
+                if (wave_u == 0) {
+                    finish(0, 0, gacc[0], gacc[1], gacc[2], gacc[3]);
+                    finish(1, 1, gacc[4], gacc[5], gacc[6], gacc[7]);
+                } else {
+                    finish(2, 0, gacc[8], gacc[9], gacc[10], gacc[11]);
+                    finish(3, 1, gacc[12], gacc[13], gacc[14], gacc[15]);
+                }
+            } else {
+                switch (wave_u) {
+                    case 0: finish(0, 0, gacc[0], gacc[1], gacc[2], gacc[3]); break;
+                    case 1: finish(1, 0, gacc[4], gacc[5], gacc[6], gacc[7]); break;
+                    case 2: finish(2, 0, gacc[8], gacc[9], gacc[10], gacc[11]); break;
+                    default: finish(3, 0, gacc[12], gacc[13], gacc[14], gacc[15]); break;
+                }
             }
         }
         // ---- Y^T = h C^T, scaled by exp(cum_t): the state registers are the A operand ----
@@ -337,10 +400,12 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(2))) void
         uint4 xop[2];
 #pragma unroll
         for (int st = 0; st < 2; ++st) xop[st] = *reinterpret_cast<const uint4 *>(sX + prow * XS + (16 * st + 8 * lh) * 2);
+        __syncthreads();     // M^T is complete
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
-            yacc = mfma(as_bf8(xop[st]), as_bf8(mhi[4 * st], mhi[4 * st + 1], mhi[4 * st + 2], mhi[4 * st + 3]), yacc);
-            yacc = mfma(as_bf8(xop[st]), as_bf8(mlo[4 * st], mlo[4 * st + 1], mlo[4 * st + 2], mlo[4 * st + 3]), yacc);
+            const int o = t * XS + (16 * st + 8 * lh) * 2;
+            yacc = mfma(as_bf8(xop[st]), as_bf8(*reinterpret_cast<const uint4 *>(sMh + o)), yacc);
+            yacc = mfma(as_bf8(xop[st]), as_bf8(*reinterpret_cast<const uint4 *>(sMl + o)), yacc);
         }
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
