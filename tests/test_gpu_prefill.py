@@ -23,6 +23,14 @@ CASES = [
     ("one_past_a_chunk", 32, 64, 2, 1, 2, "f32", "none", 33),
     ("shorter_than_the_conv", 32, 32, 2, 1, 2, "f32", "none", 2),
     ("single_token", 64, 32, 2, 1, 2, "bf16", "none", 1),
+    # bf16 tensors run on the bf16 matrix cores: every compiled tile shape, lengths that are no multiple of a chunk
+    ("p32n32_bf16", 32, 32, 3, 1, 2, "bf16", "none", 70),
+    ("p32n64_bf16", 32, 64, 2, 1, 2, "bf16", "silu", 45),
+    ("p32n128_bf16", 32, 128, 2, 1, 2, "bf16", "none", 100),
+    ("p64n32_bf16", 64, 32, 2, 1, 2, "bf16", "none", 77),
+    ("p64n128_bf16", 64, 128, 2, 2, 2, "bf16", "none", 66),
+    ("p128n32_bf16", 128, 32, 2, 1, 2, "bf16", "none", 40),
+    ("p128n128_bf16", 128, 128, 2, 1, 1, "bf16", "none", 97),
 ]
 
 
@@ -152,9 +160,10 @@ def test_prefill_full_layer_shape_sampled():
 
 
 BLOCK_CASES = [
-    ("bf16_via_lds", 64, 64, 3, 1, 3, "bf16", 150),
-    ("f32_direct", 32, 32, 2, 1, 2, "f32", 75),
-    ("bf16_small_n", 128, 32, 2, 1, 2, "bf16", 90),       # C rows too small for the output tile: element-wise stores
+    ("bf16_p64", 64, 64, 3, 1, 3, "bf16", 150),
+    ("f32", 32, 32, 2, 1, 2, "f32", 75),
+    ("bf16_small_n", 128, 32, 2, 1, 2, "bf16", 90),
+    ("bf16_p128", 128, 64, 2, 1, 3, "bf16", 130),
 ]
 
 
@@ -207,3 +216,36 @@ def test_prefill_with_block_pieces_and_ragged_lengths(case):
     for b in range(batch):
         y_r, _, _ = oras[b].verify(rd.x_raw[b:b + 1], ex_dt[b:b + 1], rd.B[0][b:b + 1], rd.C[0][b:b + 1])
         assert rel_err(to_host(y_g)[b:b + 1], y_r) <= tol, "decode after prefill, sequence %d" % b
+
+
+@pytest.mark.parametrize("io", ["bf16", "f32"])
+def test_prefill_strong_decay_and_accuracy_of_the_state(io):
+    """Decay of up to e^-30 per token: factors inside a chunk underflow, and the masked upper triangle of the chunk's
+    matrix would overflow if it were computed and multiplied instead of selected away.  Then a mild decay, where the state
+    integrates hundreds of tokens: with bf16 tensors the matrix cores multiply bf16 numbers, and the state must still be
+    stay far more accurate than one bf16 pass would leave it: an fp32 operand enters as bf16 head + bf16 tail, which drops
+    2^-17 of it (8e-6 per product; the worst of 16 k state elements a few times that), against 2^-9 (2e-3) for the head
+    alone.  The bound below sits between the two."""
+    from workload import round_to_io
+    for scale, L in ((60.0, 96), (0.2, 300)):
+        dec = Workload("decay", "scalar", batch=2, nheads=2, headdim=128, dstate=64, k=4, rounds=1, io=io, accept="uniform", seed=71)
+        prompt = generate(dec.scaled(k=L, kmax=L, rounds=1, seed=72))
+        lp, pr = prompt.layers[0], prompt.rounds[0]
+        lp.A[:] = lp.A * scale
+        lp.conv_w[:] = np.array([0.0, 0.0, 0.0, 1.0], dtype=lp.conv_w.dtype)      # conv = identity: no fp32-vs-fp64 rounding ties in
+        if lp.conv_b is not None:                                                  # the bf16 conv output, the error seen is the scan's
+            lp.conv_b[:] = 0.0
+        hip = HipLayer(dec, lp)
+        ora = eager_oracle(dec, lp)
+        y_ref, _, _ = ora.verify(pr.x_raw, pr.dt[0], pr.B[0], pr.C[0])
+        ora.commit(np.full(2, L))
+        d_x = to_dev(pr.x_raw, io)
+        y = torch.empty_like(d_x)
+        ssmv.ssm_prefill_chunked(hip.dims, hip.cache.c, d_x, hip.conv_w, hip.conv_b, to_dev(pr.dt[0], io), to_dev(pr.B[0], io),
+                                 to_dev(pr.C[0], io), hip.A, hip.D, L, y)
+        y_h, h_g = to_host(y), to_host(hip.materialize())
+        assert np.all(np.isfinite(y_h)) and np.all(np.isfinite(h_g))
+        e_y, e_h = rel_err(y_h, y_ref), rel_err(h_g, ora.h)
+        print("A x %g, %s: y error %.3g, state error %.3g" % (scale, io, e_y, e_h))
+        assert e_y <= TOL[io]
+        assert e_h <= (1e-4 if io == "bf16" else 1e-5), "state after the prompt: %.3g" % e_h
