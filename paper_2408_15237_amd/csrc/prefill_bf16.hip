@@ -91,8 +91,10 @@ __device__ __forceinline__ int swap23(int i) { return (i & ~12) | ((i & 4) << 1)
 
 }  // namespace
 
+// Two waves per SIMD (256 registers each, and then the compiler keeps the accumulators in ordinary registers: no copies
+// between the two register files around every use); a state of N = 128 (64 registers per lane) does not fit that.
 template <int P, int N>
-__global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(2))) void prefill_bf16_kernel(const PrefillParams p)
+__global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 ? 1 : 2))) void prefill_bf16_kernel(const PrefillParams p)
 {
     constexpr int Q = kQ;
     constexpr int W = SSMV_CONV_WIDTH;
