@@ -171,9 +171,9 @@ def bench_prefill(args):
     tflops = flops / (ms * 1e-3) / 1e12
     gbps = nbytes / (ms * 1e-3) / 1e9
     if wl.io == "bf16":
-        # executed matrix work: per chunk and wave 4 (G^T) + 4 N/16 (h C^T, head and tail) + 4 (M X) + 4 N/16 (update) products
-        # of 32x32x16, every wave its own G^T
-        mfma_flops = (8 + 8 * (N // 16)) * 32768.0 * (P // 32) * math.ceil(L / Q) * B_ * H
+        # executed matrix work per chunk and wave, in products of 32x32x16: N/16 (G^T, every wave its own) + 2 N/16 (h C^T, head
+        # and tail) + 4 (M X, head and tail) + 2 N/16 (update, head and tail)
+        mfma_flops = (4 + 5 * (N // 16)) * 32768.0 * (P // 32) * math.ceil(L / Q) * B_ * H
         roof = {"bound": "hbm", "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(gbps / PEAK_HBM_GBPS, 4),
                 "traffic": None, "kernel": "prefill_bf16_kernel (bf16 MFMA, split operands)", "avg_launch_us": round(ms * 1e3, 1),
                 "algorithmic_bytes_per_launch": int(nbytes), "algorithmic_flops_per_launch": int(flops),

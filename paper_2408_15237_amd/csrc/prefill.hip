@@ -1,4 +1,5 @@
-// Chunked prefill of a scalar-decay (Mamba-2 style) layer: all L prompt tokens through the recurrence of
+// Chunked prefill of a scalar-decay (Mamba-2 style) layer with fp32 tensors (bf16 tensors: prefill_bf16.hip, same
+// evaluation on the bf16 matrix cores): all L prompt tokens through the recurrence of
 // Section 2.1 Eq. 1 (with the discretisation of Section 2.2), producing every y_t and leaving the cached state and
 // the conv ring as if the L tokens had been verified and accepted.  This is where the path has a dense
 // contraction, so it runs on the matrix cores (fp32 MFMA: the state and the outputs keep fp32 accuracy).
@@ -321,16 +322,10 @@ static int launch_pn(const PrefillParams &p, hipStream_t stream)
 {
     const size_t lds = prefill_lds_floats<P, N>() * sizeof(float);
     const dim3 grid(p.H, p.batch), block(256);
-    hipError_t e;
-    if (p.io == SSMV_BF16) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<P, N, SSMV_BF16>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return (int)e;
-        hipLaunchKernelGGL((prefill_kernel<P, N, SSMV_BF16>), grid, block, lds, stream, p);
-    } else {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<P, N, SSMV_F32>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return (int)e;
-        hipLaunchKernelGGL((prefill_kernel<P, N, SSMV_F32>), grid, block, lds, stream, p);
-    }
+    // fp32 tensors only: bf16 tensors take the bf16 matrix cores (prefill_bf16.hip)
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<P, N, SSMV_F32>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return (int)e;
+    hipLaunchKernelGGL((prefill_kernel<P, N, SSMV_F32>), grid, block, lds, stream, p);
     return (int)hipGetLastError();
 }
 
