@@ -62,8 +62,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lk = lane >> 5;           // MFMA: row/column index and k index of this lane
-    const int hd = blockIdx.x, b = blockIdx.y;
     const int H = p.H, G = p.G;
+    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);       // the heads of a sequence on one XCD: B and C come out of its L2
+    const int hd = item % H, b = item / H;
     const int Ls = p.L;                                 // token stride of the arrays
     const int L = p.seq_len ? min(max(p.seq_len[b], 0), Ls) : Ls;     // this sequence's prompt length
     if (L == 0) return;                                 // nothing to feed: state, ring and outputs stay as they are
@@ -321,7 +322,7 @@ template <int P, int N>
 static int launch_pn(const PrefillParams &p, hipStream_t stream)
 {
     const size_t lds = prefill_lds_floats<P, N>() * sizeof(float);
-    const dim3 grid(p.H, p.batch), block(256);
+    const dim3 grid(p.H * p.batch), block(256);
     // fp32 tensors only: bf16 tensors take the bf16 matrix cores (prefill_bf16.hip)
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<P, N, SSMV_F32>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return (int)e;

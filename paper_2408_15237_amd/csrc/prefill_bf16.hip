@@ -118,8 +118,9 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
     float *sCum = reinterpret_cast<float *>(lds + Ld::oCum) + wave * Q;
     float *sDt = reinterpret_cast<float *>(lds + Ld::oDt) + wave * Q;
     float *sW = reinterpret_cast<float *>(lds + Ld::oW) + wave * Q;
-    const int hd = blockIdx.x, b = blockIdx.y;
     const int H = p.H, G = p.G;
+    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);       // the heads of a sequence on one XCD: B and C come out of its L2
+    const int hd = item % H, b = item / H;
     const int Ls = p.L;                                 // token stride of the arrays
     const int L = p.seq_len ? min(max(p.seq_len[b], 0), Ls) : Ls;     // this sequence's prompt length
     if (L == 0) return;                                 // nothing to feed: state, ring and outputs stay as they are
@@ -453,7 +454,7 @@ template <int P, int N>
 static int launch_pn(const PrefillParams &p, hipStream_t stream)
 {
     const size_t lds = PfLds<P, N>::total;
-    const dim3 grid(p.H, p.batch), block(2 * P);
+    const dim3 grid(p.H * p.batch), block(2 * P);
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<P, N>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return (int)e;
     hipLaunchKernelGGL((prefill_bf16_kernel<P, N>), grid, block, lds, stream, p);

@@ -135,6 +135,15 @@ int launch_copy_probe(const void *src, void *dst0, void *dst1, size_t n_bytes, h
 int launch_gated_rmsnorm(const void *y, const void *z, const float *weight, int rows, int channels, int group, float eps, int io,
                          void *out, hipStream_t stream);
 
+// Workgroups are dealt to the 8 XCDs (each with its own L2) round robin by their linear index.  This maps the linear
+// index to a work item so that every XCD gets one contiguous range of items: the workgroups that share inputs (the
+// heads of one sequence read the same B and C rows) then share an L2.  Identity when the count is no multiple of 8.
+__device__ __forceinline__ unsigned xcd_contiguous(unsigned wg, unsigned total)
+{
+    constexpr unsigned kXcds = 8;
+    return total % kXcds == 0 ? (wg % kXcds) * (total / kXcds) + wg / kXcds : wg;
+}
+
 // ---- storage-type helpers (device) ----------------------------------------------------------------
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
