@@ -48,7 +48,9 @@ struct PfLds {              // byte offsets of the LDS arrays (bf16 unless said)
     static constexpr int oBl = oBh + N * XS;               // [N][Q]  tail of w_s B_s, transposed
     static constexpr int oMh = oBl + N * XS;               // [Q][Q]  head of M^T, rows t
     static constexpr int oMl = oMh + kQ * XS;              // [Q][Q]  tail of M^T
-    static constexpr int oCum = oMl + kQ * XS;              // fp32 [NW][Q]  log2 e times the inclusive prefix of dt*A (a copy per wave)
+    static constexpr int YS = 32 * 2 + 16;                 // row stride of a wave's output tile [token][32 channels]
+    static constexpr int oY = oMl + kQ * XS;               // [NW][Q][32]  the waves' output tiles, for stores of whole 64-byte rows
+    static constexpr int oCum = oY + NW * kQ * YS;              // fp32 [NW][Q]  log2 e times the inclusive prefix of dt*A (a copy per wave)
     static constexpr int oDt = oCum + NW * kQ * 4;         // fp32 [NW][Q]  dt
     static constexpr int oW = oDt + NW * kQ * 4;           // fp32 [NW][Q]  exp(cum_Q - cum_s) dt_s
     static constexpr int total = oW + NW * kQ * 4;
@@ -115,6 +117,7 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
     const int li = lane & 31, lh = lane >> 5;           // MFMA: row/column index and k half of this lane
     const int lperm = swap23(li);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    char *sY = lds + Ld::oY + wave * (Q * Ld::YS);
     float *sCum = reinterpret_cast<float *>(lds + Ld::oCum) + wave * Q;
     float *sDt = reinterpret_cast<float *>(lds + Ld::oDt) + wave * Q;
     float *sW = reinterpret_cast<float *>(lds + Ld::oW) + wave * Q;
@@ -432,7 +435,16 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
 #pragma unroll
                 for (int e = 0; e < 4; ++e) yv[e] *= silu_fast(zf[e]);
             }
-            if (live) QV::store(y_b, off(t0 + t, HP, hd * P + pl), QV::encode(yv));
+            *reinterpret_cast<uint2 *>(sY + t * Ld::YS + (8 * q + 4 * lh) * 2) = QV::encode(yv);
+        }
+        // The tile [token][32 channels] leaves through the wave's own LDS patch as 64-byte rows (four lanes a row): a
+        // store instruction then touches 16 cache lines, not 32 with 16 bytes in each.
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int tt = 16 * r + (lane >> 2), piece = lane & 3;
+            const uint4 v = *reinterpret_cast<const uint4 *>(sY + tt * Ld::YS + piece * 16);
+            if (t0 + tt < L) Vec::store_raw(y_b, off(t0 + tt, HP, hd * P + wave * 32 + piece * 8), v);
         }
         __syncthreads();     // the next chunk overwrites X, B, C
     }
