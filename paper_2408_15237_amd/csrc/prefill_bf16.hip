@@ -319,6 +319,20 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
         }
     };
 
+    // The output tile [token][32 channels] of a chunk leaves through the wave's own LDS patch as 64-byte rows (four lanes
+    // a row: a store instruction then touches 16 cache lines, not 32 with 16 bytes in each), and one chunk LATE, next
+    // to the issue of the following chunk's loads: loads and stores share one counter and complete in no fixed order
+    // among each other, so the wait for the loads at the top of a chunk also waits for every store issued before it -
+    // which by then is a whole chunk old instead of a few cycles.
+    auto flush_outputs = [&](int c) {
+        const int t0 = c * Q;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int tt = 16 * r + (lane >> 2), piece = lane & 3;
+            const uint4 v = *reinterpret_cast<const uint4 *>(sY + tt * Ld::YS + piece * 16);
+            if (t0 + tt < L) Vec::store_raw(y_b, off(t0 + tt, HP, hd * P + wave * 32 + piece * 8), v);
+        }
+    };
     const int n_chunks = (L + Q - 1) / Q;
     const int prow = wave * 32 + li;                    // this lane's channel (inside the head) as an operand row
     Fetch fetch;
@@ -328,7 +342,8 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
         consume(c, fetch);
         __syncthreads();
         if (c + 1 < n_chunks) prefetch(c + 1, fetch);
-        __builtin_amdgcn_sched_barrier(0);              // the loads stay here, a whole chunk of arithmetic ahead of their use
+        if (c > 0) flush_outputs(c - 1);
+        __builtin_amdgcn_sched_barrier(0);              // the loads and stores stay here, a whole chunk of arithmetic ahead of the next wait
 
         const int t = li;                               // this lane's token within the chunk
         const bool live = t0 + t < L;
@@ -437,18 +452,11 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
             }
             *reinterpret_cast<uint2 *>(sY + t * Ld::YS + (8 * q + 4 * lh) * 2) = QV::encode(yv);
         }
-        // The tile [token][32 channels] leaves through the wave's own LDS patch as 64-byte rows (four lanes a row): a
-        // store instruction then touches 16 cache lines, not 32 with 16 bytes in each.
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const int tt = 16 * r + (lane >> 2), piece = lane & 3;
-            const uint4 v = *reinterpret_cast<const uint4 *>(sY + tt * Ld::YS + piece * 16);
-            if (t0 + tt < L) Vec::store_raw(y_b, off(t0 + tt, HP, hd * P + wave * 32 + piece * 8), v);
-        }
+        __builtin_amdgcn_wave_barrier();                // the tile waits in the wave's LDS patch: flush_outputs
         __syncthreads();     // the next chunk overwrites X, B, C
     }
 
+    flush_outputs(n_chunks - 1);
     // ---- state back in place; the newest W-1 raw inputs into the ring behind conv_head -----------------------
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
