@@ -11,15 +11,16 @@
 // accumulator registers for the whole prompt, TRANSPOSED (tile rows = state index n, columns = channel p): in that
 // shape the registers of a lane (its channel, 16 of the 32 n of a tile) are directly the k-slots of the A operand of
 // h C^T, so the state never visits LDS; the result tile comes out as [channel][token], a lane holding runs of four
-// adjacent channels of its token, which leave as 8-byte stores.  G^T (32 x 32) is computed by every wave for itself:
-// its result registers are, after masking and scaling, directly the B operand of M X (no LDS round trip, no barrier).
+// adjacent channels of its token (the wave turns the tile through a patch of LDS of its own into 64-byte rows for the
+// stores).  G^T (32 x 32) is computed by every wave (four products, the matrix pipe has slack); each wave finishes a
+// quarter of its registers into M^T (mask, decay, dt_s, D on the diagonal, head and tail) and shares it through LDS.
 // Operand layout (checked on the hardware): A[i = lane%32][k = 8 (lane/32) + j], B[k = 8 (lane/32) + j][col = lane%32],
 // j = 0..7 the elements of the lane's 16-byte operand; result register v of a lane is row 8 (v/4) + 4 (lane/32) + v%4,
 // column lane%32.  Registers 8 st .. 8 st + 7 of a result tile, used as the operand of step st of a following
-// product, are therefore rows 16 st + 8 (j/4) + 4 (lane/32) + j%4.  Rows of such tiles (the tokens s of G^T, the n of
-// a state tile) are stored under the permutation "swap bits 2 and 3" of the row index: then those eight registers
-// hold the CONSECUTIVE indices 16 st + 8 (lane/32) + j, and the other operand of that product is one 16-byte LDS
-// read, the same read that another product needs anyway (C for G^T and for h C^T; X for M X and for the update).
+// product, are therefore rows 16 st + 8 (j/4) + 4 (lane/32) + j%4.  Rows of the state tiles (the index n) are stored
+// under the permutation "swap bits 2 and 3" of the row index: then those eight registers hold the CONSECUTIVE indices
+// 16 st + 8 (lane/32) + j, and the other operand of h C^T is one 16-byte LDS read, the same read that G^T needs
+// anyway; likewise X serves M X and the update with one read.
 // LDS rows are padded by 16 bytes: a row stride that is an odd multiple of 16 bytes spreads 16-byte reads of
 // consecutive rows over all banks.
 #include <type_traits>
