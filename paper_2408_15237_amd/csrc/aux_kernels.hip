@@ -233,24 +233,27 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const copy_v4f *__restr
 }
 
 // Gated RMS norm of a Mamba-2 block: g = y * z * sigmoid(z) (or y without z); out = g * rsqrt(mean_group(g^2) + eps) * w.
-// One workgroup per (token row, group); a thread takes 16-byte vectors of the group, the sum of squares goes
-// through DPP row reductions, one LDS slot per wave, and a second pass over the values kept in registers.
+// `gt` threads (a multiple of 64, at least the group's 16-byte vectors up to 256) per (token row, group), 256 / gt groups of
+// a row per workgroup; a thread takes 16-byte vectors of its group, the sum of squares goes through wave shuffles and
+// one LDS slot per wave, and a second pass runs over the values kept in registers.
 template <int IO>
 __global__ __launch_bounds__(256) void gated_rmsnorm_kernel(const void *y, const void *z, const float *weight, int channels,
-                                                            int group, float eps, void *out)
+                                                            int group, int gt, float eps, void *out)
 {
     using Vec = IoVec<IO>;
     constexpr int EV = Vec::EV;
     constexpr int MAXV = 4;                              // vectors per thread: groups of up to 256*4*EV channels
     __shared__ float partial[4];
-    const int row = blockIdx.x, grp = blockIdx.y, tid = threadIdx.x;
-    const size_t base = (size_t)row * channels + (size_t)grp * group;
-    const int nvec = group / EV;
+    const int row = blockIdx.x, sub = threadIdx.x / gt, tid = threadIdx.x % gt;
+    const int grp = blockIdx.y * (256 / gt) + sub;
+    const bool have = grp < channels / group;            // the last workgroup of a row may hold fewer groups
+    const size_t base = (size_t)row * channels + (size_t)(have ? grp : 0) * group;
+    const int nvec = have ? group / EV : 0;
     float g[MAXV][EV];
     float ss = 0.f;
 #pragma unroll
     for (int i = 0; i < MAXV; ++i) {
-        const int v = tid + i * 256;
+        const int v = tid + i * gt;
         if (v < nvec) {
             Vec::load(y, base + (size_t)v * EV, g[i]);
             if (z) {
@@ -265,12 +268,14 @@ __global__ __launch_bounds__(256) void gated_rmsnorm_kernel(const void *y, const
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
-    if ((tid & 63) == 0) partial[tid >> 6] = ss;
+    if ((threadIdx.x & 63) == 0) partial[threadIdx.x >> 6] = ss;
     __syncthreads();
-    const float scale = rsqrtf((partial[0] + partial[1] + partial[2] + partial[3]) / (float)group + eps);
+    float tot = 0.f;
+    for (int w = 0; w < gt / 64; ++w) tot += partial[sub * (gt / 64) + w];
+    const float scale = rsqrtf(tot / (float)group + eps);
 #pragma unroll
     for (int i = 0; i < MAXV; ++i) {
-        const int v = tid + i * 256;
+        const int v = tid + i * gt;
         if (v < nvec) {
             float o[EV];
 #pragma unroll
@@ -283,9 +288,12 @@ __global__ __launch_bounds__(256) void gated_rmsnorm_kernel(const void *y, const
 int launch_gated_rmsnorm(const void *y, const void *z, const float *weight, int rows, int channels, int group, float eps, int io,
                          void *out, hipStream_t stream)
 {
-    const dim3 grid(rows, channels / group), block(256);
-    if (io == SSMV_BF16) hipLaunchKernelGGL(gated_rmsnorm_kernel<SSMV_BF16>, grid, block, 0, stream, y, z, weight, channels, group, eps, out);
-    else hipLaunchKernelGGL(gated_rmsnorm_kernel<SSMV_F32>, grid, block, 0, stream, y, z, weight, channels, group, eps, out);
+    const int nvec = group / (io == SSMV_BF16 ? 8 : 4);
+    const int gt = nvec > 128 ? 256 : (nvec > 64 ? 128 : 64);       // threads per group
+    const int gpb = 256 / gt, ngroups = channels / group;
+    const dim3 grid(rows, (ngroups + gpb - 1) / gpb), block(256);
+    if (io == SSMV_BF16) hipLaunchKernelGGL(gated_rmsnorm_kernel<SSMV_BF16>, grid, block, 0, stream, y, z, weight, channels, group, gt, eps, out);
+    else hipLaunchKernelGGL(gated_rmsnorm_kernel<SSMV_F32>, grid, block, 0, stream, y, z, weight, channels, group, gt, eps, out);
     return (int)hipGetLastError();
 }
 

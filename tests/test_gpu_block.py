@@ -233,7 +233,7 @@ def test_ragged_draft_counts(name, fused):
 
 
 @pytest.mark.parametrize("io,channels,group,gate", [("bf16", 4096, 4096, True), ("bf16", 4096, 512, False), ("f32", 192, 64, True),
-                                                     ("bf16", 8192, 8192, True), ("f32", 96, 4, False)])
+                                                     ("bf16", 8192, 8192, True), ("f32", 96, 4, False), ("bf16", 2304, 768, True)])
 def test_gated_rmsnorm(io, channels, group, gate):
     from workload import round_to_io
     rng = np.random.default_rng(91)
