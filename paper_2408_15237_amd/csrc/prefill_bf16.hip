@@ -21,10 +21,12 @@
 // under the permutation "swap bits 2 and 3" of the row index: then those eight registers hold the CONSECUTIVE indices
 // 16 st + 8 (lane/32) + j, and the other operand of h C^T is one 16-byte LDS read, the same read that G^T needs
 // anyway; likewise X serves M X and the update with one read.
-// LDS rows are padded by 16 bytes: a row stride that is an odd multiple of 16 bytes spreads 16-byte reads of
-// consecutive rows over all banks.
-#include <type_traits>
-
+// The chunk's raw x, B and C rows travel from global memory straight into LDS (no registers, 1 KB per wave and
+// instruction), one chunk ahead: they are requested right after the barrier that ends the staging of chunk c, land
+// during its arithmetic, and the barrier at its end publishes them.
+// LDS rows that the kernel writes itself are padded by 16 bytes: a row stride that is an odd multiple of 16 bytes
+// spreads 16-byte reads of consecutive rows over all banks; the rows of B and C, which the direct loads fill without
+// gaps, have their 16-byte pieces XOR-swizzled instead (by the choice of the global address each lane fetches).
 #include "ssmv_internal.h"
 
 namespace ssmv {
@@ -40,22 +42,42 @@ constexpr float kLog2e = 1.4426950408889634f;
 template <int P, int N>
 struct PfLds {              // byte offsets of the LDS arrays (bf16 unless said)
     static constexpr int XS = kQ * 2 + 16;                 // row stride of the arrays indexed [..][token]
-    static constexpr int NS = N * 2 + 16;                  // row stride of the arrays indexed [token][n]
     static constexpr int NW = P / 32;                      // waves
     static constexpr int oX = 0;                           // [P][Q]  conv output x_s
-    static constexpr int oB = oX + P * XS;                 // [Q][N]
-    static constexpr int oC = oB + kQ * NS;                // [Q][N]
-    static constexpr int oBh = oC + kQ * NS;               // [N][Q]  head of w_s B_s, transposed
+    static constexpr int oBh = oX + P * XS;                // [N][Q]  head of w_s B_s, transposed
     static constexpr int oBl = oBh + N * XS;               // [N][Q]  tail of w_s B_s, transposed
     static constexpr int oMh = oBl + N * XS;               // [Q][Q]  head of M^T, rows t
     static constexpr int oMl = oMh + kQ * XS;              // [Q][Q]  tail of M^T
     static constexpr int YS = 32 * 2 + 16;                 // row stride of a wave's output tile [token][32 channels]
     static constexpr int oY = oMl + kQ * XS;               // [NW][Q][32]  the waves' output tiles, for stores of whole 64-byte rows
-    static constexpr int oCum = oY + NW * kQ * YS;              // fp32 [NW][Q]  log2 e times the inclusive prefix of dt*A (a copy per wave)
+    // filled by loads that go from global memory straight into LDS (1 KB per wave and instruction, lane l at byte 16 l):
+    static constexpr int oXraw = oY + NW * kQ * YS;        // [Q][P]  raw conv inputs of the chunk, rows of 2 P bytes
+    static constexpr int BCS = kQ * N * 2;                 // one copy of B or C: [Q][N], rows of 2 N bytes, 16-byte pieces swizzled
+    static constexpr int oB = oXraw + kQ * P * 2;          // two copies (chunks alternate): the next chunk's arrive while this one's are read
+    static constexpr int oC = oB + 2 * BCS;
+    static constexpr int oCar = oC + 2 * BCS;              // fp32 [2][3][P]  the last three raw inputs of a chunk, for the next one's conv
+    static constexpr int oCum = oCar + 2 * 3 * P * 4;      // fp32 [NW][Q]  log2 e times the inclusive prefix of dt*A (a copy per wave)
     static constexpr int oDt = oCum + NW * kQ * 4;         // fp32 [NW][Q]  dt
     static constexpr int oW = oDt + NW * kQ * 4;           // fp32 [NW][Q]  exp(cum_Q - cum_s) dt_s
     static constexpr int total = oW + NW * kQ * 4;
+    // Rows of B and C are 2 N bytes with no padding (the direct loads fill LDS contiguously), so the 16-byte pieces of row r
+    // sit at piece index (logical index ^ swz(r)): 16 consecutive rows then spread a 16-byte column read over all banks.
+    static constexpr int PIECES = N / 8;
+    static __host__ __device__ constexpr int swz(int r) { return PIECES == 16 ? (r & 15) : PIECES == 8 ? ((r ^ (r >> 3)) & 7) : ((r >> 2) & 3); }
 };
+
+typedef __attribute__((address_space(3))) char lds_char_t;
+
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands at LDS address `dst` + 16 l (dst is the
+// same in all lanes and travels in M0).  Issued from assembly, so that the compiler does not count these loads: it would
+// otherwise wait for them before the next LDS read that it cannot prove to be disjoint from their target, and at every
+// workgroup barrier.  The kernel waits for them itself (wait_direct_loads) ahead of the barrier that publishes the data.
+__device__ __forceinline__ void load_to_lds16(const void *src, const char *dst)
+{
+    const unsigned lds_addr = (unsigned)(size_t)(lds_char_t *)dst;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr) : "memory");
+}
+__device__ __forceinline__ void wait_direct_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // two fp32 values -> packed bf16 heads and packed bf16 tails (first value in the low half)
 __device__ __forceinline__ void split2(float a, float b, uint32_t &hi, uint32_t &lo)
@@ -105,14 +127,15 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
     constexpr int TN = N / 32;
     constexpr int QS = Q / 2;            // consecutive tokens one thread convolves per chunk (two threads per channel)
     using Ld = PfLds<P, N>;
-    constexpr int XS = Ld::XS, NS = Ld::NS;
+    constexpr int XS = Ld::XS, PIECES = Ld::PIECES;
     using Vec = IoVec<SSMV_BF16>;
     constexpr int EV = Vec::EV;
     static_assert(P % 32 == 0 && P <= 128 && N % 32 == 0 && W == 4, "tile shapes");
 
     extern __shared__ float4 lds_raw[];
     char *lds = reinterpret_cast<char *>(lds_raw);
-    char *sX = lds + Ld::oX, *sB = lds + Ld::oB, *sC = lds + Ld::oC, *sBh = lds + Ld::oBh, *sBl = lds + Ld::oBl, *sMh = lds + Ld::oMh, *sMl = lds + Ld::oMl;
+    char *sX = lds + Ld::oX, *sBh = lds + Ld::oBh, *sBl = lds + Ld::oBl, *sMh = lds + Ld::oMh, *sMl = lds + Ld::oMl, *sXraw = lds + Ld::oXraw;
+    float *sCar = reinterpret_cast<float *>(lds + Ld::oCar);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lh = lane >> 5;           // MFMA: row/column index and k half of this lane
@@ -186,62 +209,41 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
     for (int j = 0; j < W - 1; ++j)
         hist[j] = load_io(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 - (W - 1) + j) & mask)) * HP + ch, SSMV_BF16);
 
-    constexpr int NV = N / EV;                          // 16-byte vectors per token of B (and of C)
-    constexpr int BI = (Q * NV + NT - 1) / NT;          // of them per thread and chunk
     constexpr int UI = (4 * N + NT - 1) / NT;           // (n, eight tokens) units of the transposed B per thread and chunk
-    struct Fetch { uint32_t x[QS + W - 1]; uint4 bv[BI], cv[BI]; uint32_t bt[UI][8]; uint32_t dt; };
-    // FAST: a chunk that lies inside the prompt and is not its first needs no clamping of token indices
-    auto prefetch_as = [&](int c, Fetch &f, auto fast_tag) {
-        constexpr bool FAST = decltype(fast_tag)::value;
-        auto tok = [&](int tg) { return FAST ? tg : clampL(tg); };
-        const int t0 = c * Q, s0 = sg * QS;
-        if constexpr (FAST) {                               // uniform row pointer stepped from token to token, 32-bit lane offset
-            const uint16_t *xr = x_b + (size_t)(t0 + s0 - (W - 1)) * HP;
+    // The chunk's raw x, B and C rows go from global memory straight into LDS, 1 KB per wave and instruction (lane l's 16
+    // bytes land at byte 16 l of the destination): no registers hold them while they are under way, and a chunk costs a
+    // wave 4 to 6 load instructions instead of 30.  dt (one value per lane) takes the ordinary way.
+    auto issue_loads = [&](int c, uint32_t &dt_bits) {
+        const int t0 = c * Q;
+        auto tok = [&](int row) { return min(t0 + row, L - 1); };
+        constexpr int LR = P / 8;                       // lanes per row of x, 64 / LR rows per instruction, two instructions per wave
 #pragma unroll
-            for (int j = 0; j < QS + W - 1; ++j, xr += HP) f.x[j] = xr[ch];
-        } else {
-#pragma unroll
-            for (int j = 0; j < QS + W - 1; ++j) f.x[j] = (x_b + (size_t)clampL(t0 + s0 - (W - 1) + j) * HP)[ch];
+        for (int k = 0; k < 2; ++k) {
+            const int idx = 2 * wave_u + k;
+            const int row = idx * (64 / LR) + lane / LR, piece = lane % LR;
+            load_to_lds16(x_b + off(tok(row), HP, hd * P + piece * 8), sXraw + idx * 1024);
         }
+        char *dB = lds + Ld::oB + (c & 1) * Ld::BCS, *dC = lds + Ld::oC + (c & 1) * Ld::BCS;
 #pragma unroll
-        for (int i = 0; i < BI; ++i) {
-            const int item = tid + i * NT;
-            const int s_ = item / NV, n = (item % NV) * EV;
-            const size_t o = off(tok(t0 + (s_ < Q ? s_ : Q - 1)), GN, n);
-            f.bv[i] = Vec::load_raw(B_b, o);
-            f.cv[i] = Vec::load_raw(C_b, o);
-        }
-#pragma unroll
-        for (int i = 0; i < UI; ++i) {
-            const int u = tid + i * NT;
-            const unsigned n = u % N;
-            const int oct = N >= 64 ? __builtin_amdgcn_readfirstlane(u / N) : u / N;
-            if constexpr (FAST) {
-                const uint16_t *br = B_b + (size_t)(t0 + 8 * (oct & 3)) * GN;
-#pragma unroll
-                for (int j = 0; j < 8; ++j, br += GN) f.bt[i][j] = br[n];
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) f.bt[i][j] = (B_b + (size_t)clampL(t0 + 8 * (oct & 3) + j) * GN)[n];
+        for (int k = 0; k < (PIECES / 2 + Ld::NW - 1) / Ld::NW; ++k) {
+            const int idx = wave_u + k * Ld::NW;        // PIECES / 2 instructions cover the 32 rows
+            if (idx < PIECES / 2) {
+                const int row = idx * (64 / PIECES) + lane / PIECES, pp = lane % PIECES;
+                const size_t o = off(tok(row), GN, (pp ^ Ld::swz(row)) * 8);
+                load_to_lds16(B_b + o, dB + idx * 1024);
+                load_to_lds16(C_b + o, dC + idx * 1024);
             }
         }
-        f.dt = dt_b[off(tok(t0 + li), H, 0)];
-    };
-    auto prefetch = [&](int c, Fetch &f) {
-        if (c > 0 && (c + 1) * Q <= L) {
-            prefetch_as(c, f, std::true_type{});
-            asm volatile("" ::: "memory");              // keeps the two sets of loads apart (merged, they would need selected addresses)
-        } else {
-            prefetch_as(c, f, std::false_type{});
-        }
+        dt_bits = dt_b[off(tok(li), H, 0)];
     };
     // Per chunk, of this lane's token t = li: log2 e * cum_t and exp(cum_t); and exp(cum_Q) (the same in every lane).
     float cum_t, at_t, aq;
-    auto consume = [&](int c, const Fetch &f) {
+    auto consume = [&](int c, uint32_t dt_bits) {
         const int t0 = c * Q, s0 = sg * QS;
+        const char *sB = lds + Ld::oB + (c & 1) * Ld::BCS;
         // ---- dt, its prefix sums and the decay factors: every wave for itself (32 tokens, both halves alike) ----
         {
-            float d = Vec::decode1(f.dt) + dtb_h;
+            float d = Vec::decode1(dt_bits) + dtb_h;
             if (p.dt_softplus) d = softplus_fast(d);
             if (t0 + li >= L) d = 0.f;                  // padding: no decay, no input
             float v = d * A2_h;
@@ -259,17 +261,25 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
         }
         // ---- conv of this thread's QS tokens, rows [p][token] ----
         {
+            // raw inputs: [token][channel] in LDS; the three ahead of this thread's tokens are the ring history (first chunk),
+            // what the other half's threads left of the previous chunk, or simply earlier rows of this one
+            const uint16_t *xin = reinterpret_cast<const uint16_t *>(sXraw) + pc;
             float tap[W - 1];
+            if (s0 != 0) {
 #pragma unroll
-            for (int j = 0; j < W - 1; ++j) {
-                const int tg = t0 + s0 - (W - 1) + j;   // < 0 only in the first chunk: -(W-1)+j, i.e. hist[j]
-                tap[j] = tg < 0 ? hist[j] : Vec::decode1(f.x[j]);
+                for (int j = 0; j < W - 1; ++j) tap[j] = Vec::decode1(xin[(s0 - (W - 1) + j) * P]);
+            } else if (c == 0) {
+#pragma unroll
+                for (int j = 0; j < W - 1; ++j) tap[j] = hist[j];
+            } else {
+#pragma unroll
+                for (int j = 0; j < W - 1; ++j) tap[j] = sCar[(((c - 1) & 1) * 3 + j) * P + pc];
             }
             float t1 = tap[0], t2 = tap[1], t3 = tap[2];
             float xv[QS];
 #pragma unroll
             for (int j = 0; j < QS; ++j) {
-                const float r = Vec::decode1(f.x[j + W - 1]);
+                const float r = Vec::decode1(xin[(s0 + j) * P]);
                 // same fp32 order and rounding as conv1d_state_update
                 float acc = cbias;
                 acc = fmaf(wgt[0], t1, acc);
@@ -278,6 +288,11 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
                 acc = fmaf(wgt[3], r, acc);
                 xv[j] = acc;
                 t1 = t2; t2 = t3; t3 = r;
+            }
+            if (s0 + QS == Q) {                         // the chunk's last three raw inputs, for the next chunk
+                sCar[((c & 1) * 3 + 0) * P + pc] = t1;
+                sCar[((c & 1) * 3 + 1) * P + pc] = t2;
+                sCar[((c & 1) * 3 + 2) * P + pc] = t3;
             }
             if (silu) {
 #pragma unroll
@@ -291,16 +306,6 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
             for (int v = 0; v < QS / 8; ++v)
                 *reinterpret_cast<uint4 *>(sX + o + 16 * v) = make_uint4(xr[4 * v], xr[4 * v + 1], xr[4 * v + 2], xr[4 * v + 3]);
         }
-        // ---- B and C as they are (bits) ----
-#pragma unroll
-        for (int i = 0; i < BI; ++i) {
-            const int item = tid + i * NT;
-            if (item < Q * NV) {
-                const int s_ = item / NV, n = (item % NV) * EV;
-                *reinterpret_cast<uint4 *>(sB + s_ * NS + n * 2) = f.bv[i];
-                *reinterpret_cast<uint4 *>(sC + s_ * NS + n * 2) = f.cv[i];
-            }
-        }
         // ---- w_s B_s transposed, head and tail: eight tokens of one n per unit ----
 #pragma unroll
         for (int i = 0; i < UI; ++i) {
@@ -313,7 +318,12 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
                 uint32_t bh[4], bl[4];
 #pragma unroll
                 for (int j2 = 0; j2 < 4; ++j2)
-                    split2(wv[2 * j2] * Vec::decode1(f.bt[i][2 * j2]), wv[2 * j2 + 1] * Vec::decode1(f.bt[i][2 * j2 + 1]), bh[j2], bl[j2]);
+                {
+                    const int r0 = 8 * oct + 2 * j2, r1 = r0 + 1;       // B[token][n] out of the swizzled rows
+                    const float b0 = Vec::decode1(*reinterpret_cast<const uint16_t *>(sB + r0 * (N * 2) + (((n >> 3) ^ Ld::swz(r0)) * 16) + (n & 7) * 2));
+                    const float b1 = Vec::decode1(*reinterpret_cast<const uint16_t *>(sB + r1 * (N * 2) + (((n >> 3) ^ Ld::swz(r1)) * 16) + (n & 7) * 2));
+                    split2(wv[2 * j2] * b0, wv[2 * j2 + 1] * b1, bh[j2], bl[j2]);
+                }
                 *reinterpret_cast<uint4 *>(sBh + n * XS + oct * 16) = make_uint4(bh[0], bh[1], bh[2], bh[3]);
                 *reinterpret_cast<uint4 *>(sBl + n * XS + oct * 16) = make_uint4(bl[0], bl[1], bl[2], bl[3]);
             }
@@ -336,15 +346,18 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
     };
     const int n_chunks = (L + Q - 1) / Q;
     const int prow = wave * 32 + li;                    // this lane's channel (inside the head) as an operand row
-    Fetch fetch;
-    prefetch(0, fetch);
+    uint32_t dt_bits;
+    issue_loads(0, dt_bits);
+    wait_direct_loads();
+    __syncthreads();
     for (int c = 0; c < n_chunks; ++c) {
         const int t0 = c * Q;
-        consume(c, fetch);
+        const char *sB = lds + Ld::oB + (c & 1) * Ld::BCS, *sC = lds + Ld::oC + (c & 1) * Ld::BCS;
+        consume(c, dt_bits);
         __syncthreads();
-        if (c + 1 < n_chunks) prefetch(c + 1, fetch);
+        if (c + 1 < n_chunks) issue_loads(c + 1, dt_bits);         // under way for the whole chunk
         if (c > 0) flush_outputs(c - 1);
-        __builtin_amdgcn_sched_barrier(0);              // the loads and stores stay here, a whole chunk of arithmetic ahead of the next wait
+        __builtin_amdgcn_sched_barrier(0);              // the loads and stores stay here, a chunk of arithmetic ahead of the next wait
 
         const int t = li;                               // this lane's token within the chunk
         const bool live = t0 + t < L;
@@ -358,13 +371,13 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
         // C of this lane's token, all of it: the B operand of G^T and of h C^T
         uint4 cop[N / 16];
 #pragma unroll
-        for (int st = 0; st < N / 16; ++st) cop[st] = *reinterpret_cast<const uint4 *>(sC + t * NS + (16 * st + 8 * lh) * 2);
+        for (int st = 0; st < N / 16; ++st) cop[st] = *reinterpret_cast<const uint4 *>(sC + t * (N * 2) + (((2 * st + lh) ^ Ld::swz(t)) * 16));
         // ---- G^T = B C^T, then this wave's share of M^T: masked, decayed, scaled, D on the diagonal; head and tail to LDS ----
         {
             f16v gacc = {0};
 #pragma unroll
             for (int st = 0; st < N / 16; ++st)
-                gacc = mfma(as_bf8(*reinterpret_cast<const uint4 *>(sB + li * NS + (16 * st + 8 * lh) * 2)), as_bf8(cop[st]), gacc);
+                gacc = mfma(as_bf8(*reinterpret_cast<const uint4 *>(sB + li * (N * 2) + (((2 * st + lh) ^ Ld::swz(li)) * 16))), as_bf8(cop[st]), gacc);
             // registers 4 q .. 4 q + 3 of G^T -> M^T for tokens s = 8 q + 4 lh + [0, 4); r = the quad's index within the wave's share
             auto finish = [&](int q, int r, float g0, float g1, float g2, float g3) {
                 const int s0 = 8 * q + 4 * lh;
@@ -454,7 +467,8 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
             *reinterpret_cast<uint2 *>(sY + t * Ld::YS + (8 * q + 4 * lh) * 2) = QV::encode(yv);
         }
         __builtin_amdgcn_wave_barrier();                // the tile waits in the wave's LDS patch: flush_outputs
-        __syncthreads();     // the next chunk overwrites X, B, C
+        wait_direct_loads();                            // this wave's share of the next chunk's inputs has landed ...
+        __syncthreads();     // ... and so has everybody's; the next chunk overwrites X, B^T, M
     }
 
     flush_outputs(n_chunks - 1);
