@@ -316,14 +316,15 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
                 const float4 w0 = *reinterpret_cast<const float4 *>(sW + 8 * oct), w1 = *reinterpret_cast<const float4 *>(sW + 8 * oct + 4);
                 const float wv[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
                 uint32_t bh[4], bl[4];
+                // B[token 8 oct + j][n] out of the swizzled rows: the piece index of n, XORed with the row's key (the same
+                // in all lanes), plus what does not depend on j - one instruction per element
+                const int piece16 = (n >> 3) * 16, rest = (n & 7) * 2 + oct * (8 * N * 2);
+                auto b_at = [&](int j) {
+                    const int key16 = Ld::swz(8 * oct + j) * 16;
+                    return Vec::decode1(*reinterpret_cast<const uint16_t *>(sB + ((piece16 ^ key16) + rest) + j * (N * 2)));
+                };
 #pragma unroll
-                for (int j2 = 0; j2 < 4; ++j2)
-                {
-                    const int r0 = 8 * oct + 2 * j2, r1 = r0 + 1;       // B[token][n] out of the swizzled rows
-                    const float b0 = Vec::decode1(*reinterpret_cast<const uint16_t *>(sB + r0 * (N * 2) + (((n >> 3) ^ Ld::swz(r0)) * 16) + (n & 7) * 2));
-                    const float b1 = Vec::decode1(*reinterpret_cast<const uint16_t *>(sB + r1 * (N * 2) + (((n >> 3) ^ Ld::swz(r1)) * 16) + (n & 7) * 2));
-                    split2(wv[2 * j2] * b0, wv[2 * j2 + 1] * b1, bh[j2], bl[j2]);
-                }
+                for (int j2 = 0; j2 < 4; ++j2) split2(wv[2 * j2] * b_at(2 * j2), wv[2 * j2 + 1] * b_at(2 * j2 + 1), bh[j2], bl[j2]);
                 *reinterpret_cast<uint4 *>(sBh + n * XS + oct * 16) = make_uint4(bh[0], bh[1], bh[2], bh[3]);
                 *reinterpret_cast<uint4 *>(sBl + n * XS + oct * 16) = make_uint4(bl[0], bl[1], bl[2], bl[3]);
             }
