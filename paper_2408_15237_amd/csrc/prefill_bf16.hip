@@ -33,6 +33,7 @@ namespace ssmv {
 
 typedef float f16v __attribute__((ext_vector_type(16)));
 typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
 
 namespace {
 
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
     extern __shared__ float4 lds_raw[];
     char *lds = reinterpret_cast<char *>(lds_raw);
     char *sX = lds + Ld::oX, *sBh = lds + Ld::oBh, *sBl = lds + Ld::oBl, *sMh = lds + Ld::oMh, *sMl = lds + Ld::oMl, *sXraw = lds + Ld::oXraw;
-    float *sCar = reinterpret_cast<float *>(lds + Ld::oCar);
+    uint32_t *sCar = reinterpret_cast<uint32_t *>(lds + Ld::oCar);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lh = lane >> 5;           // MFMA: row/column index and k half of this lane
@@ -187,9 +188,9 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
     const int pc = tid % P;
     const int sg = P >= 64 ? __builtin_amdgcn_readfirstlane(tid / P) : tid / P;      // uniform over a wave when P >= 64
     const unsigned ch = hd * P + pc;
-    float wgt[W];
-#pragma unroll
-    for (int w = 0; w < W; ++w) wgt[w] = load_io(p.wgt, (size_t)ch * W + w, SSMV_BF16);
+    // the four taps as two packed pairs (they are bf16 in memory): the conv is two bf16 dot products per token
+    const uint2 wraw = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(p.wgt) + (size_t)ch * W);
+    const bf2 w01 = __builtin_bit_cast(bf2, wraw.x), w23 = __builtin_bit_cast(bf2, wraw.y);
     const float cbias = p.bias ? load_io(p.bias, ch, SSMV_BF16) : 0.f;
     // One base pointer per tensor that is uniform over the workgroup plus an element offset; tokens are clamped into
     // the prompt, so every load is unconditional: a token before the prompt is replaced by the ring history, tokens past
@@ -204,10 +205,10 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
     auto clampL = [&](int tg) { return tg < 0 ? 0 : (tg < L ? tg : L - 1); };
     auto raw_bits = [&](int tg) { return (uint32_t)(x_b + (size_t)clampL(tg) * HP)[ch]; };    // uniform row pointer, 32-bit lane offset
     // the W-1 raw inputs ahead of the prompt (newest last)
-    float hist[W - 1];
+    uint32_t hist[W - 1];                               // as bits
 #pragma unroll
     for (int j = 0; j < W - 1; ++j)
-        hist[j] = load_io(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 - (W - 1) + j) & mask)) * HP + ch, SSMV_BF16);
+        hist[j] = reinterpret_cast<const uint16_t *>(p.ring)[((size_t)b * p.ring_len + ((conv_head + 1 - (W - 1) + j) & mask)) * HP + ch];
 
     constexpr int UI = (4 * N + NT - 1) / NT;           // (n, eight tokens) units of the transposed B per thread and chunk
     // The chunk's raw x, B and C rows go from global memory straight into LDS, 1 KB per wave and instruction (lane l's 16
@@ -264,35 +265,31 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
             // raw inputs: [token][channel] in LDS; the three ahead of this thread's tokens are the ring history (first chunk),
             // what the other half's threads left of the previous chunk, or simply earlier rows of this one
             const uint16_t *xin = reinterpret_cast<const uint16_t *>(sXraw) + pc;
-            float tap[W - 1];
+            uint32_t xb[QS + W - 1];                    // the raw inputs of tokens s0 - 3 .. s0 + QS - 1, as bits
             if (s0 != 0) {
 #pragma unroll
-                for (int j = 0; j < W - 1; ++j) tap[j] = Vec::decode1(xin[(s0 - (W - 1) + j) * P]);
+                for (int j = 0; j < W - 1; ++j) xb[j] = xin[(s0 - (W - 1) + j) * P];
             } else if (c == 0) {
 #pragma unroll
-                for (int j = 0; j < W - 1; ++j) tap[j] = hist[j];
+                for (int j = 0; j < W - 1; ++j) xb[j] = hist[j];
             } else {
 #pragma unroll
-                for (int j = 0; j < W - 1; ++j) tap[j] = sCar[(((c - 1) & 1) * 3 + j) * P + pc];
+                for (int j = 0; j < W - 1; ++j) xb[j] = sCar[(((c - 1) & 1) * 3 + j) * P + pc];
             }
-            float t1 = tap[0], t2 = tap[1], t3 = tap[2];
+#pragma unroll
+            for (int j = 0; j < QS; ++j) xb[j + W - 1] = xin[(s0 + j) * P];
+            // x_t = bias + (w0, w1).(r_(t-3), r_(t-2)) + (w2, w3).(r_(t-1), r_t): bf16 products are exact in fp32, the sums
+            // are fp32 (v_dot2c_f32_bf16); adjacent raw inputs are packed once and serve two tokens
+            bf2 pk[QS + 2];
+#pragma unroll
+            for (int i = 0; i < QS + 2; ++i) pk[i] = __builtin_bit_cast(bf2, xb[i] | (xb[i + 1] << 16));
             float xv[QS];
 #pragma unroll
-            for (int j = 0; j < QS; ++j) {
-                const float r = Vec::decode1(xin[(s0 + j) * P]);
-                // same fp32 order and rounding as conv1d_state_update
-                float acc = cbias;
-                acc = fmaf(wgt[0], t1, acc);
-                acc = fmaf(wgt[1], t2, acc);
-                acc = fmaf(wgt[2], t3, acc);
-                acc = fmaf(wgt[3], r, acc);
-                xv[j] = acc;
-                t1 = t2; t2 = t3; t3 = r;
-            }
+            for (int j = 0; j < QS; ++j)
+                xv[j] = __builtin_amdgcn_fdot2_f32_bf16(w23, pk[j + 2], __builtin_amdgcn_fdot2_f32_bf16(w01, pk[j], cbias, false), false);
             if (s0 + QS == Q) {                         // the chunk's last three raw inputs, for the next chunk
-                sCar[((c & 1) * 3 + 0) * P + pc] = t1;
-                sCar[((c & 1) * 3 + 1) * P + pc] = t2;
-                sCar[((c & 1) * 3 + 2) * P + pc] = t3;
+#pragma unroll
+                for (int j = 0; j < W - 1; ++j) sCar[((c & 1) * 3 + j) * P + pc] = xb[QS + j];
             }
             if (silu) {
 #pragma unroll
