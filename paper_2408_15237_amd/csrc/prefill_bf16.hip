@@ -54,9 +54,13 @@ struct PfLds {              // byte offsets of the LDS arrays (bf16 unless said)
     // filled by loads that go from global memory straight into LDS (1 KB per wave and instruction, lane l at byte 16 l):
     static constexpr int oXraw = oY + NW * kQ * YS;        // [Q][P]  raw conv inputs of the chunk, rows of 2 P bytes
     static constexpr int BCS = kQ * N * 2;                 // one copy of B or C: [Q][N], rows of 2 N bytes, 16-byte pieces swizzled
-    static constexpr int oB = oXraw + kQ * P * 2;          // two copies (chunks alternate): the next chunk's arrive while this one's are read
-    static constexpr int oC = oB + 2 * BCS;
-    static constexpr int oCar = oC + 2 * BCS;              // fp32 [2][3][P]  the last three raw inputs of a chunk, for the next one's conv
+    // Wide heads keep two copies of B and C (chunks alternate; the next chunk's are requested at the start of this one's
+    // arithmetic).  Narrow heads (few waves per workgroup, so the number of workgroups per CU matters more) keep one and
+    // request the next chunk's B and C only once this chunk's have been read (after the barrier in the middle).
+    static constexpr int BCC = P >= 128 ? 2 : 1;
+    static constexpr int oB = oXraw + kQ * P * 2;
+    static constexpr int oC = oB + BCC * BCS;
+    static constexpr int oCar = oC + BCC * BCS;              // fp32 [2][3][P]  the last three raw inputs of a chunk, for the next one's conv
     static constexpr int oCum = oCar + 2 * 3 * P * 4;      // fp32 [NW][Q]  log2 e times the inclusive prefix of dt*A (a copy per wave)
     static constexpr int oDt = oCum + NW * kQ * 4;         // fp32 [NW][Q]  dt
     static constexpr int oW = oDt + NW * kQ * 4;           // fp32 [NW][Q]  exp(cum_Q - cum_s) dt_s
@@ -214,7 +218,7 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
     // The chunk's raw x, B and C rows go from global memory straight into LDS, 1 KB per wave and instruction (lane l's 16
     // bytes land at byte 16 l of the destination): no registers hold them while they are under way, and a chunk costs a
     // wave 4 to 6 load instructions instead of 30.  dt (one value per lane) takes the ordinary way.
-    auto issue_loads = [&](int c, uint32_t &dt_bits) {
+    auto issue_x_loads = [&](int c, uint32_t &dt_bits) {
         const int t0 = c * Q;
         auto tok = [&](int row) { return min(t0 + row, L - 1); };
         constexpr int LR = P / 8;                       // lanes per row of x, 64 / LR rows per instruction, two instructions per wave
@@ -224,7 +228,12 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
             const int row = idx * (64 / LR) + lane / LR, piece = lane % LR;
             load_to_lds16(x_b + off(tok(row), HP, hd * P + piece * 8), sXraw + idx * 1024);
         }
-        char *dB = lds + Ld::oB + (c & 1) * Ld::BCS, *dC = lds + Ld::oC + (c & 1) * Ld::BCS;
+        dt_bits = dt_b[off(tok(li), H, 0)];
+    };
+    auto issue_bc_loads = [&](int c) {
+        const int t0 = c * Q;
+        auto tok = [&](int row) { return min(t0 + row, L - 1); };
+        char *dB = lds + Ld::oB + (c & (Ld::BCC - 1)) * Ld::BCS, *dC = lds + Ld::oC + (c & (Ld::BCC - 1)) * Ld::BCS;
 #pragma unroll
         for (int k = 0; k < (PIECES / 2 + Ld::NW - 1) / Ld::NW; ++k) {
             const int idx = wave_u + k * Ld::NW;        // PIECES / 2 instructions cover the 32 rows
@@ -235,13 +244,12 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
                 load_to_lds16(C_b + o, dC + idx * 1024);
             }
         }
-        dt_bits = dt_b[off(tok(li), H, 0)];
     };
     // Per chunk, of this lane's token t = li: log2 e * cum_t and exp(cum_t); and exp(cum_Q) (the same in every lane).
     float cum_t, at_t, aq;
     auto consume = [&](int c, uint32_t dt_bits) {
         const int t0 = c * Q, s0 = sg * QS;
-        const char *sB = lds + Ld::oB + (c & 1) * Ld::BCS;
+        const char *sB = lds + Ld::oB + (c & (Ld::BCC - 1)) * Ld::BCS;
         // ---- dt, its prefix sums and the decay factors: every wave for itself (32 tokens, both halves alike) ----
         {
             float d = Vec::decode1(dt_bits) + dtb_h;
@@ -345,15 +353,19 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
     const int n_chunks = (L + Q - 1) / Q;
     const int prow = wave * 32 + li;                    // this lane's channel (inside the head) as an operand row
     uint32_t dt_bits;
-    issue_loads(0, dt_bits);
+    issue_x_loads(0, dt_bits);
+    issue_bc_loads(0);
     wait_direct_loads();
     __syncthreads();
     for (int c = 0; c < n_chunks; ++c) {
         const int t0 = c * Q;
-        const char *sB = lds + Ld::oB + (c & 1) * Ld::BCS, *sC = lds + Ld::oC + (c & 1) * Ld::BCS;
+        const char *sB = lds + Ld::oB + (c & (Ld::BCC - 1)) * Ld::BCS, *sC = lds + Ld::oC + (c & (Ld::BCC - 1)) * Ld::BCS;
         consume(c, dt_bits);
         __syncthreads();
-        if (c + 1 < n_chunks) issue_loads(c + 1, dt_bits);         // under way for the whole chunk
+        if (c + 1 < n_chunks) {                         // under way for the whole chunk
+            issue_x_loads(c + 1, dt_bits);
+            if (Ld::BCC == 2) issue_bc_loads(c + 1);
+        }
         if (c > 0) flush_outputs(c - 1);
         __builtin_amdgcn_sched_barrier(0);              // the loads and stores stay here, a chunk of arithmetic ahead of the next wait
 
@@ -433,7 +445,8 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
         uint4 xop[2];
 #pragma unroll
         for (int st = 0; st < 2; ++st) xop[st] = *reinterpret_cast<const uint4 *>(sX + prow * XS + (16 * st + 8 * lh) * 2);
-        __syncthreads();     // M^T is complete
+        __syncthreads();     // M^T is complete; nobody reads this chunk's B and C rows any more
+        if (Ld::BCC == 1 && c + 1 < n_chunks) issue_bc_loads(c + 1);
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
             const int o = t * XS + (16 * st + 8 * lh) * 2;
