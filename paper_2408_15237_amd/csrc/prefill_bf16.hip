@@ -54,10 +54,11 @@ struct PfLds {              // byte offsets of the LDS arrays (bf16 unless said)
     // filled by loads that go from global memory straight into LDS (1 KB per wave and instruction, lane l at byte 16 l):
     static constexpr int oXraw = oY + NW * kQ * YS;        // [Q][P]  raw conv inputs of the chunk, rows of 2 P bytes
     static constexpr int BCS = kQ * N * 2;                 // one copy of B or C: [Q][N], rows of 2 N bytes, 16-byte pieces swizzled
-    // Wide heads keep two copies of B and C (chunks alternate; the next chunk's are requested at the start of this one's
-    // arithmetic).  Narrow heads (few waves per workgroup, so the number of workgroups per CU matters more) keep one and
-    // request the next chunk's B and C only once this chunk's have been read (after the barrier in the middle).
-    static constexpr int BCC = P >= 128 ? 2 : 1;
+    // Two copies of B and C (chunks alternate; the next chunk's are requested at the start of this one's arithmetic) where
+    // that does not cost a workgroup per CU; else one copy, and the next chunk's B and C are requested only once this
+    // chunk's have been read (after the barrier in the middle): narrow heads (few waves per workgroup: 48 KB -> 40 KB
+    // is a fourth workgroup per CU) and N = 128 (90 KB -> 74 KB is a second one).
+    static constexpr int BCC = (P >= 128 && N < 128) ? 2 : 1;
     static constexpr int oB = oXraw + kQ * P * 2;
     static constexpr int oC = oB + BCC * BCS;
     static constexpr int oCar = oC + BCC * BCS;              // fp32 [2][3][P]  the last three raw inputs of a chunk, for the next one's conv
