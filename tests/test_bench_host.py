@@ -1,0 +1,60 @@
+"""Host logic of bench.py (no GPU): the pending-token schedule behind its byte counts against the integer model of the
+cache, the algorithmic byte count of a launch against hand-computed cases, and the refusal of more than one GPU."""
+import os
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from workload import CONFIGS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+import bench  # noqa: E402
+
+
+@pytest.mark.parametrize("hj_only", [False, True])
+def test_pending_schedule_matches_the_integer_model(hj_only):
+    """bench.pend_after predicts, per round, how many accepted tokens each sequence still has to replay; the kernels'
+    byte counts hang on it.  The integer model of the cache (commit rules of Algorithm 2 with lazy folding) is the
+    authority: run it over the same acceptance history."""
+    rng = np.random.default_rng(5)
+    batch, k, rounds = 7, 4, 40
+    accepted = [rng.integers(0, k + 1, size=batch) for _ in range(rounds)]
+    sched = bench.pend_after(accepted, [k] * rounds, hj_only=hj_only)
+    bk = oracle.BookkeepingModel(batch, ring_len=8, conv_width=4, hj_only=hj_only)
+    for r in range(rounds):
+        assert sched[r].tolist() == list(bk.pend), "before round %d" % r
+        bk.verify(k)
+        bk.commit(accepted[r])
+
+
+def test_algorithmic_bytes_of_a_launch_by_hand():
+    """cfg1 (one sequence, 32 heads x 128 x 64, k = 4, bf16 tensors, fp32 state): S = 1 MiB.  Nothing pending: the state is
+    read once and written once; two tokens pending: a second snapshot and their stashed inputs on top."""
+    wl = CONFIGS["cfg1"]
+    S = 32 * 128 * 64 * 4
+    Cx, H, N, k, e = 4096, 32, 64, 4, 2
+    tokens_in = k * (Cx + H + 2 * N) * e
+    y_out = k * Cx * e
+    stash_out = k * (Cx + H + N) * e
+    assert bench.verify_bytes(wl, [0], k, fused=False) == 2 * S + tokens_in + y_out + stash_out
+    pending_in = 2 * (Cx + H + N) * e
+    assert bench.verify_bytes(wl, [2], k, fused=False) == 3 * S + tokens_in + y_out + stash_out + pending_in
+    # conv roll fused in: the ring append, three history rows, four taps and the bias per channel come on top
+    fused_extra = (k * Cx + 3 * Cx + 5 * Cx) * e
+    assert bench.verify_bytes(wl, [2], k, fused=True) == bench.verify_bytes(wl, [2], k, fused=False) + fused_extra
+    # the single-snapshot variant never writes h_k
+    assert bench.verify_bytes(wl.scaled(snapshot_mode="hj_only"), [2], k, fused=False) == bench.verify_bytes(wl, [2], k, fused=False) - S
+    # a whole split round = the verify launch plus the conv launch (raw in, ring append, xc out, history, weights)
+    conv_launch = (k * Cx * 3 + 3 * Cx + 5 * Cx) * e
+    assert bench.round_bytes(wl, [0], k, fused=False) == bench.verify_bytes(wl, [0], k, fused=False) + conv_launch
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and "--gpus 1" in r.stderr
+    assert r.stdout.strip() == ""
