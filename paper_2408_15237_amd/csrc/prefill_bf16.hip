@@ -40,19 +40,25 @@ namespace {
 constexpr int kQ = 32;      // tokens per chunk
 constexpr float kLog2e = 1.4426950408889634f;
 
+// waves per 32-channel tile: a large state under a narrow head is split over n
+__host__ __device__ constexpr int prefill_nsplit(int P, int N) { return (N >= 128 && P <= 64) ? 2 : 1; }
+
 template <int P, int N>
 struct PfLds {              // byte offsets of the LDS arrays (bf16 unless said)
     static constexpr int XS = kQ * 2 + 16;                 // row stride of the arrays indexed [..][token]
-    static constexpr int NW = P / 32;                      // waves
+    static constexpr int NP = P / 32;                      // 32-channel tiles of the head
+    static constexpr int NSPL = prefill_nsplit(P, N);
+    static constexpr int NW = NP * NSPL;                   // waves
     static constexpr int oX = 0;                           // [P][Q]  conv output x_s
     static constexpr int oBh = oX + P * XS;                // [N][Q]  head of w_s B_s, transposed
     static constexpr int oBl = oBh + N * XS;               // [N][Q]  tail of w_s B_s, transposed
     static constexpr int oMh = oBl + N * XS;               // [Q][Q]  head of M^T, rows t
     static constexpr int oMl = oMh + kQ * XS;              // [Q][Q]  tail of M^T
     static constexpr int YS = 32 * 2 + 16;                 // row stride of a wave's output tile [token][32 channels]
-    static constexpr int oY = oMl + kQ * XS;               // [NW][Q][32]  the waves' output tiles, for stores of whole 64-byte rows
+    static constexpr int oY = oMl + kQ * XS;               // [NP][Q][32]  the output tiles, for stores of whole 64-byte rows
     // filled by loads that go from global memory straight into LDS (1 KB per wave and instruction, lane l at byte 16 l):
-    static constexpr int oXraw = oY + NW * kQ * YS;        // [Q][P]  raw conv inputs of the chunk, rows of 2 P bytes
+    static constexpr int oZ = oY + NP * kQ * YS;           // fp32 [NP][16][64]  h C^T over the second half of n, for the tile's first wave
+    static constexpr int oXraw = oZ + (NSPL - 1) * NP * 4096;        // [Q][P]  raw conv inputs of the chunk, rows of 2 P bytes
     static constexpr int BCS = kQ * N * 2;                 // one copy of B or C: [Q][N], rows of 2 N bytes, 16-byte pieces swizzled
     // Two copies of B and C (chunks alternate; the next chunk's are requested at the start of this one's arithmetic) where
     // that does not cost a workgroup per CU; else one copy, and the next chunk's B and C are requested only once this
@@ -123,16 +129,23 @@ __device__ __forceinline__ int swap23(int i) { return (i & ~12) | ((i & 4) << 1)
 }  // namespace
 
 // Two waves per SIMD (256 registers each, and then the compiler keeps the accumulators in ordinary registers: no copies
-// between the two register files around every use); a state of N = 128 (64 registers per lane) does not fit that.
+// between the two register files around every use); a tile's state of N = 128 in one wave (64 registers per lane) does
+// not fit that.
+// A state of N = 128 under a narrow head (P <= 64) is split over two waves per 32-channel tile, each with half of n: the
+// second adds its share of h C^T through LDS, both update their own half of the state, and the workgroup has twice the
+// threads for the staging.
 template <int P, int N>
-__global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 ? 1 : 2))) void prefill_bf16_kernel(const PrefillParams p)
+__global__ __launch_bounds__(2 * P * prefill_nsplit(P, N)) __attribute__((amdgpu_waves_per_eu((N >= 128 && prefill_nsplit(P, N) == 1) ? 1 : 2)))
+void prefill_bf16_kernel(const PrefillParams p)
 {
+    using Ld = PfLds<P, N>;
     constexpr int Q = kQ;
     constexpr int W = SSMV_CONV_WIDTH;
-    constexpr int NT = 2 * P;            // threads: one wave per 32 channels
+    constexpr int NSPL = Ld::NSPL;
+    constexpr int NT = 2 * P * NSPL;     // threads: one wave per 32 channels (and per half of n where the state is split)
     constexpr int TN = N / 32;
-    constexpr int QS = Q / 2;            // consecutive tokens one thread convolves per chunk (two threads per channel)
-    using Ld = PfLds<P, N>;
+    constexpr int TNL = TN / NSPL;       // state tiles of a wave
+    constexpr int QS = Q * P / NT;       // consecutive tokens one thread convolves per chunk (NT / P threads per channel)
     constexpr int XS = Ld::XS, PIECES = Ld::PIECES;
     using Vec = IoVec<SSMV_BF16>;
     constexpr int EV = Vec::EV;
@@ -147,7 +160,9 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
     const int li = lane & 31, lh = lane >> 5;           // MFMA: row/column index and k half of this lane
     const int lperm = swap23(li);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    char *sY = lds + Ld::oY + wave * (Q * Ld::YS);
+    const int pt = Ld::NSPL == 1 ? wave_u : wave_u % Ld::NP;   // the wave's 32-channel tile
+    const int nh = Ld::NSPL == 1 ? 0 : wave_u / Ld::NP;        // and its half of n (0 unless the state is split)
+    char *sY = lds + Ld::oY + pt * (Q * Ld::YS);
     float *sCum = reinterpret_cast<float *>(lds + Ld::oCum) + wave * Q;
     float *sDt = reinterpret_cast<float *>(lds + Ld::oDt) + wave * Q;
     float *sW = reinterpret_cast<float *>(lds + Ld::oW) + wave * Q;
@@ -168,11 +183,11 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
     float *state = p.state + (size_t)cur * p.slot_stride + ((size_t)b * H + hd) * P * N;
 
     // state -> accumulator registers, transposed tiles [n][p]: register 4 q + e of tile tn holds
-    // h[p = 32 wave + li][n = 32 tn + 16 (q/2) + 8 lh + 4 (q%2) + e]
-    f16v hacc[TN];
-    const size_t srow = (size_t)(wave * 32 + li) * N + 8 * lh;
+    // h[p = 32 pt + li][n = 32 (TNL nh + tn) + 16 (q/2) + 8 lh + 4 (q%2) + e]
+    f16v hacc[TNL];
+    const size_t srow = (size_t)(pt * 32 + li) * N + 32 * TNL * nh + 8 * lh;
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn)
+    for (int tn = 0; tn < TNL; ++tn)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const float4 v = *reinterpret_cast<const float4 *>(state + srow + 32 * tn + 16 * (q / 2) + 4 * (q % 2));
@@ -222,10 +237,11 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
     auto issue_x_loads = [&](int c, uint32_t &dt_bits) {
         const int t0 = c * Q;
         auto tok = [&](int row) { return min(t0 + row, L - 1); };
-        constexpr int LR = P / 8;                       // lanes per row of x, 64 / LR rows per instruction, two instructions per wave
+        constexpr int LR = P / 8;                       // lanes per row of x, 64 / LR rows per instruction, P / 16 instructions
+        constexpr int XPW = 2 / NSPL;                   // of them per wave
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const int idx = 2 * wave_u + k;
+        for (int k = 0; k < XPW; ++k) {
+            const int idx = XPW * wave_u + k;
             const int row = idx * (64 / LR) + lane / LR, piece = lane % LR;
             load_to_lds16(x_b + off(tok(row), HP, hd * P + piece * 8), sXraw + idx * 1024);
         }
@@ -348,11 +364,12 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
         for (int r = 0; r < 2; ++r) {
             const int tt = 16 * r + (lane >> 2), piece = lane & 3;
             const uint4 v = *reinterpret_cast<const uint4 *>(sY + tt * Ld::YS + piece * 16);
-            if (t0 + tt < L) Vec::store_raw(y_b, off(t0 + tt, HP, hd * P + wave * 32 + piece * 8), v);
+            if (t0 + tt < L) Vec::store_raw(y_b, off(t0 + tt, HP, hd * P + pt * 32 + piece * 8), v);
         }
     };
     const int n_chunks = (L + Q - 1) / Q;
-    const int prow = wave * 32 + li;                    // this lane's channel (inside the head) as an operand row
+    const int prow = pt * 32 + li;                      // this lane's channel (inside the head) as an operand row
+    float *sZ = reinterpret_cast<float *>(lds + Ld::oZ) + pt * 1024;
     uint32_t dt_bits;
     issue_x_loads(0, dt_bits);
     issue_bc_loads(0);
@@ -367,17 +384,17 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
             issue_x_loads(c + 1, dt_bits);
             if (Ld::BCC == 2) issue_bc_loads(c + 1);
         }
-        if (c > 0) flush_outputs(c - 1);
+        if (c > 0 && nh == 0) flush_outputs(c - 1);
         __builtin_amdgcn_sched_barrier(0);              // the loads and stores stay here, a chunk of arithmetic ahead of the next wait
 
         const int t = li;                               // this lane's token within the chunk
         const bool live = t0 + t < L;
         using QV = XVec<SSMV_BF16, 4>;                  // four adjacent channels
         typename QV::Raw zraw[4];
-        if (gated) {                                    // requested ahead of the matrix products
+        if (gated && nh == 0) {                         // requested ahead of the matrix products
             const int tc = live ? t0 + t : L - 1;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) zraw[q] = QV::load(z_b, off(tc, HP, hd * P + wave * 32 + 8 * q + 4 * lh));
+            for (int q = 0; q < 4; ++q) zraw[q] = QV::load(z_b, off(tc, HP, hd * P + pt * 32 + 8 * q + 4 * lh));
         }
         // C of this lane's token, all of it: the B operand of G^T and of h C^T
         uint4 cop[N / 16];
@@ -430,45 +447,66 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
         // ---- Y^T = h C^T, scaled by exp(cum_t): the state registers are the A operand ----
         f16v yacc = {0};
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
+        for (int tn = 0; tn < TNL; ++tn)
 #pragma unroll
             for (int st = 0; st < 2; ++st) {
                 uint32_t ah[4], al[4];
 #pragma unroll
                 for (int d = 0; d < 4; ++d) split2(hacc[tn][8 * st + 2 * d], hacc[tn][8 * st + 2 * d + 1], ah[d], al[d]);
-                const bf8 cb = as_bf8(cop[2 * tn + st]);
+                // C for the wave's own tiles: with a split state read again at the wave's offset (a choice between
+                // registers by a variable would put the array into scratch memory)
+                uint4 c4;
+                if constexpr (NSPL == 2) c4 = *reinterpret_cast<const uint4 *>(sC + t * (N * 2) + (((2 * (2 * (TNL * nh + tn) + st) + lh) ^ Ld::swz(t)) * 16));
+                else c4 = cop[2 * tn + st];
+                const bf8 cb = as_bf8(c4);
                 yacc = mfma(as_bf8(ah[0], ah[1], ah[2], ah[3]), cb, yacc);
                 yacc = mfma(as_bf8(al[0], al[1], al[2], al[3]), cb, yacc);
             }
+        if constexpr (NSPL == 2) {
+            if (nh == 1) {                              // the second half of n: hand the sum to the tile's first wave
 #pragma unroll
-        for (int v = 0; v < 16; ++v) yacc[v] *= at_t;
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<float4 *>(sZ + q * 256 + lane * 4) = make_float4(yacc[4 * q], yacc[4 * q + 1], yacc[4 * q + 2], yacc[4 * q + 3]);
+            }
+        }
         // ---- Y^T += X^T M^T;  h^T <- exp(cum_Q) h^T + (diag(w) B)^T X: X is the A operand of one, the B operand of the other ----
         uint4 xop[2];
 #pragma unroll
         for (int st = 0; st < 2; ++st) xop[st] = *reinterpret_cast<const uint4 *>(sX + prow * XS + (16 * st + 8 * lh) * 2);
         __syncthreads();     // M^T is complete; nobody reads this chunk's B and C rows any more
         if (Ld::BCC == 1 && c + 1 < n_chunks) issue_bc_loads(c + 1);
+        if (nh == 0) {
+            if constexpr (NSPL == 2) {
 #pragma unroll
-        for (int st = 0; st < 2; ++st) {
-            const int o = t * XS + (16 * st + 8 * lh) * 2;
-            yacc = mfma(as_bf8(xop[st]), as_bf8(*reinterpret_cast<const uint4 *>(sMh + o)), yacc);
-            yacc = mfma(as_bf8(xop[st]), as_bf8(*reinterpret_cast<const uint4 *>(sMl + o)), yacc);
+                for (int q = 0; q < 4; ++q) {
+                    const float4 z4 = *reinterpret_cast<const float4 *>(sZ + q * 256 + lane * 4);
+                    yacc[4 * q] += z4.x; yacc[4 * q + 1] += z4.y; yacc[4 * q + 2] += z4.z; yacc[4 * q + 3] += z4.w;
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) yacc[v] *= at_t;
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+                const int o = t * XS + (16 * st + 8 * lh) * 2;
+                yacc = mfma(as_bf8(xop[st]), as_bf8(*reinterpret_cast<const uint4 *>(sMh + o)), yacc);
+                yacc = mfma(as_bf8(xop[st]), as_bf8(*reinterpret_cast<const uint4 *>(sMl + o)), yacc);
+            }
         }
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
+        for (int tn = 0; tn < TNL; ++tn) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) hacc[tn][v] *= aq;
 #pragma unroll
             for (int st = 0; st < 2; ++st) {
-                const int o = (32 * tn + lperm) * XS + (16 * st + 8 * lh) * 2;
+                const int o = (32 * (TNL * nh + tn) + lperm) * XS + (16 * st + 8 * lh) * 2;
                 hacc[tn] = mfma(as_bf8(*reinterpret_cast<const uint4 *>(sBh + o)), as_bf8(xop[st]), hacc[tn]);
                 hacc[tn] = mfma(as_bf8(*reinterpret_cast<const uint4 *>(sBl + o)), as_bf8(xop[st]), hacc[tn]);
             }
         }
         // ---- gate, store ----
+        if (nh == 0) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int pl = wave * 32 + 8 * q + 4 * lh;      // first of the four channels (inside the head)
             float yv[4] = {yacc[4 * q + 0], yacc[4 * q + 1], yacc[4 * q + 2], yacc[4 * q + 3]};
             if (gated) {
                 float zf[4];
@@ -478,15 +516,16 @@ __global__ __launch_bounds__(2 * P) __attribute__((amdgpu_waves_per_eu(N >= 128 
             }
             *reinterpret_cast<uint2 *>(sY + t * Ld::YS + (8 * q + 4 * lh) * 2) = QV::encode(yv);
         }
+        }
         __builtin_amdgcn_wave_barrier();                // the tile waits in the wave's LDS patch: flush_outputs
         wait_direct_loads();                            // this wave's share of the next chunk's inputs has landed ...
         __syncthreads();     // ... and so has everybody's; the next chunk overwrites X, B^T, M
     }
 
-    flush_outputs(n_chunks - 1);
+    if (nh == 0) flush_outputs(n_chunks - 1);
     // ---- state back in place; the newest W-1 raw inputs into the ring behind conv_head -----------------------
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn)
+    for (int tn = 0; tn < TNL; ++tn)
 #pragma unroll
         for (int q = 0; q < 4; ++q)
             *reinterpret_cast<float4 *>(state + srow + 32 * tn + 16 * (q / 2) + 4 * (q % 2)) =
@@ -501,7 +540,7 @@ template <int P, int N>
 static int launch_pn(const PrefillParams &p, hipStream_t stream)
 {
     const size_t lds = PfLds<P, N>::total;
-    const dim3 grid(p.H * p.batch), block(2 * P);
+    const dim3 grid(p.H * p.batch), block(2 * P * PfLds<P, N>::NSPL);
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<P, N>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return (int)e;
     hipLaunchKernelGGL((prefill_bf16_kernel<P, N>), grid, block, lds, stream, p);
