@@ -39,6 +39,9 @@ def parse_args():
     ap.add_argument("--rows", type=int, default=0, help="verify kernel: state rows per lane (0 = auto)")
     ap.add_argument("--waves", type=int, default=0, help="verify kernel: waves per workgroup (0 = auto)")
     ap.add_argument("--kernel-only", action="store_true", help="only the verify-kernel loop (for rocprofv3 runs)")
+    ap.add_argument("--engine", choices=["auto", "vector"], default="auto",
+                    help="auto: the library picks (the matrix-core kernel on a tiled state where it applies); "
+                         "vector: the vector-ALU kernel on a row-major state")
     ap.add_argument("--single-snapshot", action="store_true",
                     help="the single-snapshot variant: h_k is never stored, every accepted token is replayed next round")
     ap.add_argument("--naive", action="store_true",
@@ -130,7 +133,7 @@ def bench_prefill(args):
     io_t = torch.bfloat16 if wl.io == "bf16" else torch.float32
     dev = "cuda"
     dims = ssmv.make_dims(wl.batch, wl.nheads, wl.headdim, wl.dstate, ngroups=wl.ngroups, kmax=wl.kmax_eff, ring_len=wl.ring_len,
-                          io=wl.io, a_mode=wl.a_mode, conv_act=wl.conv_act)
+                          io=wl.io, a_mode=wl.a_mode, conv_act=wl.conv_act, engine=args.engine)
     up = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).to(io_t).contiguous()
     A, D = torch.from_numpy(lp.A).to(dev), torch.from_numpy(lp.D).to(dev)
     conv_w, conv_b = up(lp.conv_w), (None if lp.conv_b is None else up(lp.conv_b))
@@ -253,7 +256,7 @@ def main():
 
     dims = ssmv.make_dims(wl.batch, wl.nheads, wl.headdim, wl.dstate, ngroups=wl.ngroups, kmax=wl.kmax_eff,
                           ring_len=wl.ring_len, io=wl.io, a_mode=wl.a_mode, conv_act=wl.conv_act,
-                          snapshot_mode=wl.snapshot_mode)
+                          snapshot_mode=wl.snapshot_mode, engine=args.engine)
     sizes = ssmv.ssmv_cache_sizes(dims)
     cache_bytes = sum(sizes)
     n_inst = args.instances or max(1, math.ceil(args.footprint_gib * 2 ** 30 / cache_bytes))

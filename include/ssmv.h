@@ -63,6 +63,11 @@ enum { SSMV_ACT_NONE = 0, SSMV_ACT_SILU = 1 };  /* conv_act                     
  * a fully accepted round, stays pending and is replayed by the next verify.  Same outputs and same logical
  * state; about a third fewer bytes per round for up to k more replay steps. */
 enum { SSMV_SNAP_BOTH = 0, SSMV_SNAP_HJ_ONLY = 1 };
+/* engine.  AUTO lets the library pick the kernel and with it the layout of the state slots: scalar-A mode with bf16
+ * tokens, headdim a multiple of 64, dstate in {32, 64, 128} and kmax <= 8 (HJ_ONLY: pend can reach kmax, so 2*kmax <= 16)
+ * runs the launch of Section 4.3 on the matrix cores and keeps each (sequence, head) block of a slot in 16x16 tiles;
+ * everything else runs on the vector ALUs with row-major slots.  VECTOR forces the latter.  Same results to rounding. */
+enum { SSMV_ENGINE_AUTO = 0, SSMV_ENGINE_VECTOR = 1 };
 
 #define SSMV_KMAX_LIMIT 16      /* largest supported kmax                   */
 #define SSMV_CONV_WIDTH 4       /* the only supported conv width            */
@@ -82,12 +87,15 @@ typedef struct {
     int32_t a_mode;         /* SSMV_A_SCALAR | SSMV_A_DIAG                                        */
     int32_t conv_act;       /* SSMV_ACT_NONE | SSMV_ACT_SILU                                      */
     int32_t snapshot_mode;  /* SSMV_SNAP_BOTH | SSMV_SNAP_HJ_ONLY                                 */
+    int32_t engine;         /* SSMV_ENGINE_AUTO | SSMV_ENGINE_VECTOR                              */
 } ssmv_dims;
 
 /* The per-layer cache (Section 4.2: one cached state per sequence, advanced lazily;
  * Section 4.3 footnote: the conv inputs as a circular buffer). */
 typedef struct {
-    float   *state;        /* [3][batch][H][P][N] fp32, N fastest: three slots per sequence         */
+    float   *state;        /* three slots of batch*H*P*N fp32, one block of P*N per (sequence, head); the order
+                            * INSIDE a block is the library's (row-major or tiled, see `engine`): bring a state
+                            * in with ssmv_cache_reset and take it out with ssmv_materialize               */
     void    *conv_ring;    /* [batch][R][Cx] io_dtype, channel fastest: raw conv inputs             */
     void    *win_xc[2];    /* [batch][kmax][Cx]   io_dtype: conv outputs of a round (ping-pong)     */
     void    *win_dt[2];    /* [batch][kmax][H]    io_dtype                                          */

@@ -225,11 +225,14 @@ class BookkeepingModel:
         self.last_k = [tok0 + k] * self.batch
 
     def commit(self, accepted) -> None:
-        if self.last_k[0] == 0:
-            self.err = 1          # commit without a verify: nothing to commit
-            return
+        """Per sequence: one with no verify pending (last_k == 0) is left as it is and the sticky error is set.
+        The window parity is one value for the whole batch; it follows sequence 0."""
+        flip = self.last_k[0] != 0
         for b in range(self.batch):
             lk = self.last_k[b]
+            if lk == 0:
+                self.err = 1      # commit without a verify: nothing to commit for this sequence
+                continue
             a = int(accepted[b])
             if a < 0 or a > lk:
                 self.err = 1
@@ -246,7 +249,8 @@ class BookkeepingModel:
                 self.pend[b] = a
             self.conv_head[b] = (self.conv_head[b] + a) & (self.R - 1)
             self.last_k[b] = 0
-        self.win_par ^= 1
+        if flip:
+            self.win_par ^= 1
 
 
 class LazyMirror:
@@ -287,14 +291,18 @@ class LazyMirror:
             g = snap[pd]
         return g[0]
 
-    def verify(self, x_raw, dt, Bm, Cm):
+    def verify(self, x_raw, dt, Bm, Cm, tok0: int = 0):
+        """tok0 > 0: a later call of a round that several calls feed (the draft side of Section 4.3 produces its
+        tokens one call at a time).  It continues from the state the earlier calls left in the h_k slot, advances that
+        slot in place, replays nothing, and appends its tokens to the round's stash and ring behind the tok0 earlier ones."""
         x_raw, dt, Bm, Cm = map(_c, (x_raw, dt, Bm, Cm))
         bk, W, R = self.bk, self.W, self.R
         k = x_raw.shape[1]
-        assert 1 <= k <= self.kmax
+        assert 1 <= k and 0 <= tok0 and tok0 + k <= self.kmax
+        assert tok0 == 0 or not self.hj_only
         raw = np.empty((self.batch, W - 1 + k, self.Cx))
         for b in range(self.batch):
-            head = bk.conv_head[b]
+            head = (bk.conv_head[b] + tok0) & (R - 1)  # newest raw input fed so far
             for t in range(k):                        # append after the head; old committed entries stay
                 self.ring[b, (head + 1 + t) & (R - 1)] = x_raw[b, t]
             for i in range(W - 1 + k):                # oldest needed entry is head-(W-2)
@@ -302,20 +310,23 @@ class LazyMirror:
         xc = conv_causal(raw, self.conv_w, self.conv_b, self.act, self.io)
         y = np.empty((self.batch, k, self.Cx))
         for b in range(self.batch):
-            g = self._replayed(b)
             cur = bk.cur[b]
-            if bk.pend[b] > 0:
-                self.slots[(cur + 1) % 3, b] = g                     # snapshot h_j
+            if tok0 == 0:
+                g = self._replayed(b)
+                if bk.pend[b] > 0:
+                    self.slots[(cur + 1) % 3, b] = g                 # snapshot h_j
+            else:
+                g = self.slots[(cur + 2) % 3, b]                     # where the earlier calls of the round stopped
             yb, snap = scan_tokens(self.a_mode, g[None], xc[b:b + 1], dt[b:b + 1], Bm[b:b + 1], Cm[b:b + 1],
                                    self.A, self.D)
             y[b] = yb[0]
             if not self.hj_only:
                 self.slots[(cur + 2) % 3, b] = snap[k, 0]            # snapshot h_k
         npar = bk.win_par ^ 1
-        self.win_xc[npar, :, :k] = xc
-        self.win_dt[npar, :, :k] = dt
-        self.win_B[npar, :, :k] = Bm
-        bk.verify(k)
+        self.win_xc[npar, :, tok0:tok0 + k] = xc
+        self.win_dt[npar, :, tok0:tok0 + k] = dt
+        self.win_B[npar, :, tok0:tok0 + k] = Bm
+        bk.verify(k, tok0)
         return y, xc
 
     def commit(self, accepted) -> None:

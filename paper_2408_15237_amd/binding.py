@@ -28,6 +28,8 @@ IO_CODES = {"f32": SSMV_F32, "bf16": SSMV_BF16}
 MODE_CODES = {"scalar": SSMV_A_SCALAR, "diag": SSMV_A_DIAG}
 ACT_CODES = {"none": SSMV_ACT_NONE, "silu": SSMV_ACT_SILU}
 SNAP_CODES = {"both": SSMV_SNAP_BOTH, "hj_only": SSMV_SNAP_HJ_ONLY}
+SSMV_ENGINE_AUTO, SSMV_ENGINE_VECTOR = 0, 1
+ENGINE_CODES = {"auto": SSMV_ENGINE_AUTO, "vector": SSMV_ENGINE_VECTOR}
 
 EXPORTS = [
     "ssmv_cache_sizes", "ssmv_cache_reset", "conv1d_state_update", "ssm_verify_multistep",
@@ -57,7 +59,7 @@ class SsmvError(RuntimeError):
 class ssmv_dims(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "nheads", "headdim", "dstate", "ngroups", "conv_width", "conv_channels", "kmax",
-        "ring_len", "io_dtype", "a_mode", "conv_act", "snapshot_mode")]
+        "ring_len", "io_dtype", "a_mode", "conv_act", "snapshot_mode", "engine")]
 
 
 class ssmv_cache(ctypes.Structure):
@@ -141,7 +143,7 @@ def _stream(stream) -> Optional[int]:
 
 
 def make_dims(batch, nheads, headdim, dstate, ngroups=1, kmax=4, ring_len=None, io="bf16", a_mode="scalar",
-              conv_act="none", conv_width=SSMV_CONV_WIDTH, conv_channels=None, snapshot_mode="both") -> ssmv_dims:
+              conv_act="none", conv_width=SSMV_CONV_WIDTH, conv_channels=None, snapshot_mode="both", engine="auto") -> ssmv_dims:
     if ring_len is None:
         ring_len = 1
         while ring_len < conv_width - 1 + kmax:
@@ -151,7 +153,8 @@ def make_dims(batch, nheads, headdim, dstate, ngroups=1, kmax=4, ring_len=None, 
                      IO_CODES[io] if isinstance(io, str) else io,
                      MODE_CODES[a_mode] if isinstance(a_mode, str) else a_mode,
                      ACT_CODES[conv_act] if isinstance(conv_act, str) else conv_act,
-                     SNAP_CODES[snapshot_mode] if isinstance(snapshot_mode, str) else snapshot_mode)
+                     SNAP_CODES[snapshot_mode] if isinstance(snapshot_mode, str) else snapshot_mode,
+                     ENGINE_CODES[engine] if isinstance(engine, str) else engine)
 
 
 # ---- the C entry points, same names, torch tensors (or raw pointers) in place of pointers ----------

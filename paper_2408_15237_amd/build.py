@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libssmv.so")
-SOURCES = ["api.hip", "aux_kernels.hip", "verify_scalar.hip", "verify_diag.hip", "prefill.hip", "prefill_bf16.hip"]
+SOURCES = ["api.hip", "aux_kernels.hip", "verify_scalar.hip", "verify_diag.hip", "verify_mfma.hip", "prefill.hip", "prefill_bf16.hip"]
 HEADERS = [os.path.join(CSRC, "ssmv_internal.h"), os.path.join(CSRC, "verify_impl.h"),
            os.path.join(ROOT, "include", "ssmv.h")]
 
@@ -34,15 +34,20 @@ def _stale(target: str, deps) -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = False, verbose: bool = False) -> str:
-    os.makedirs(OBJ, exist_ok=True)
+def build(force: bool = False, verbose: bool = False, trace: bool = False) -> str:
+    """trace=True builds libssmv_trace.so instead: the same library with -DSSMV_TRACE (per-workgroup wall-clock stamps
+    inside the matrix-core verify kernel and the hook that hands it a buffer; for trace_stamps.py, not for use)."""
+    obj_dir = OBJ + ("_trace" if trace else "")
+    lib = os.path.join(PKG, "libssmv_trace.so") if trace else LIB
+    flags = FLAGS + (["-DSSMV_TRACE"] if trace else [])
+    os.makedirs(obj_dir, exist_ok=True)
     hipcc = _hipcc()
     jobs = []
     for s in SOURCES:
         src = os.path.join(CSRC, s)
-        obj = os.path.join(OBJ, s.replace(".hip", ".o"))
+        obj = os.path.join(obj_dir, s.replace(".hip", ".o"))
         if force or _stale(obj, [src] + HEADERS):
-            jobs.append([hipcc] + FLAGS + ["-c", src, "-o", obj])
+            jobs.append([hipcc] + flags + ["-c", src, "-o", obj])
 
     def run(cmd):
         r = subprocess.run(cmd, capture_output=True, text=True)
@@ -53,13 +58,13 @@ def build(force: bool = False, verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=4) as ex:
         list(ex.map(run, jobs))
-    objs = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES]
-    if force or jobs or _stale(LIB, objs):
-        run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB + ".tmp"])
-        os.replace(LIB + ".tmp", LIB)
-    return LIB
+    objs = [os.path.join(obj_dir, s.replace(".hip", ".o")) for s in SOURCES]
+    if force or jobs or _stale(lib, objs):
+        run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", lib + ".tmp"])
+        os.replace(lib + ".tmp", lib)
+    return lib
 
 
 if __name__ == "__main__":
     import sys
-    print(build(force="--force" in sys.argv, verbose=True))
+    print(build(force="--force" in sys.argv, verbose=True, trace="--trace" in sys.argv))

@@ -27,11 +27,6 @@ int hip_fail(int hip_code, const char *what)
     return fail(SSMV_EHIP, "%s: %s", what, hipGetErrorString((hipError_t)hip_code));
 }
 
-#ifdef SSMV_TRACE
-// Profiling builds (-DSSMV_TRACE) only: device buffer of 8 wall-clock stamps per verify workgroup.
-long long *g_trace = nullptr;
-extern "C" void ssmv_debug_set_trace(long long *t) { g_trace = t; }
-#endif
 std::atomic<int> g_tune_rows{0};
 std::atomic<int> g_tune_waves{0};
 
@@ -49,6 +44,7 @@ int check_dims(const ssmv_dims *d)
     if (d->conv_act != SSMV_ACT_NONE && d->conv_act != SSMV_ACT_SILU) return fail(SSMV_EINVAL, "conv_act %d unknown", d->conv_act);
     if (d->snapshot_mode != SSMV_SNAP_BOTH && d->snapshot_mode != SSMV_SNAP_HJ_ONLY)
         return fail(SSMV_EINVAL, "snapshot_mode %d unknown", d->snapshot_mode);
+    if (d->engine != SSMV_ENGINE_AUTO && d->engine != SSMV_ENGINE_VECTOR) return fail(SSMV_EINVAL, "engine %d unknown", d->engine);
     if (d->nheads % d->ngroups != 0) return fail(SSMV_EINVAL, "nheads %d not a multiple of ngroups %d", d->nheads, d->ngroups);
     if ((long)d->conv_channels != (long)d->nheads * d->headdim)
         return fail(SSMV_EINVAL, "conv_channels %d != nheads*headdim %ld", d->conv_channels, (long)d->nheads * d->headdim);
@@ -77,6 +73,18 @@ int check_dims(const ssmv_dims *d)
     if (slot * 3 > 2.0e10) return fail(SSMV_EUNSUPPORTED, "state of %.3g elements is beyond what one cache may hold", slot * 3);
     if ((double)d->batch * d->nheads * d->headdim > 2.0e9) return fail(SSMV_EUNSUPPORTED, "too many state rows");
     return SSMV_OK;
+}
+
+// Largest number of pending tokens a verify may meet.
+int pend_max_of(const ssmv_dims *d) { return d->snapshot_mode == SSMV_SNAP_HJ_ONLY ? d->kmax : d->kmax - 1; }
+
+// Whether the caches of these dimensions keep their state slots in 16x16 tiles (state_off4) and their verify launches run
+// on the matrix cores: scalar-A mode, bf16 tokens, a shape that kernel is built for, and never more than 16 tokens
+// (pending + drafts) in one launch.  A property of the dimensions, so every call on a cache agrees on it.
+bool state_tiled(const ssmv_dims *d)
+{
+    return d->engine == SSMV_ENGINE_AUTO && d->a_mode == SSMV_A_SCALAR && d->io_dtype == SSMV_BF16 &&
+           verify_mfma_supported(d->dstate, d->headdim) && pend_max_of(d) + d->kmax <= 16;
 }
 
 int check_ptr(const void *p, const char *name)
@@ -167,12 +175,17 @@ void fill_verify(VerifyParams &p, const ssmv_dims *d, const ssmv_cache *c)
     for (int i = 0; i < 2; ++i) { p.win_xc[i] = c->win_xc[i]; p.win_dt[i] = c->win_dt[i]; p.win_B[i] = c->win_B[i]; }
     p.cur_slot = c->cur_slot; p.pend = c->pend; p.last_k = c->last_k; p.win_par = c->win_par;
     p.ring = c->conv_ring; p.conv_head = c->conv_head; p.ring_len = d->ring_len; p.conv_act = d->conv_act;
-#ifdef SSMV_TRACE
-    p.trace = g_trace;
-#endif
+    p.tiled = state_tiled(d);
 }
 
 }  // namespace
+
+#ifdef SSMV_TRACE
+// Profiling builds (-DSSMV_TRACE) only, no part of the library's interface: a device buffer of 8 wall-clock stamps per
+// workgroup of the matrix-core verify kernel.
+namespace ssmv { int set_trace_mfma(long long *buf); }
+extern "C" int ssmv_debug_set_trace(long long *buf) { return ssmv::set_trace_mfma(buf); }
+#endif
 
 extern "C" {
 
@@ -224,6 +237,7 @@ int ssmv_cache_reset(const ssmv_dims *d, const ssmv_cache *c, const float *h0, c
     ResetParams p{};
     p.batch = d->batch; p.Cx = d->conv_channels; p.R = d->ring_len; p.W = d->conv_width; p.io = d->io_dtype;
     p.state_elems = (size_t)d->batch * d->nheads * d->headdim * d->dstate;
+    p.P = d->headdim; p.N = d->dstate; p.tiled = state_tiled(d);
     p.state = c->state; p.h0 = h0; p.ring = c->conv_ring; p.conv_init = conv_init;
     p.cur_slot = c->cur_slot; p.pend = c->pend; p.conv_head = c->conv_head; p.last_k = c->last_k;
     p.win_par = c->win_par; p.err_flag = c->err_flag; p.pos = c->pos;
@@ -264,6 +278,9 @@ static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const ssmv_ste
         return fail(SSMV_EUNSUPPORTED, "ragged draft counts in a round fed by several calls (a sequence's window entries would not be contiguous)");
     if (a->dt_softplus != 0 && a->dt_softplus != 1) return fail(SSMV_EINVAL, "dt_softplus %d not in {0,1}", a->dt_softplus);
     if ((a->x_raw != nullptr) == (a->xc != nullptr)) return fail(SSMV_EINVAL, "exactly one of x_raw and xc must be given");
+    if (a->xc && a->tok0 > 0)
+        return fail(SSMV_EUNSUPPORTED, "a later call of a round (tok0 %d > 0) must pass x_raw: conv1d_state_update cannot append behind "
+                                       "the round's earlier tokens", a->tok0);
     if (a->x_raw) {
         if ((rc = check_ptr(a->x_raw, "x_raw")) != SSMV_OK) return rc;
         if ((rc = check_ptr(a->conv_wgt, "wgt")) != SSMV_OK) return rc;
@@ -290,11 +307,16 @@ static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const ssmv_ste
     p.dt_bias = a->dt_bias;
     p.z = a->z;
     p.k_seq = a->k_seq;
-    p.pend_max = d->snapshot_mode == SSMV_SNAP_HJ_ONLY ? d->kmax : d->kmax - 1;
+    p.pend_max = pend_max_of(d);
     p.write_hk = d->snapshot_mode != SSMV_SNAP_HJ_ONLY;
     p.lds_tokens = (a->tok0 > 0 ? 0 : p.pend_max) + k;
     p.xc = a->xc; p.dt = a->dt; p.Bm = a->Bm; p.Cm = a->Cm; p.A = a->A; p.D = a->D; p.y = a->y_out; p.h_out = nullptr;
     p.x_raw = a->x_raw; p.wgt = a->conv_wgt; p.bias = a->conv_bias;
+    // tiled caches: the matrix-core kernel, unless a launch shape of the vector kernel was asked for explicitly
+    if (p.tiled && g_tune_rows.load() == 0 && g_tune_waves.load() == 0) {
+        const int hm = launch_verify_mfma(p, (hipStream_t)hip_stream);
+        return hm == 0 ? SSMV_OK : hip_fail(hm, what);
+    }
     VerifyShape shape;
     if ((rc = choose_shape(d, p.lds_tokens, k, p.z != nullptr, &shape, &p.rows_wg, &p.tiles)) != SSMV_OK) return rc;
     p.log2_rows_wg = ilog2_host(p.rows_wg);
@@ -342,7 +364,7 @@ int ssmv_materialize_block(const ssmv_dims *d, const ssmv_cache *c, const float 
     p.pend_mask = ~0;
     p.dt_softplus = dt_softplus;
     p.dt_bias = dt_bias;
-    p.pend_max = d->snapshot_mode == SSMV_SNAP_HJ_ONLY ? d->kmax : d->kmax - 1;
+    p.pend_max = pend_max_of(d);
     p.write_hk = 0;
     p.lds_tokens = p.pend_max > 0 ? p.pend_max : 1;
     p.A = A; p.D = A;   // D is not read when k == 0
@@ -373,8 +395,11 @@ int ssm_prefill_block(const ssmv_dims *d, const ssmv_cache *c, const ssmv_prefil
         return fail(SSMV_EUNSUPPORTED, "chunked prefill is built for headdim in {32,64,128} and dstate in {32,64,128}, not %d x %d",
                     d->headdim, d->dstate);
     // the kernel addresses a sequence's tokens with 32-bit element offsets formed on the 24-bit multiplier
-    if (a->L >= (1 << 24) || (double)a->L * d->conv_channels >= 2147483648.0)
-        return fail(SSMV_EUNSUPPORTED, "a prompt of %d tokens x %d channels does not fit 32-bit offsets: feed it in pieces", a->L, d->conv_channels);
+    // (x and y rows are conv_channels long, B and C rows ngroups*dstate, dt rows nheads)
+    const double widest = (double)(d->conv_channels > d->ngroups * d->dstate ? d->conv_channels : d->ngroups * d->dstate);
+    if (a->L >= (1 << 24) || (double)a->L * widest >= 2147483648.0)
+        return fail(SSMV_EUNSUPPORTED, "a prompt of %d tokens x %.0f elements per token row does not fit 32-bit offsets: feed it in pieces",
+                    a->L, widest);
     if ((rc = check_ptr(a->x_raw, "x_raw")) != SSMV_OK) return rc;
     if ((rc = check_ptr(a->conv_wgt, "wgt")) != SSMV_OK) return rc;
     if (a->conv_bias && !aligned16(a->conv_bias)) return fail(SSMV_EALIGN, "bias is not 16-byte aligned");
@@ -391,6 +416,7 @@ int ssm_prefill_block(const ssmv_dims *d, const ssmv_cache *c, const ssmv_prefil
     p.batch = d->batch; p.H = d->nheads; p.P = d->headdim; p.N = d->dstate; p.G = d->ngroups; p.L = a->L; p.io = d->io_dtype;
     p.ring_len = d->ring_len; p.conv_act = d->conv_act;
     p.dt_softplus = a->dt_softplus; p.dt_bias = a->dt_bias; p.z = a->z; p.seq_len = a->seq_len;
+    p.tiled = state_tiled(d);
     p.state = c->state;
     p.slot_stride = (size_t)d->batch * d->nheads * d->headdim * d->dstate;
     p.ring = c->conv_ring; p.cur_slot = c->cur_slot; p.conv_head = c->conv_head;

@@ -156,7 +156,12 @@ __global__ __launch_bounds__(256) void reset_state_kernel(const ResetParams p)
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
         if (p.h0) v = reinterpret_cast<const float4 *>(p.h0)[i];
-        reinterpret_cast<float4 *>(p.state)[i] = v;
+        size_t o = i * 4;
+        if (p.tiled) {                         // h0 is row-major; the slot keeps each (sequence, head) block in tiles
+            const size_t blk = (size_t)p.P * p.N, head = o / blk, e = o - head * blk;
+            o = head * blk + state_off4(true, (int)(e / p.N), (int)(e % p.N), p.N);
+        }
+        *reinterpret_cast<float4 *>(p.state + o) = v;
     }
 }
 

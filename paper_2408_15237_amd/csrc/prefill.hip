@@ -80,8 +80,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
 
     // state -> LDS
     for (int idx = tid; idx < P * N / 4; idx += 256) {
-        const float4 v = *reinterpret_cast<const float4 *>(state + idx * 4);
         const int row = (idx * 4) / N, col = (idx * 4) % N;
+        const float4 v = *reinterpret_cast<const float4 *>(state + state_off4(p.tiled, row, col, N));
         float *d = sH + row * NP + col;
         d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
     }
@@ -298,7 +298,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillParams p)
     for (int idx = tid; idx < P * N / 4; idx += 256) {
         const int row = (idx * 4) / N, col = (idx * 4) % N;
         const float *s = sH + row * NP + col;
-        *reinterpret_cast<float4 *>(state + idx * 4) = make_float4(s[0], s[1], s[2], s[3]);
+        *reinterpret_cast<float4 *>(state + state_off4(p.tiled, row, col, N)) = make_float4(s[0], s[1], s[2], s[3]);
     }
     if (tid < P) {
         for (int tg = (L - (W - 1) > 0 ? L - (W - 1) : 0); tg < L; ++tg)

@@ -87,7 +87,7 @@ typedef __attribute__((address_space(3))) char lds_char_t;
 __device__ __forceinline__ void load_to_lds16(const void *src, const char *dst)
 {
     const unsigned lds_addr = (unsigned)(size_t)(lds_char_t *)dst;
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr) : "memory");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr) : "memory", "m0");
 }
 __device__ __forceinline__ void wait_direct_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -185,12 +185,14 @@ void prefill_bf16_kernel(const PrefillParams p)
     // state -> accumulator registers, transposed tiles [n][p]: register 4 q + e of tile tn holds
     // h[p = 32 pt + li][n = 32 (TNL nh + tn) + 16 (q/2) + 8 lh + 4 (q%2) + e]
     f16v hacc[TNL];
-    const size_t srow = (size_t)(pt * 32 + li) * N + 32 * TNL * nh + 8 * lh;
+    // (row, first column) of the lane's float4 number q of tile tn; the slot is row-major or tiled (state_off4)
+    const int srow_ = pt * 32 + li, scol0 = 32 * TNL * nh + 8 * lh;
+    auto state_at = [&](int tn, int q) { return state + state_off4(p.tiled, srow_, scol0 + 32 * tn + 16 * (q / 2) + 4 * (q % 2), N); };
 #pragma unroll
     for (int tn = 0; tn < TNL; ++tn)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const float4 v = *reinterpret_cast<const float4 *>(state + srow + 32 * tn + 16 * (q / 2) + 4 * (q % 2));
+            const float4 v = *reinterpret_cast<const float4 *>(state_at(tn, q));
             hacc[tn][4 * q + 0] = v.x; hacc[tn][4 * q + 1] = v.y; hacc[tn][4 * q + 2] = v.z; hacc[tn][4 * q + 3] = v.w;
         }
     // Every wave computes G^T whole (rows s, columns t = li) and finishes the 16 / (waves) of its registers that are its
@@ -528,7 +530,7 @@ void prefill_bf16_kernel(const PrefillParams p)
     for (int tn = 0; tn < TNL; ++tn)
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            *reinterpret_cast<float4 *>(state + srow + 32 * tn + 16 * (q / 2) + 4 * (q % 2)) =
+            *reinterpret_cast<float4 *>(state_at(tn, q)) =
                 make_float4(hacc[tn][4 * q + 0], hacc[tn][4 * q + 1], hacc[tn][4 * q + 2], hacc[tn][4 * q + 3]);
     if (tid < P) {
         for (int tg = (L - (W - 1) > 0 ? L - (W - 1) : 0); tg < L; ++tg)

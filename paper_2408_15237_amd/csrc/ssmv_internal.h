@@ -28,6 +28,7 @@ struct VerifyParams {
     const void *z;       // gate input [batch][k][channels] or null
     const int *k_seq;    // per-sequence draft counts [batch] or null
     int log2_rows_wg;    // rows_wg is a power of two
+    int tiled;           // 1: the state slots are kept in 16x16 tiles (state_off4), scalar mode only
     // fused conv roll (x_raw != nullptr): ring append + width-4 conv computed while staging
     int ring_len, conv_act;
     void *ring;
@@ -48,10 +49,6 @@ struct VerifyParams {
     const float *A, *D;
     void *y;
     float *h_out;        // non-null: materialize mode (replay only, write here, touch nothing else)
-#ifdef SSMV_TRACE
-    long long *trace;    // profiling builds only: 8 wall-clock stamps per workgroup (start, bookkeeping read,
-                         // loads issued, staged, barrier passed, drafts begin, drafts done, stores acknowledged)
-#endif
 };
 
 struct ConvParams {
@@ -65,6 +62,7 @@ struct ConvParams {
 struct PrefillParams {
     int batch, H, P, N, G, L, io, ring_len, conv_act;   // L: token stride of the arrays = longest prompt
     int dt_softplus;         // 1: dt <- softplus(dt + dt_bias)
+    int tiled;               // 1: the state slots are kept in 16x16 tiles (state_off4)
     const float *dt_bias;    // [H] or null
     const void *z;           // gate input [batch][L][H*P] or null
     const int32_t *seq_len;  // [batch] or null: prompt length per sequence (<= L)
@@ -97,6 +95,7 @@ struct CommitParams {
 
 struct ResetParams {
     int batch, Cx, R, W, io;
+    int P, N, tiled;         // rows and columns of one (sequence, head) block of the state, and its layout
     size_t state_elems;      // batch*H*P*N (slot 0 only)
     float *state;
     const float *h0;
@@ -117,10 +116,27 @@ struct VerifyShape {
 __host__ __device__ constexpr int lanes_per_row(int N) { return (N / 4 < 16) ? N / 4 : 16; }
 __host__ __device__ constexpr int rows_per_instr(int N) { return 64 / lanes_per_row(N); }
 
+// ---- layout of a state slot ---------------------------------------------------------------------
+// A slot holds batch*H blocks of P rows x N fp32, one per (sequence, head).  Inside a block the layout is either plain
+// row-major (element (p, n) at p*N + n) or TILED: 16x16 tiles in the register order of a 16x16 matrix-core accumulator.
+// Tile (p/16, n/16) is 256 consecutive floats; inside it the four floats n%16 in [4g, 4g+4) of row p%16 are the float4
+// number 16 g + p%16.  Lane l = 16 g + p%16 of a wave then holds, after ONE 16-byte access per lane that covers 1 KiB of
+// contiguous memory, exactly its share of the tile as accumulator (rows n, columns p) - and the same registers are the
+// k-slots of the other operand of a product that contracts over n.  Row-major memory would make that access 16 rows x 64
+// bytes per instruction, which the memory system serves an eighth (loads) to a third (stores) slower.
+// Tiled needs P and N to be multiples of 16; n is a multiple of 4 here.
+__host__ __device__ inline size_t state_off4(bool tiled, int p, int n, int N)
+{
+    return tiled ? (((size_t)(p >> 4) * (N >> 4) + (n >> 4)) << 8) + ((((n & 15) >> 2) << 4) + (p & 15)) * 4 : (size_t)p * N + n;
+}
+
 // launchers implemented in verify_scalar.hip / verify_diag.hip; return hipError_t as int
 int launch_verify_scalar(const VerifyParams &p, VerifyShape shape, hipStream_t stream);
 int launch_verify_diag(const VerifyParams &p, VerifyShape shape, hipStream_t stream);
 size_t verify_lds_bytes(const VerifyParams &p, bool diag);
+// the matrix-core form of the scalar-mode kernel (verify_mfma.hip): bf16 I/O, tiled state, at most 16 tokens per launch
+int launch_verify_mfma(const VerifyParams &p, hipStream_t stream);
+bool verify_mfma_supported(int N, int P);
 bool verify_shape_supported(int N, int R, bool diag);
 
 int launch_conv(const ConvParams &p, hipStream_t stream);

@@ -122,13 +122,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const int rows_wg = p.rows_wg;
     const int k = p.k;
     const bool materialize = p.h_out != nullptr;
-#ifdef SSMV_TRACE
-    long long *trace_ = p.trace ? p.trace + 8 * ((size_t)blockIdx.x + gridDim.x * (blockIdx.y + (size_t)gridDim.y * blockIdx.z)) : nullptr;
-#define SSMV_TP(i) do { if (trace_ && threadIdx.x == 0) trace_[i] = wall_clock64(); } while (0)
-#else
-#define SSMV_TP(i) do { } while (0)
-#endif
-    SSMV_TP(0);
 
     // ---- which (sequence, head, tile): all uniform ------------------------------------------------
     // grid = (tiles, heads, batch) in scalar mode, (tiles, batch) in diag mode: no integer division needed
@@ -151,7 +144,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const int pd = min(max(p.pend[b], 0), p.pend_max) & (EXTRA ? p.pend_mask : ~0);
     const int src_slot = EXTRA ? (cur + p.src_add) % 3 : cur;
     const int par = p.win_par[0] & 1;
-    SSMV_TP(1);
 
     // ---- state loads first: uniform base pointer + 32-bit lane offsets -------------------------------
     v4f h[R][V];
@@ -161,16 +153,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const unsigned lrow0 = wave * (RPI * R) + rsel * R;
     const unsigned loff0 = (lrow0 << LOG2N) + sub * 4;
     const int nvalid = rows_dom - (int)(row0 + lrow0);
+    // element offset, inside a slot, of strip v of the lane's row r.  Row-major slots: the lane's rows are N apart.  Tiled
+    // slots (scalar mode, state_off4): 16-byte pieces scattered over the tiles - this kernel then only serves the calls
+    // the matrix-core kernel does not take (materialize, an explicitly chosen launch shape).
+    const bool tiled = !DIAG && p.tiled;
+    // uniform base of the workgroup inside a slot plus a 32-bit lane offset
+    const size_t slot_base = tiled ? ((size_t)b * p.H + hd) * p.P * N : (grow << LOG2N);
+    auto state_elem = [&](int r, int v) -> unsigned {
+        if (tiled) return (unsigned)state_off4(true, (int)(row0 + lrow0) + r, (int)(sub * 4 + v * (LPR * 4)), N);
+        return loff0 + r * N + v * (LPR * 4);
+    };
     {
-        const float *src = p.state + (size_t)src_slot * p.slot_stride + (grow << LOG2N);
+        const float *src = p.state + (size_t)src_slot * p.slot_stride + slot_base;
         const float *srcA = p.A + ((size_t)row0 << LOG2N);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const unsigned o = r < nvalid ? loff0 + r * N : sub * 4;  // clamp to row 0: unconditional in-bounds load
+            const int rr = r < nvalid ? r : -(int)lrow0;   // clamp to the workgroup's row 0: unconditional in-bounds load
 #pragma unroll
             // streamed once per round: non-temporal, so that 100 MB per launch do not churn the caches
-            for (int v = 0; v < V; ++v) h[r][v] = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(src + o + v * (LPR * 4)));
+            for (int v = 0; v < V; ++v) h[r][v] = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(src + state_elem(rr, v)));
             if constexpr (DIAG) {
+                const unsigned o = r < nvalid ? loff0 + r * N : sub * 4;
 #pragma unroll
                 for (int v = 0; v < V; ++v) a2[r][v] = *reinterpret_cast<const v4f *>(srcA + o + v * (LPR * 4)) * LOG2E;
             }
@@ -405,7 +408,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     uint32_t fDec = 0;
     if constexpr (!DIAG) fDec = dec_load((int)tid < T ? tid : 0);      // unconditional (idle lanes read token 0), like dt above
     __builtin_amdgcn_sched_barrier(0);
-    SSMV_TP(2);
     b_use(qB, fB);
     c_use(qC, fC);
     x_use(qX, fX);
@@ -471,9 +473,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         }
     }
     if (!materialize && first_tile && hd == 0 && tid == 0) p.last_k[b] = t0 + kb;
-    SSMV_TP(3);
     __syncthreads();
-    SSMV_TP(4);
 
     // the per-row values of the lane's R adjacent rows out of a [rows_wg] LDS array (16-byte reads where R allows)
     auto lane_rows = [&](const float *arr, float (&out)[R]) {
@@ -577,27 +577,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             }
         }
     };
-    auto store_state = [&](float *dst_base) {
-        float *dst = dst_base + (grow << LOG2N);
+    auto store_state = [&](float *dst_base, bool slot_layout) {    // into a slot, or row-major into the caller's h_out
+        float *dst = dst_base + (slot_layout ? slot_base : (grow << LOG2N));
         const float al = SC ? __builtin_amdgcn_exp2f(L2) : 1.f;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (r >= nvalid) continue;
 #pragma unroll
-            for (int v = 0; v < V; ++v)
-                __builtin_nontemporal_store(SC ? h[r][v] * al : h[r][v], reinterpret_cast<v4f *>(dst + loff0 + r * N + v * (LPR * 4)));
+            for (int v = 0; v < V; ++v) {
+                const unsigned o = slot_layout ? state_elem(r, v) : loff0 + r * N + v * (LPR * 4);
+                __builtin_nontemporal_store(SC ? h[r][v] * al : h[r][v], reinterpret_cast<v4f *>(dst + o));
+            }
         }
     };
     // (i) replay the pending tokens: no outputs
     for (int s_ = 0; s_ < pd; ++s_) advance(s_);
     if (materialize) {
-        store_state(p.h_out);
+        store_state(p.h_out, false);
         return;
     }
     // (ii) snapshot h_j
-    if (pd > 0) store_state(p.state + (size_t)((cur + 1) % 3) * p.slot_stride);
+    if (pd > 0) store_state(p.state + (size_t)((cur + 1) % 3) * p.slot_stride, true);
     // (iii) the k draft tokens
-    SSMV_TP(5);
     for (int t = 0; t < kb; ++t) {
         advance(pd + t);
         const float al = SC ? __builtin_amdgcn_exp2f(L2) : 1.f;
@@ -627,8 +628,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         }
     }
     // (iv) snapshot h_k (Algorithm 2), unless every accepted token is to stay pending
-    SSMV_TP(6);
-    if (p.write_hk) store_state(p.state + (size_t)((cur + 2) % 3) * p.slot_stride);
+    if (p.write_hk) store_state(p.state + (size_t)((cur + 2) % 3) * p.slot_stride, true);
 
     __syncthreads();
     // y <- y * z * sigmoid(z) when a gate is given (the SiLU gate of a Mamba block), in fp32 before the rounding
@@ -656,12 +656,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             }
         }
     }
-#ifdef SSMV_TRACE
-    if (trace_ && threadIdx.x == 0) {                   // this wave's stores have been acknowledged
-        asm volatile("s_waitcnt vmcnt(0)");
-        trace_[7] = wall_clock64();
-    }
-#endif
 }
 
 // ---- host side ------------------------------------------------------------------------------------

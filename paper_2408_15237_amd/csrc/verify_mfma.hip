@@ -1,0 +1,469 @@
+// The fused multi-step verification kernel (Section 4.2 MultiStep, fused as in Section 4.3 of arXiv 2408.15237) with its
+// arithmetic on the matrix cores: scalar-A mode, bf16 tokens, fp32 state kept in 16x16 tiles (state_off4), at most 16 tokens
+// (pending + drafts) per launch.
+//
+// Eq. 1 unrolled over the T = pend + k tokens of a launch, with cum_t = A * (dt_0 + .. + dt_t) (in log2 units) and h_0 the
+// live state:
+//   h_j  = 2^cum_(pend-1) h_0 + sum_{s <  pend} w^j_s x_s (x) B_s ,   w^j_s = dt_s 2^(cum_(pend-1) - cum_s)
+//   h_k  = beta h_j           + sum_{s >= pend} w^k_s x_s (x) B_s ,   w^k_s = dt_s 2^(cum_(T-1) - cum_s),  beta = 2^(cum_(T-1) - cum_(pend-1))
+//   y_t  = 2^cum_t C_t . h_0  + sum_{s <= t} M_ts x_s ,               M_ts = (C_t . B_s) dt_s 2^(cum_t - cum_s)  (+ D at s = t)
+// Every exponent is <= 0, so nothing overflows however strong the decay.  The three sums and C . h_0 are products of 16 x 16
+// tiles with a contraction over the tokens (padded to 16) or over n, on v_mfma_f32_16x16x32_bf16; x, B and C ARE bf16 and
+// enter exactly; every fp32 operand (h_0, the weighted rows w_s B_s, M) enters as a bf16 head plus a bf16 tail
+// (v = hi + lo + O(2^-17 |v|)), the two stacked along the 32-deep contraction of one instruction against the other operand
+// repeated; accumulation is fp32, and the decay of the state itself (2^cum h_0, beta h_j) is an fp32 multiply.
+//
+// Layout (gfx950, wave64; lane l = 16 g + li):
+//   * one workgroup of 4 waves owns 64 NT rows (channels) of ONE (sequence, head); wave w owns NT tiles of 16 rows.  A tile
+//     of the state (16 rows x 16 n) is 1 KiB contiguous in memory and ONE 16-byte access per lane: lane l holds the floats
+//     n = 16 q + 4 g .. + 3 of row li.  Those four registers are at once (a) the accumulator layout of U = (w B)^T X with rows
+//     n and columns p, so the snapshots are produced in place and stored as they were loaded, and (b) after conversion, four
+//     k-slots of the first operand of Y1^T = h_0 C^T (rows p, contraction over n).
+//   * The tokens are fetched BEFORE the state, and turned into the LDS operands (the conv roll, the transposed and weighted B
+//     rows, G = B C^T and M on the matrix core of wave 0) while the 33 MB of state of the launch are still under way: the wait
+//     that staging needs covers the token loads only (loads return in order).  After the barrier a wave needs, per tile of
+//     16 x 64 state values, 4 + 4 + 4 + 1 matrix instructions and about 100 vector instructions.
+//   * x and the weighted B sit in LDS as [row][16 tokens] bf16 with rows padded to 48 bytes: the 16-byte operand reads of 8
+//     lanes then fall into 8 different bank groups.
+#include "ssmv_internal.h"
+
+namespace ssmv {
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+typedef unsigned u4v __attribute__((ext_vector_type(4)));
+typedef unsigned u2v __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ bf8 as_bf8(u4v v) { return __builtin_bit_cast(bf8, v); }
+__device__ __forceinline__ v4f mfma16(bf8 a, bf8 b, v4f c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_or_zero(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+// inclusive prefix sum over the 16 lanes of a row (row_shr 1, 2, 4, 8; lanes shifted in from outside read 0)
+__device__ __forceinline__ float prefix16(float v)
+{
+    v += dpp_or_zero<0x111>(v);
+    v += dpp_or_zero<0x112>(v);
+    v += dpp_or_zero<0x114>(v);
+    v += dpp_or_zero<0x118>(v);
+    return v;
+}
+__device__ __forceinline__ float lane_get(float v, int lane)     // the value lane `lane` of this wave holds
+{
+    return __int_as_float(__builtin_amdgcn_ds_bpermute(lane << 2, __float_as_int(v)));
+}
+__device__ __forceinline__ float uniform_lane(float v, int lane)  // the same for a wave-uniform lane number
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+__device__ __forceinline__ float bf16lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// two fp32 values -> packed bf16 heads and packed bf16 tails (first value in the low half)
+__device__ __forceinline__ void split2(float a, float b, uint32_t &hi, uint32_t &lo)
+{
+    hi = pack_bf16x2(a, b);
+    lo = pack_bf16x2(a - bf16lo(hi), b - bf16hi(hi));
+}
+
+// Keeps the optimiser from moving the decode of a loaded value up to its load (where it would need a wait for every load
+// issued before it): the value is opaque from here on.
+__device__ __forceinline__ void pin(uint32_t &v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void pin(u2v &v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void pin(u4v &v) { asm volatile("" : "+v"(v)); }
+
+#ifdef SSMV_TRACE
+// Profiling builds only: 8 wall-clock stamps per workgroup (100 MHz), written by thread 0.
+__device__ long long *trace_buf_ = nullptr;
+#define SSMV_TP(i) do { if (trace_ && threadIdx.x == 0) trace_[i] = wall_clock64(); } while (0)
+#else
+#define SSMV_TP(i) do { } while (0)
+#endif
+
+template <int N, int NT, bool CONV, bool EXTRA>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void verify_mfma_kernel(const VerifyParams p)
+{
+    constexpr int NQ = N / 16;                           // 16-wide tiles along n
+    constexpr int NH = N / 32;                           // 32-deep steps of a contraction over n
+    constexpr int RW = 64 * NT;                          // rows of the workgroup
+    constexpr int XS = 24;                               // LDS row stride (bf16 elements) of a [.][16 tokens] row: 48 bytes
+    constexpr int CS = N + 8;                            // LDS row stride of a C row
+    constexpr int W = SSMV_CONV_WIDTH;
+    constexpr int BT0 = 256 - 2 * N > 0 ? 256 - 2 * N : 0;   // first thread that builds the weighted B rows
+    static_assert(W == 4, "the conv window below is written for four taps");
+
+    __shared__ __attribute__((aligned(16))) uint16_t sX[RW * XS];          // x           [row][token]
+    __shared__ __attribute__((aligned(16))) uint16_t sWj[2 * N * XS];      // w^j_s B_s   [head|tail][n][token]
+    __shared__ __attribute__((aligned(16))) uint16_t sWk[2 * N * XS];      // w^k_s B_s
+    __shared__ __attribute__((aligned(16))) uint16_t sC[16 * CS];          // C           [draft][n]
+    __shared__ __attribute__((aligned(16))) uint16_t sM[2 * 16 * XS];      // M           [head|tail][draft][token]
+
+    const unsigned tid = threadIdx.x, l = tid & 63u, w = __builtin_amdgcn_readfirstlane(tid >> 6), li = l & 15u, g = l >> 4;
+    const int tile = blockIdx.x, hd = blockIdx.y, b = blockIdx.z;
+#ifdef SSMV_TRACE
+    long long *trace_ = trace_buf_ ? trace_buf_ + 8 * ((size_t)blockIdx.x + gridDim.x * (blockIdx.y + (size_t)gridDim.y * blockIdx.z)) : nullptr;
+#endif
+    SSMV_TP(0);
+    const int k = p.k, H = p.H, P = p.P, HP = H * P, GN = p.G * N;
+
+    // ---- bookkeeping written by the commit kernel (clamped: a corrupted cache cannot index out of bounds) ---------------
+    // tok0 > 0: a later call of a round that an earlier call began (draft side, Section 4.3): continue from the h_k slot,
+    // in place, replay nothing, append to the round's stash and ring behind the tok0 earlier tokens.
+    const int t0 = EXTRA ? p.tok0 : 0;
+    const int cur = (int)((unsigned)p.cur_slot[b] % 3u);
+    const int pd = min(max(p.pend[b], 0), p.pend_max) & (EXTRA ? p.pend_mask : ~0);
+    const int src_slot = EXTRA ? (cur + p.src_add) % 3 : cur;
+    const int par = p.win_par[0] & 1;
+    int kb = k;
+    if constexpr (EXTRA) if (p.k_seq) kb = min(max(p.k_seq[b], 1), k);
+    const int T = pd + kb;                               // <= 16: the host launches this kernel only if pend_max + k <= 16
+    // per-head parameters: read here, as scalar loads beside the bookkeeping (further down they would become vector loads
+    // queued behind the state)
+    const float A2 = p.A[hd] * 1.4426950408889634f, D_h = p.D[hd];
+    float dtb_h = 0.f;
+    if constexpr (EXTRA) if (p.dt_bias) dtb_h = p.dt_bias[hd];
+
+    int grp = 0;
+    bool first_head_of_group = true;
+    if (p.G > 1) {
+        const int hpg = H / p.G;
+        grp = hd / hpg;
+        first_head_of_group = hd - grp * hpg == 0;
+    }
+    const bool first_tile = tile == 0;
+    const bool writes_B = first_tile && first_head_of_group;
+    const int ch0 = hd * P + tile * RW;                  // first channel of this workgroup
+    const size_t tok_in = (size_t)b * k, tok_win = (size_t)b * p.kmax;
+    // both halves of the window are kernel arguments; a select, not an indexed load that would wait for `par`
+    auto half = [&](void *const (&w2)[2], int which) { return static_cast<uint16_t *>(which ? w2[1] : w2[0]); };
+    const uint16_t *winB = half(p.win_B, par), *winX = half(p.win_xc, par), *winDt = half(p.win_dt, par);
+    uint16_t *winB_out = half(p.win_B, par ^ 1), *winX_out = half(p.win_xc, par ^ 1), *winDt_out = half(p.win_dt, par ^ 1);
+    const uint16_t *Bmp = static_cast<const uint16_t *>(p.Bm), *Cmp = static_cast<const uint16_t *>(p.Cm);
+    const uint16_t *dtp = static_cast<const uint16_t *>(p.dt);
+    const uint16_t *xin = static_cast<const uint16_t *>(CONV ? p.x_raw : p.xc);
+    uint16_t *ring = static_cast<uint16_t *>(p.ring);
+    const size_t oB_win = tok_win * GN + (size_t)grp * N, oB_in = tok_in * GN + (size_t)grp * N;
+    const size_t oX_win = tok_win * HP + ch0, oX_in = tok_in * HP + ch0;
+    const size_t oDt_win = tok_win * H + hd, oDt_in = tok_in * H + hd;
+    const size_t oB_wout = oB_win + (size_t)t0 * GN, oX_wout = oX_win + (size_t)t0 * HP, oDt_wout = oDt_win + (size_t)t0 * H;
+    const size_t ring_b = (size_t)b * p.ring_len * HP + ch0;
+    const int ring_mask = p.ring_len - 1;
+    int conv_head = 0;
+    if constexpr (CONV) conv_head = (p.conv_head[b] + t0) & ring_mask;      // newest raw input fed so far
+
+    // ---- token loads, all issued before the state loads: uniform base pointers, 32-bit lane offsets -------------------------
+    // dt: lane li of every wave takes token li (every wave needs the decay factors)
+    uint32_t dt_raw = 0;
+    if ((int)li < T) dt_raw = (int)li < pd ? (winDt + oDt_win)[li * H] : (dtp + oDt_in)[(li - pd) * H];
+    // x: thread (row xp, chunk) takes the 8 token slots [xt0, xt0 + 8) of its row: pending tokens from the stash, drafts from
+    // this call's input - with the conv folded in: the raw inputs of the chunk's drafts and the three before them
+    const bool xrole = tid < 2 * RW;
+    const unsigned xp = tid % RW;
+    const int xt0 = 8 * (int)__builtin_amdgcn_readfirstlane(tid / RW);     // uniform over a wave
+    const int i_lo = max(0, pd - xt0), i_hi = min(8, T - xt0);             // drafts of the chunk: slots [i_lo, i_hi)
+    uint32_t xv[8], rawv[CONV ? 11 : 1];
+    u2v wraw = {0u, 0u};
+    uint32_t bias_raw = 0;
+    if (xrole) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int tt = xt0 + i;
+            xv[i] = 0;
+            if (tt < pd) xv[i] = (winX + oX_win + (size_t)tt * HP)[xp];
+            else if (!CONV && tt < T) xv[i] = (xin + oX_in + (size_t)(tt - pd) * HP)[xp];
+        }
+        if constexpr (CONV) {
+#pragma unroll
+            for (int m = 0; m < 11; ++m) {
+                rawv[m] = 0;
+                const int j = xt0 - pd - 3 + m;            // position relative to this call's first token; -3..-1: the ring
+                if (m >= i_lo && m < i_hi + 3)
+                    rawv[m] = (j < 0 ? ring + ring_b + (size_t)((conv_head + 1 + j) & ring_mask) * HP : xin + oX_in + (size_t)j * HP)[xp];
+            }
+            if (i_lo < i_hi) {
+                wraw = reinterpret_cast<const u2v *>(static_cast<const uint16_t *>(p.wgt) + (size_t)ch0 * W)[xp];
+                // (no bias: any readable address; the value is dropped at its use)
+                bias_raw = (static_cast<const uint16_t *>(p.bias ? p.bias : p.wgt) + ch0)[xp];
+            }
+        }
+    }
+    // B for the weighted rows: thread (n, chunk) takes B[token][n] of the 8 tokens of its chunk
+    const bool brole = (int)tid >= BT0;
+    const unsigned bn = (unsigned)((int)tid - BT0) % N;
+    const int bt0 = N >= 64 ? 8 * (int)__builtin_amdgcn_readfirstlane((unsigned)((int)tid - BT0) / N) : 8 * (((int)tid - BT0) / N);
+    uint32_t braw[8];
+    if (brole) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int tt = bt0 + i;
+            braw[i] = 0;
+            if (tt < T) braw[i] = (tt < pd ? winB + oB_win + (size_t)tt * GN : Bmp + oB_in + (size_t)(tt - pd) * GN)[bn];
+        }
+    }
+    // wave 0: rows of B (token li) and C (draft li) as operands of G^T = B C^T, 8 consecutive n per lane and step.  Lanes past
+    // the last token read some valid row and drop it at the use.
+    u4v Bs[NH], Cs[NH];
+    if (w == 0) {
+        const unsigned sb = min(li, (unsigned)(T - 1)), sc = min(li, (unsigned)(kb - 1));
+        const uint16_t *row = (int)sb < pd ? winB + oB_win + (size_t)sb * GN : Bmp + oB_in + (size_t)(sb - pd) * GN;
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            Bs[h] = *reinterpret_cast<const u4v *>(row + 8 * g + 32 * h);
+            Cs[h] = *reinterpret_cast<const u4v *>(Cmp + oB_in + sc * GN + 8 * g + 32 * h);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    SSMV_TP(1);
+
+    // ---- state loads: NT tiles of 16 rows per wave, NQ accesses of 1 KiB per tile (streamed once per round: non-temporal) ---
+    v4f st[NT][NQ];
+    const size_t head_base = ((size_t)b * H + hd) * P * N;
+    const unsigned pt0 = tile * (RW / 16) + w * NT;     // this wave's first row tile inside the head
+    const unsigned st_off = ((pt0 * NQ) << 8) + l * 4;  // its first access inside the head's block
+    {
+        const float *src = p.state + (size_t)src_slot * p.slot_stride + head_base + st_off;
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) st[i][q] = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(src + ((i * NQ + q) << 8)));
+    }
+    const bool gated = EXTRA && p.z != nullptr;
+    u2v zraw[NT];
+    if constexpr (EXTRA) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            zraw[i] = u2v{0u, 0u};
+            if (gated && (int)li < kb)
+                zraw[i] = *reinterpret_cast<const u2v *>(static_cast<const uint16_t *>(p.z) + oX_in + (size_t)li * HP + (w * NT + i) * 16 + 4 * g);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    SSMV_TP(2);
+    // the token values are used from here on (the wait this needs covers the token loads only: loads return in order)
+    pin(dt_raw);
+    if (xrole) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pin(xv[i]);
+        if constexpr (CONV) {
+#pragma unroll
+            for (int m = 0; m < 11; ++m) pin(rawv[m]);
+            pin(wraw);
+            pin(bias_raw);
+        }
+    }
+    if (brole) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pin(braw[i]);
+    }
+    if (w == 0) {
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            pin(Bs[h]);
+            pin(Cs[h]);
+            if ((int)li >= T) Bs[h] = u4v{0u, 0u, 0u, 0u};
+            if ((int)li >= kb) Cs[h] = u4v{0u, 0u, 0u, 0u};
+        }
+    }
+    SSMV_TP(3);
+
+    // ---- decay factors and weights: every wave, lane li = token li ---------------------------------------------------------
+    float dtv = bf16lo(dt_raw);
+    if constexpr (EXTRA) {                               // optional softplus(dt + dt_bias) ahead of the discretisation (Section 2.2)
+        dtv += dtb_h;
+        if (p.dt_softplus) dtv = softplus_fast(dtv);
+    }
+    if ((int)li >= T) dtv = 0.f;
+    const float cum = prefix16(dtv * A2);                // log2 of the decay over tokens 0..li
+    const float cumJ = pd > 0 ? uniform_lane(cum, pd - 1) : 0.f;
+    const float cumK = uniform_lane(cum, T - 1);
+    const float wj = (int)li < pd ? dtv * __builtin_amdgcn_exp2f(cumJ - cum) : 0.f;
+    const float wk = ((int)li >= pd && (int)li < T) ? dtv * __builtin_amdgcn_exp2f(cumK - cum) : 0.f;
+    const float alphaJ = __builtin_amdgcn_exp2f(cumJ), beta = __builtin_amdgcn_exp2f(cumK - cumJ);
+    const float cy = lane_get(cum, min(pd + (int)li, 15));   // draft li is token pd + li
+    const float alphaY = __builtin_amdgcn_exp2f(cy);
+
+    // ---- x: conv roll, stash, ring append, and the [row][token] operand ---------------------------------------------------
+    if (xrole) {
+        float wf[4] = {bf16lo(wraw.x), bf16hi(wraw.x), bf16lo(wraw.y), bf16hi(wraw.y)};
+        const float bias_f = p.bias ? bf16lo(bias_raw) : 0.f;
+        uint32_t out[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int tt = xt0 + i, t = tt - pd;
+            uint32_t bits = xv[i];
+            const bool draft = tt >= pd && tt < T;
+            if constexpr (CONV) {
+                if (draft) {
+                    // width-4 causal depthwise conv, fp32 accumulate in tap order, rounded to the I/O type
+                    float s = bias_f;
+                    s = fmaf(wf[0], bf16lo(rawv[i]), s);
+                    s = fmaf(wf[1], bf16lo(rawv[i + 1]), s);
+                    s = fmaf(wf[2], bf16lo(rawv[i + 2]), s);
+                    s = fmaf(wf[3], bf16lo(rawv[i + 3]), s);
+                    if (p.conv_act == SSMV_ACT_SILU) s = s / (1.f + expf(-s));
+                    bits = f32_to_bf16_bits(s);
+                    ring[ring_b + (size_t)((conv_head + 1 + t) & ring_mask) * HP + xp] = (uint16_t)rawv[i + 3];
+                }
+            }
+            if (draft) winX_out[oX_wout + (size_t)t * HP + xp] = (uint16_t)bits;
+            out[i] = tt < T ? (bits & 0xffffu) : 0u;
+        }
+        *reinterpret_cast<u4v *>(sX + xp * XS + xt0) = u4v{out[0] | (out[1] << 16), out[2] | (out[3] << 16), out[4] | (out[5] << 16), out[6] | (out[7] << 16)};
+    }
+
+    // ---- weighted, transposed B rows: head and tail, for the snapshot h_j (pending tokens) and for h_k (drafts) -------------
+    if (brole) {
+        uint32_t hj[4], lj[4], hk[4], lk[4];
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) {
+            const float b0 = bf16lo(braw[2 * ii]), b1 = bf16lo(braw[2 * ii + 1]);
+            split2(lane_get(wk, bt0 + 2 * ii) * b0, lane_get(wk, bt0 + 2 * ii + 1) * b1, hk[ii], lk[ii]);
+            split2(lane_get(wj, bt0 + 2 * ii) * b0, lane_get(wj, bt0 + 2 * ii + 1) * b1, hj[ii], lj[ii]);
+        }
+        *reinterpret_cast<u4v *>(sWk + bn * XS + bt0) = u4v{hk[0], hk[1], hk[2], hk[3]};
+        *reinterpret_cast<u4v *>(sWk + (N + bn) * XS + bt0) = u4v{lk[0], lk[1], lk[2], lk[3]};
+        if (pd > 0) {
+            *reinterpret_cast<u4v *>(sWj + bn * XS + bt0) = u4v{hj[0], hj[1], hj[2], hj[3]};
+            *reinterpret_cast<u4v *>(sWj + (N + bn) * XS + bt0) = u4v{lj[0], lj[1], lj[2], lj[3]};
+        }
+    }
+
+    // ---- wave 0: G^T = B C^T on the matrix core, M^T from it; the C rows; the stash of B and dt -----------------------------
+    if (w == 0) {
+        v4f G = {0.f, 0.f, 0.f, 0.f};                    // lane: draft t = li, tokens s = 4 g + r
+#pragma unroll
+        for (int h = 0; h < NH; ++h) G = mfma16(as_bf8(Bs[h]), as_bf8(Cs[h]), G);
+        const int tty = pd + (int)li;                    // draft li as a token of the launch
+        float m[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int s = 4 * g + r;
+            const float cs = lane_get(cum, s), ds = lane_get(dtv, s);
+            float mv = G[r] * __builtin_amdgcn_exp2f(cy - cs) * ds;
+            if (s == tty) mv += D_h;                     // the skip term D x_t
+            m[r] = ((int)li < kb && s <= tty) ? mv : 0.f;
+        }
+        uint32_t h0, h1, l0, l1;
+        split2(m[0], m[1], h0, l0);
+        split2(m[2], m[3], h1, l1);
+        *reinterpret_cast<u2v *>(sM + li * XS + 4 * g) = u2v{h0, h1};
+        *reinterpret_cast<u2v *>(sM + (16 + li) * XS + 4 * g) = u2v{l0, l1};
+#pragma unroll
+        for (int h = 0; h < NH; ++h) *reinterpret_cast<u4v *>(sC + li * CS + 8 * g + 32 * h) = Cs[h];
+        if ((int)li >= pd && (int)li < T) {
+            if (writes_B) {
+#pragma unroll
+                for (int h = 0; h < NH; ++h) *reinterpret_cast<u4v *>(winB_out + oB_wout + (size_t)(li - pd) * GN + 8 * g + 32 * h) = Bs[h];
+            }
+            if (first_tile && g == 0) winDt_out[oDt_wout + (size_t)(li - pd) * H] = (uint16_t)dt_raw;   // the raw dt: replay transforms it again
+        }
+        if (first_tile && hd == 0 && tid == 0) p.last_k[b] = t0 + kb;
+    }
+    __syncthreads();
+    SSMV_TP(4);
+#ifdef SSMV_TRACE
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    SSMV_TP(5);
+#endif
+
+    // ---- the products, tile by tile ------------------------------------------------------------------------------------------
+    float *dstJ = p.state + (size_t)((cur + 1) % 3) * p.slot_stride + head_base + st_off;
+    float *dstK = p.state + (size_t)((cur + 2) % 3) * p.slot_stride + head_base + st_off;
+    uint16_t *yp = static_cast<uint16_t *>(p.y);
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        const unsigned ptl = w * NT + i;                 // row tile inside the workgroup
+        const bf8 Xop = as_bf8(*reinterpret_cast<const u4v *>(sX + (ptl * 16 + li) * XS + 8 * (g & 1)));
+        // Y1^T = h_0 C^T : rows p, columns t, contraction over n; head and tail of h_0 stacked along the contraction
+        v4f Y1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const v4f hv = st[i][q];
+            uint32_t a0, a1, a2, a3;
+            split2(hv.x, hv.y, a0, a2);
+            split2(hv.z, hv.w, a1, a3);
+            const u4v a = {a0, a1, a2, a3};
+            const u2v c2 = *reinterpret_cast<const u2v *>(sC + li * CS + 16 * q + 4 * g);
+            Y1 = mfma16(as_bf8(a), as_bf8(u4v{c2.x, c2.y, c2.x, c2.y}), Y1);
+        }
+        // (i) + (ii): fold the pending tokens in and store the snapshot h_j
+        if (pd > 0) {
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const bf8 Aw = as_bf8(*reinterpret_cast<const u4v *>(sWj + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1)));
+                st[i][q] = mfma16(Aw, Xop, st[i][q] * alphaJ);
+                __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstJ + ((i * NQ + q) << 8)));
+            }
+        }
+        // (iii) + (iv): the drafts, and the snapshot h_k (Algorithm 2), unless every accepted token is to stay pending
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const bf8 Aw = as_bf8(*reinterpret_cast<const u4v *>(sWk + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1)));
+            st[i][q] = mfma16(Aw, Xop, st[i][q] * beta);
+            if (p.write_hk) __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstK + ((i * NQ + q) << 8)));
+        }
+        // Y2^T = X^T M^T : the drafts' outputs from the tokens of this launch (D x_t on the diagonal of M)
+        const bf8 Mop = as_bf8(*reinterpret_cast<const u4v *>(sM + ((g >> 1) * 16 + li) * XS + 8 * (g & 1)));
+        const v4f Y2 = mfma16(Xop, Mop, v4f{0.f, 0.f, 0.f, 0.f});
+        // lane: draft t = li, channels ptl*16 + 4 g .. + 3
+        if ((int)li < k) {
+            float yv[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) yv[r] = (int)li < kb ? fmaf(Y1[r], alphaY, Y2[r]) : 0.f;    // tokens not taken: zeros
+            if constexpr (EXTRA) {
+                if (gated) {                             // y <- y * z * sigmoid(z), in fp32 before the rounding
+                    yv[0] *= silu_fast(bf16lo(zraw[i].x)); yv[1] *= silu_fast(bf16hi(zraw[i].x));
+                    yv[2] *= silu_fast(bf16lo(zraw[i].y)); yv[3] *= silu_fast(bf16hi(zraw[i].y));
+                }
+            }
+            *reinterpret_cast<u2v *>(yp + oX_in + (size_t)li * HP + ptl * 16 + 4 * g) = u2v{pack_bf16x2(yv[0], yv[1]), pack_bf16x2(yv[2], yv[3])};
+        }
+    }
+    SSMV_TP(6);
+#ifdef SSMV_TRACE
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's stores have been acknowledged
+    SSMV_TP(7);
+#endif
+}
+
+template <int N, int NT>
+int launch_shape(const VerifyParams &p, hipStream_t stream)
+{
+    const dim3 grid(p.P / (64 * NT), p.H, p.batch), block(256);
+    const bool conv = p.x_raw != nullptr;
+    const bool extra = p.tok0 > 0 || p.dt_softplus || p.dt_bias || p.z || p.k_seq;
+    if (conv) {
+        if (extra) hipLaunchKernelGGL((verify_mfma_kernel<N, NT, true, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((verify_mfma_kernel<N, NT, true, false>), grid, block, 0, stream, p);
+    } else {
+        if (extra) hipLaunchKernelGGL((verify_mfma_kernel<N, NT, false, true>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((verify_mfma_kernel<N, NT, false, false>), grid, block, 0, stream, p);
+    }
+    return (int)hipGetLastError();
+}
+
+}  // namespace
+
+#ifdef SSMV_TRACE
+int set_trace_mfma(long long *buf) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(trace_buf_), &buf, sizeof(buf)); }
+#endif
+
+bool verify_mfma_supported(int N, int P) { return (N == 32 || N == 64 || N == 128) && P >= 64 && P % 64 == 0; }
+
+int launch_verify_mfma(const VerifyParams &p, hipStream_t stream)
+{
+    if (!verify_mfma_supported(p.N, p.P) || p.io != SSMV_BF16 || !p.tiled || p.h_out || p.lds_tokens > 16)
+        return (int)hipErrorInvalidConfiguration;
+    // two row tiles per wave while that still leaves four workgroups per compute unit, else one
+    const bool two = p.N <= 64 && p.P % 128 == 0 && (long)p.batch * p.H * (p.P / 128) >= 1024;
+    switch (p.N) {
+        case 32: return two ? launch_shape<32, 2>(p, stream) : launch_shape<32, 1>(p, stream);
+        case 64: return two ? launch_shape<64, 2>(p, stream) : launch_shape<64, 1>(p, stream);
+        default: return launch_shape<128, 1>(p, stream);
+    }
+}
+
+}  // namespace ssmv

@@ -33,7 +33,7 @@ def test_constants_match_header():
     for name in ("SSMV_KMAX_LIMIT", "SSMV_CONV_WIDTH", "SSMV_CACHE_NPTR"):
         m = re.search(r"#define\s+%s\s+(\d+)" % name, text)
         assert int(m.group(1)) == getattr(ssmv, name)
-    assert ctypes.sizeof(ssmv.ssmv_dims) == 13 * 4
+    assert ctypes.sizeof(ssmv.ssmv_dims) == 14 * 4
     assert ctypes.sizeof(ssmv.ssmv_cache) == 15 * 8
 
 

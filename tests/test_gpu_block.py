@@ -144,8 +144,11 @@ def test_round_fed_by_several_calls_equals_one_call(name, split):
         _check_ints(many, bk, "round %d" % i)
         idx = torch.from_numpy(many.cache.ints()["cur_slot"]).long()
         live_many, live_one = (v.cache.state_view()[idx, torch.arange(wl.batch)] for v in (many, one))
-        assert rel_err(to_host(live_many), to_host(live_one)) <= 1e-5, "round %d: live slots differ" % i
-        assert rel_err(to_host(many.materialize()), to_host(one.materialize())) <= 1e-5, "round %d: states differ" % i
+        # fp32 rounding on the vector path; on the matrix-core path (bf16 tokens) every fp32 operand of a product enters
+        # as a bf16 head plus tail, 2^-17 relative per product, and the split decides which products are formed
+        h_same = 1e-5 if wl.io == "f32" else 1e-4
+        assert rel_err(to_host(live_many), to_host(live_one)) <= h_same, "round %d: live slots differ" % i
+        assert rel_err(to_host(many.materialize()), to_host(one.materialize())) <= h_same, "round %d: states differ" % i
         for nm in ("conv_ring", "win_xc0", "win_xc1", "win_dt0", "win_dt1", "win_B0", "win_B1"):
             assert torch.equal(many.cache.buffers[nm], one.cache.buffers[nm]), nm
         assert rel_err(to_host(many.materialize()), ora.h) <= tol

@@ -227,3 +227,113 @@ def test_bookkeeping_error_paths():
     bk.commit([7, -2])                              # out of range: clamped to [0, k], sticky error
     assert bk.err == 1 and bk.pend == [0, 0] and bk.pos == [3, 0] and bk.cur == [2, 0]
     assert bk.conv_head == [(2 + 3) % 8, 2]
+
+
+@pytest.mark.parametrize("wl", [TINY, TINY_DIAG], ids=lambda w: w.name)
+def test_I2_from_a_given_conv_history(wl):
+    """Section 4.3 footnote: the conv part of the cache is the last W-1 raw inputs, oldest first.  A schedule started
+    from a random history must equal ONE library convolution over (history ++ accepted stream), whose first outputs
+    see the history in that order; a reversed or shifted history fails this."""
+    data = generate(wl)
+    lp = data.layers[0]
+    W, Cx = wl.conv_width, wl.conv_channels
+    rng = np.random.default_rng(77)
+    init = oracle.round_io(rng.standard_normal((wl.batch, W - 1, Cx)), wl.io)
+    eager = oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.conv_act, wl.ngroups, conv_init=init)
+    lazy = oracle.LazyMirror(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.kmax_eff, wl.ring_len,
+                             wl.conv_act, wl.ngroups, conv_init=init)
+    got_xc = [[] for _ in range(wl.batch)]
+    acc_x = [[] for _ in range(wl.batch)]
+    for rd in data.rounds:
+        _, xc, _ = eager.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
+        yl, xcl = lazy.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
+        assert np.array_equal(xc, xcl)
+        for b in range(wl.batch):
+            a = int(rd.accepted[b])
+            got_xc[b].append(xc[b, :a]); acc_x[b].append(rd.x_raw[b, :a])
+        eager.commit(rd.accepted); lazy.commit(rd.accepted)
+        assert np.allclose(lazy.materialize(), eager.h, rtol=1e-12, atol=1e-13)
+    for b in range(wl.batch):
+        xs = np.concatenate([init[b]] + acc_x[b])                       # oldest first, then the accepted stream
+        L = xs.shape[0] - (W - 1)
+        assert L > 0
+        want = torch.nn.functional.conv1d(
+            torch.from_numpy(xs).T[None], torch.from_numpy(lp.conv_w.astype(np.float64))[:, None, :],
+            None if lp.conv_b is None else torch.from_numpy(lp.conv_b.astype(np.float64)), groups=Cx)[0].T
+        assert want.shape[0] == L
+        if wl.conv_act == "silu":
+            want = torch.nn.functional.silu(want)
+        tol = 1e-2 if wl.io == "bf16" else 3e-7
+        assert np.allclose(np.concatenate(got_xc[b]), want.numpy(), rtol=tol, atol=tol)
+    # the history matters and its order matters: the first outputs change when it is reversed
+    rd = data.rounds[0]
+    e_rev = oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.conv_act, wl.ngroups,
+                               conv_init=init[:, ::-1])
+    e_fwd = oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.conv_act, wl.ngroups, conv_init=init)
+    assert not np.allclose(e_rev.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])[1][:, 0], e_fwd.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])[1][:, 0])
+
+
+def _compositions(n):
+    """All ways to write n as an ordered sum of positive integers."""
+    if n == 0:
+        yield ()
+        return
+    for first in range(1, n + 1):
+        for rest in _compositions(n - first):
+            yield (first,) + rest
+
+
+@pytest.mark.parametrize("wl", [TINY, TINY_DIAG.scaled(k=4)], ids=lambda w: w.name)
+def test_round_fed_by_several_calls_equals_one_call(wl):
+    """Section 4.3, draft side: a round whose k tokens arrive over several calls leaves the cache exactly where one
+    k-token call would, for every way of splitting k <= 4, over rounds with ragged acceptance in between."""
+    data = generate(wl.scaled(rounds=4))
+    lp = data.layers[0]
+    mk = lambda: oracle.LazyMirror(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.kmax_eff, wl.ring_len,
+                                   wl.conv_act, wl.ngroups)
+    for split in _compositions(wl.k):
+        one, many = mk(), mk()
+        eager = _eager(wl, data)
+        for rd in data.rounds:
+            y1, xc1 = one.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
+            ye, _, _ = eager.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
+            t0, ys, xcs = 0, [], []
+            for n in split:
+                s = slice(t0, t0 + n)
+                y, xc = many.verify(rd.x_raw[:, s], rd.dt[0][:, s], rd.B[0][:, s], rd.C[0][:, s], tok0=t0)
+                ys.append(y); xcs.append(xc)
+                t0 += n
+                assert many.bk.last_k == [t0] * wl.batch
+            assert np.array_equal(np.concatenate(xcs, axis=1), xc1)
+            assert np.allclose(np.concatenate(ys, axis=1), y1, rtol=1e-13, atol=1e-14)
+            assert np.allclose(y1, ye, rtol=1e-12, atol=1e-13)
+            assert np.array_equal(many.ring, one.ring) and np.array_equal(many.win_xc, one.win_xc)
+            assert np.array_equal(many.win_dt, one.win_dt) and np.array_equal(many.win_B, one.win_B)
+            assert np.allclose(many.slots, one.slots, rtol=1e-13, atol=1e-14)
+            for m in (one, many):
+                m.commit(rd.accepted)
+            eager.commit(rd.accepted)
+            for name in ("cur", "pend", "pos", "conv_head", "last_k", "win_par", "err"):
+                assert getattr(many.bk, name) == getattr(one.bk, name), name
+            assert np.allclose(many.materialize(), eager.h, rtol=1e-12, atol=1e-13)
+
+
+def test_commit_is_per_sequence_when_some_have_no_verify_pending():
+    """A sequence whose last_k is 0 is left untouched and raises the sticky error; the others commit as usual; the
+    batch-wide window parity follows sequence 0.  Every mix of (verified, not verified) over three sequences."""
+    for mask in itertools.product((0, 1), repeat=3):
+        for a in range(4):
+            bk = oracle.BookkeepingModel(3, 8, 4)
+            ref = oracle.BookkeepingModel(1, 8, 4)
+            bk.verify(3)
+            bk.last_k = [3 * m for m in mask]
+            bk.commit([a, a, a])
+            ref.verify(3); ref.commit([a])
+            for b, m in enumerate(mask):
+                if m:
+                    assert (bk.cur[b], bk.pend[b], bk.pos[b], bk.conv_head[b]) == (ref.cur[0], ref.pend[0], ref.pos[0], ref.conv_head[0])
+                else:
+                    assert (bk.cur[b], bk.pend[b], bk.pos[b], bk.conv_head[b]) == (0, 0, 0, 2)
+                assert bk.last_k[b] == 0
+            assert bk.err == (0 if all(mask) else 1)
+            assert bk.win_par == mask[0]

@@ -28,6 +28,7 @@ class Workload:
     conv_act: str = "none"   # "none" | "silu"
     conv_bias: bool = True
     snapshot_mode: str = "both"   # "both": h_j and h_k as Algorithm 2 | "hj_only": single-snapshot variant
+    engine: str = "auto"     # "auto": the library picks the kernel | "vector": the vector-ALU kernel and row-major state
     kmax: int = 0        # 0 -> k
     layers: int = 1
     seed: int = 0
