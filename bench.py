@@ -258,6 +258,7 @@ def main():
                           ring_len=wl.ring_len, io=wl.io, a_mode=wl.a_mode, conv_act=wl.conv_act,
                           snapshot_mode=wl.snapshot_mode, engine=args.engine)
     sizes = ssmv.ssmv_cache_sizes(dims)
+    matrix_engine = ssmv.ssmv_engine_of(dims) == 1
     cache_bytes = sum(sizes)
     n_inst = args.instances or max(1, math.ceil(args.footprint_gib * 2 ** 30 / cache_bytes))
     caches = [ssmv.LayerCache.allocate(dims) for _ in range(n_inst)]
@@ -346,18 +347,24 @@ def main():
 
     K = args.steps if args.steps > 0 else n_inst * n_rounds
     W = args.warmup if args.warmup >= 0 else max(3, n_inst)
-    rounds_run = (W + K + n_inst - 1) // n_inst + 1
+    # Whatever --warmup is: three untimed rounds through every cache first, so that the pending counts (and with them
+    # the replay work and the h_j stores) have the workload's mix when the timed region starts.  Round 0 on fresh caches
+    # has nothing pending and is 22 % lighter than a steady-state round.
+    PRIME = 3 * n_inst
+    rounds_run = (PRIME + W + K + n_inst - 1) // n_inst + 1
     pend_sched = pend_after([data.rounds[i % n_rounds].accepted for i in range(rounds_run)], [k] * rounds_run,
                             hj_only=wl.snapshot_mode == "hj_only")
+    step_bytes = lambda s: round_bytes(wl, pend_sched[s // n_inst], k, fused, gate=args.block, calls=k if args.draft else 1)
+    # the workload's own figure: mean over its rounds in the steady state (every round but the first)
+    workload_bytes = sum(step_bytes(r * n_inst) for r in range(1, max(2, n_rounds))) / max(1, n_rounds - 1)
 
     result = {}
-    if args.kernel_only:
-        # three untimed rounds through every cache, so that the pending counts have their workload mix
-        for s in range(3 * n_inst):
-            step(s)
-        torch.cuda.synchronize()
+    for s in range(PRIME):
+        step(s)
+    torch.cuda.synchronize()
     if not args.kernel_only:
-        for s in range(W):
+        W0, W = PRIME, PRIME + W                       # first warm-up step, first timed step
+        for s in range(W0, W):
             step(s)
         torch.cuda.synchronize()
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -389,15 +396,21 @@ def main():
         total_ms = ev0.elapsed_time(ev1)
         for c in caches:
             ssmv.ssmv_check(c.c)
-        # algorithmic bytes of exactly the timed steps
-        tot_bytes = 0
-        for s in range(W, W + K):
-            tot_bytes += round_bytes(wl, pend_sched[s // n_inst], k, fused, gate=args.block, calls=k if args.draft else 1)
+        # algorithmic bytes of exactly the timed steps; they must be the workload's mix
+        tot_bytes = sum(step_bytes(s) for s in range(W, W + K))
+        timed_bytes = tot_bytes / K
+        slack = 0.02 if K >= 20 else 0.08              # a handful of steps sees one round's realised pending counts
+        if abs(timed_bytes / workload_bytes - 1.0) > slack:
+            print("bench.py: the timed steps move %.1f MB each, the workload %.1f MB: not the workload's launch mix"
+                  % (timed_bytes / 1e6, workload_bytes / 1e6), file=sys.stderr)
+            sys.exit(3)
+        W -= PRIME                                       # reported as given
         tokens = wl.batch * k * K
         result.update(
             value=tokens / (total_ms * 1e-3),
             ms_per_step=total_ms / K,
             step_hbm_gbps=tot_bytes / (total_ms * 1e-3) / 1e9,
+            timed_bytes=timed_bytes,
         )
 
     # ---- the dominant kernel alone: n_meas back-to-back launches (one HIP graph, kernel nodes only) rotating
@@ -452,7 +465,7 @@ def main():
     avg_ms = sum(durs) / len(durs)
     achieved = (kbytes / n_meas) / (avg_ms * 1e-3) / 1e9
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "verify_kernel_%s_pmc.txt" % wl.name)
+    tpath = os.path.join(ROOT, "profiles", "%s_%s_pmc.txt" % ("verify_mfma_kernel" if matrix_engine else "verify_kernel", wl.name))
     default_path = fused and not general and wl.snapshot_mode == "both" and args.rows == 0 and args.waves == 0
     if default_path and os.path.exists(tpath):     # the counters were read on the default launch only
         for line in open(tpath):
@@ -460,8 +473,9 @@ def main():
                 traffic = float(line.split(":")[1])
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                 "frac": round(achieved / PEAK_HBM_GBPS, 4), "traffic": traffic,
-                "kernel": ("verify_kernel (conv roll fused, one token appended to the round)" if args.draft else
-                           "verify_kernel (conv roll fused)" if fused else "verify_kernel"), "avg_launch_us": round(avg_ms * 1e3, 3),
+                "kernel": ("verify_mfma_kernel" if matrix_engine and args.rows == 0 and args.waves == 0 else "verify_kernel") +
+                          (" (conv roll fused, one token appended to the round)" if args.draft else " (conv roll fused)" if fused else ""),
+                "avg_launch_us": round(avg_ms * 1e3, 3),
                 "median_launch_us": round(durs[len(durs) // 2] * 1e3, 3),
                 "algorithmic_bytes_per_launch": kbytes // n_meas, "launches_timed": n_meas * len(durs)}
 
@@ -517,7 +531,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": ("f32 state and accumulation; bf16 matrix products of head+tail split f32 operands" if matrix_engine else "f32"),
         "data": "synthetic",
         "config": {"workload": "%s: %s-A layer, batch %d, %d heads x headdim %d x d_state %d, k=%d, %s I/O + fp32 state, "
                                "%s acceptance, %d rounds, cold protocol over %d rotating caches (%.2f GiB)"
@@ -532,6 +546,9 @@ def main():
                            else ("naive: snapshot copy + k single-token (conv, verify, commit) rounds per layer" if args.naive
                                  else "conv, verify and commit launches per layer")},
         "hbm_gbps_whole_step": round(result["step_hbm_gbps"], 1),
+        "algorithmic_bytes_per_step_timed": int(result["timed_bytes"]),
+        "algorithmic_bytes_per_step_workload": int(workload_bytes),
+        "engine": "matrix cores, tiled state" if matrix_engine else "vector ALUs, row-major state",
         "copy_r1w2_gbps": round(copy_gbps, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,

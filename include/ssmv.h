@@ -109,6 +109,10 @@ typedef struct {
     int32_t *err_flag;     /* [1] sticky; set by the device on a bad accepted[] or a stray commit   */
 } ssmv_cache;
 
+/* Which kernel the verify launches of these dimensions run on, and with it the layout of the state slots (see
+ * `engine`): 1 = matrix cores on tiled slots, 0 = vector ALUs on row-major slots; a negative ssmv_status for bad dims. */
+int ssmv_engine_of(const ssmv_dims *dims);
+
 /* Bytes the caller must allocate for each pointer of ssmv_cache, in declaration
  * order: state, conv_ring, win_xc[0], win_xc[1], win_dt[0], win_dt[1], win_B[0],
  * win_B[1], cur_slot, pend, pos, conv_head, last_k, win_par, err_flag.  Each size is

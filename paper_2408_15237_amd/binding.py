@@ -34,7 +34,7 @@ ENGINE_CODES = {"auto": SSMV_ENGINE_AUTO, "vector": SSMV_ENGINE_VECTOR}
 EXPORTS = [
     "ssmv_cache_sizes", "ssmv_cache_reset", "conv1d_state_update", "ssm_verify_multistep",
     "ssm_conv_verify_multistep", "ssm_block_multistep", "ssmv_materialize_block", "ssm_prefill_chunked", "ssm_prefill_block", "ssm_commit_rollback", "ssm_commit_rollback_multi", "ssmv_materialize", "ssmv_first_conflict", "ssmv_gated_rmsnorm", "ssmv_check",
-    "ssmv_set_tuning", "ssmv_copy_probe", "ssmv_last_error", "ssmv_version",
+    "ssmv_set_tuning", "ssmv_copy_probe", "ssmv_engine_of", "ssmv_last_error", "ssmv_version",
 ]
 
 
@@ -96,6 +96,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     dp, cp = ctypes.POINTER(ssmv_dims), ctypes.POINTER(ssmv_cache)
     lib.ssmv_cache_sizes.argtypes = [dp, ctypes.POINTER(sz)]
+    lib.ssmv_engine_of.argtypes = [dp]
     lib.ssmv_cache_reset.argtypes = [dp, cp, vp, vp, vp]
     lib.conv1d_state_update.argtypes = [dp, cp, vp, vp, vp, i32, vp, vp]
     lib.ssm_verify_multistep.argtypes = [dp, cp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
@@ -158,6 +159,13 @@ def make_dims(batch, nheads, headdim, dstate, ngroups=1, kmax=4, ring_len=None, 
 
 
 # ---- the C entry points, same names, torch tensors (or raw pointers) in place of pointers ----------
+
+def ssmv_engine_of(dims: ssmv_dims) -> int:
+    rc = load_library().ssmv_engine_of(ctypes.byref(dims))
+    if rc < 0:
+        _ck(rc)
+    return rc
+
 
 def ssmv_cache_sizes(dims: ssmv_dims) -> List[int]:
     out = (ctypes.c_size_t * SSMV_CACHE_NPTR)()

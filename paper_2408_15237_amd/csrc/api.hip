@@ -203,6 +203,13 @@ int ssmv_set_tuning(int32_t rows_per_lane, int32_t waves_per_group)
     return SSMV_OK;
 }
 
+int ssmv_engine_of(const ssmv_dims *d)
+{
+    const int rc = check_dims(d);
+    if (rc != SSMV_OK) return rc;
+    return state_tiled(d) ? 1 : 0;
+}
+
 int ssmv_cache_sizes(const ssmv_dims *d, size_t out_bytes[SSMV_CACHE_NPTR])
 {
     int rc = check_dims(d);

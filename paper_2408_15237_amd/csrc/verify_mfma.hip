@@ -88,17 +88,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
 {
     constexpr int NQ = N / 16;                           // 16-wide tiles along n
     constexpr int NH = N / 32;                           // 32-deep steps of a contraction over n
-    constexpr int RW = 64 * NT;                          // rows of the workgroup
-    constexpr int XS = 24;                               // LDS row stride (bf16 elements) of a [.][16 tokens] row: 48 bytes
-    constexpr int CS = N + 8;                            // LDS row stride of a C row
+    constexpr int RW = 64 * NT;                          // rows (channels) of the workgroup
+    constexpr int XS = 20;                               // LDS row stride (bf16) of a [.][16 tokens] operand row: 40 bytes
+    constexpr int CS = N + 8;                            // LDS row stride of a B or C row
+    constexpr int XRS = RW + 8;                          // LDS row stride of a raw x row
+    constexpr int CX = RW / 8, CB = N / 8;               // 16-byte pieces of an x row, of a B or C row
     constexpr int W = SSMV_CONV_WIDTH;
     constexpr int BT0 = 256 - 2 * N > 0 ? 256 - 2 * N : 0;   // first thread that builds the weighted B rows
-    static_assert(W == 4, "the conv window below is written for four taps");
+    constexpr int XIT = (3 + 16 + 64 / CX - 1) / (64 / CX);  // load rounds of wave 0 over the raw x rows
+    constexpr int BIT = (16 + 64 / CB - 1) / (64 / CB);      // load rounds of waves 1 and 2 over the B and C rows
+    static_assert(W == 4, "the conv below is written for four taps");
 
+    __shared__ __attribute__((aligned(16))) uint16_t sXr[19 * XRS];        // raw x: 3 rows of history, then row 3 + token
+    __shared__ __attribute__((aligned(16))) uint16_t sBr[16 * CS];         // B       [token][n]
+    __shared__ __attribute__((aligned(16))) uint16_t sC[16 * CS];          // C       [draft][n]
+    __shared__ __attribute__((aligned(16))) uint16_t sWgt[RW * W];         // conv taps [row][4]
+    __shared__ __attribute__((aligned(16))) uint16_t sBias[RW];
     __shared__ __attribute__((aligned(16))) uint16_t sX[RW * XS];          // x           [row][token]
     __shared__ __attribute__((aligned(16))) uint16_t sWj[2 * N * XS];      // w^j_s B_s   [head|tail][n][token]
     __shared__ __attribute__((aligned(16))) uint16_t sWk[2 * N * XS];      // w^k_s B_s
-    __shared__ __attribute__((aligned(16))) uint16_t sC[16 * CS];          // C           [draft][n]
     __shared__ __attribute__((aligned(16))) uint16_t sM[2 * 16 * XS];      // M           [head|tail][draft][token]
 
     const unsigned tid = threadIdx.x, l = tid & 63u, w = __builtin_amdgcn_readfirstlane(tid >> 6), li = l & 15u, g = l >> 4;
@@ -125,6 +133,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const float A2 = p.A[hd] * 1.4426950408889634f, D_h = p.D[hd];
     float dtb_h = 0.f;
     if constexpr (EXTRA) if (p.dt_bias) dtb_h = p.dt_bias[hd];
+    int conv_head = 0;
+    if constexpr (CONV) conv_head = (p.conv_head[b] + t0) & (p.ring_len - 1);      // newest raw input fed so far
 
     int grp = 0;
     bool first_head_of_group = true;
@@ -151,69 +161,49 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const size_t oB_wout = oB_win + (size_t)t0 * GN, oX_wout = oX_win + (size_t)t0 * HP, oDt_wout = oDt_win + (size_t)t0 * H;
     const size_t ring_b = (size_t)b * p.ring_len * HP + ch0;
     const int ring_mask = p.ring_len - 1;
-    int conv_head = 0;
-    if constexpr (CONV) conv_head = (p.conv_head[b] + t0) & ring_mask;      // newest raw input fed so far
 
-    // ---- token loads, all issued before the state loads: uniform base pointers, 32-bit lane offsets -------------------------
-    // dt: lane li of every wave takes token li (every wave needs the decay factors)
-    uint32_t dt_raw = 0;
-    if ((int)li < T) dt_raw = (int)li < pd ? (winDt + oDt_win)[li * H] : (dtp + oDt_in)[(li - pd) * H];
-    // x: thread (row xp, chunk) takes the 8 token slots [xt0, xt0 + 8) of its row: pending tokens from the stash, drafts from
-    // this call's input - with the conv folded in: the raw inputs of the chunk's drafts and the three before them
-    const bool xrole = tid < 2 * RW;
-    const unsigned xp = tid % RW;
-    const int xt0 = 8 * (int)__builtin_amdgcn_readfirstlane(tid / RW);     // uniform over a wave
-    const int i_lo = max(0, pd - xt0), i_hi = min(8, T - xt0);             // drafts of the chunk: slots [i_lo, i_hi)
-    uint32_t xv[8], rawv[CONV ? 11 : 1];
-    u2v wraw = {0u, 0u};
-    uint32_t bias_raw = 0;
-    if (xrole) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int tt = xt0 + i;
-            xv[i] = 0;
-            if (tt < pd) xv[i] = (winX + oX_win + (size_t)tt * HP)[xp];
-            else if (!CONV && tt < T) xv[i] = (xin + oX_in + (size_t)(tt - pd) * HP)[xp];
-        }
-        if constexpr (CONV) {
-#pragma unroll
-            for (int m = 0; m < 11; ++m) {
-                rawv[m] = 0;
-                const int j = xt0 - pd - 3 + m;            // position relative to this call's first token; -3..-1: the ring
-                if (m >= i_lo && m < i_hi + 3)
-                    rawv[m] = (j < 0 ? ring + ring_b + (size_t)((conv_head + 1 + j) & ring_mask) * HP : xin + oX_in + (size_t)j * HP)[xp];
-            }
-            if (i_lo < i_hi) {
-                wraw = reinterpret_cast<const u2v *>(static_cast<const uint16_t *>(p.wgt) + (size_t)ch0 * W)[xp];
-                // (no bias: any readable address; the value is dropped at its use)
-                bias_raw = (static_cast<const uint16_t *>(p.bias ? p.bias : p.wgt) + ch0)[xp];
-            }
-        }
-    }
-    // B for the weighted rows: thread (n, chunk) takes B[token][n] of the 8 tokens of its chunk
-    const bool brole = (int)tid >= BT0;
-    const unsigned bn = (unsigned)((int)tid - BT0) % N;
-    const int bt0 = N >= 64 ? 8 * (int)__builtin_amdgcn_readfirstlane((unsigned)((int)tid - BT0) / N) : 8 * (((int)tid - BT0) / N);
-    uint32_t braw[8];
-    if (brole) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int tt = bt0 + i;
-            braw[i] = 0;
-            if (tt < T) braw[i] = (tt < pd ? winB + oB_win + (size_t)tt * GN : Bmp + oB_in + (size_t)(tt - pd) * GN)[bn];
-        }
-    }
-    // wave 0: rows of B (token li) and C (draft li) as operands of G^T = B C^T, 8 consecutive n per lane and step.  Lanes past
-    // the last token read some valid row and drop it at the use.
-    u4v Bs[NH], Cs[NH];
+    // ---- token loads: whole rows in 16-byte pieces, a few instructions per wave, all issued before the state loads -------
+    // wave 0: the raw x rows (history out of the ring, pending tokens out of the stash, this call's tokens); wave 1: the B
+    // rows; wave 2: the C rows; wave 3: conv taps and bias.  Every wave: dt of token li in lane li.
+    // Loads are unconditional inside a role (rows past the last one read the last one again and are dropped at the use):
+    // a load under a lane mask, or one merged with a constant, makes the compiler wait for it on the spot.
+    u4v xk[XIT], bk[BIT], ck[3];                         // one set per role: no value is merged across the roles
     if (w == 0) {
-        const unsigned sb = min(li, (unsigned)(T - 1)), sc = min(li, (unsigned)(kb - 1));
-        const uint16_t *row = (int)sb < pd ? winB + oB_win + (size_t)sb * GN : Bmp + oB_in + (size_t)(sb - pd) * GN;
+        constexpr int RPI = 64 / CX;                     // rows per load instruction
+        const int rfirst = CONV ? 0 : 3, nrow = 3 + T - rfirst;
 #pragma unroll
-        for (int h = 0; h < NH; ++h) {
-            Bs[h] = *reinterpret_cast<const u4v *>(row + 8 * g + 32 * h);
-            Cs[h] = *reinterpret_cast<const u4v *>(Cmp + oB_in + sc * GN + 8 * g + 32 * h);
+        for (int it = 0; it < XIT; ++it) {
+            if (it * RPI < nrow) {
+                const int r = min(rfirst + it * RPI + (int)(l / CX), 2 + T);       // row of sXr
+                const int tt = r - 3;
+                const uint16_t *src = r < 3 ? ring + ring_b + (size_t)((conv_head - 2 + r) & ring_mask) * HP
+                                     : tt < pd ? winX + oX_win + (size_t)tt * HP : xin + oX_in + (size_t)(tt - pd) * HP;
+                xk[it] = *reinterpret_cast<const u4v *>(src + 8 * (l % CX));
+            }
         }
+    } else if (w == 1 || w == 2) {
+        constexpr int RPI = 64 / CB;
+        const int nrow = w == 1 ? T : kb;
+#pragma unroll
+        for (int it = 0; it < BIT; ++it) {
+            if (it * RPI < nrow) {
+                const int r = min(it * RPI + (int)(l / CB), nrow - 1);
+                const uint16_t *src = w == 2 ? Cmp + oB_in + (size_t)r * GN : r < pd ? winB + oB_win + (size_t)r * GN : Bmp + oB_in + (size_t)(r - pd) * GN;
+                bk[it] = *reinterpret_cast<const u4v *>(src + 8 * (l % CB));
+            }
+        }
+    } else if (CONV) {
+        // taps [row][4] bf16: RW/2 pieces; bias: RW/8 pieces (no bias: the taps are read once more and dropped)
+        const u4v *wsrc = reinterpret_cast<const u4v *>(static_cast<const uint16_t *>(p.wgt) + (size_t)ch0 * W);
+        ck[0] = wsrc[min(l, (unsigned)(RW / 2 - 1))];
+        if constexpr (RW / 2 > 64) ck[1] = wsrc[64 + l];
+        ck[2] = (p.bias ? reinterpret_cast<const u4v *>(static_cast<const uint16_t *>(p.bias) + ch0) : wsrc)[l % CX];
+    }
+    // every wave: dt of token li in lane li (lanes past the last token read the last one)
+    uint32_t dt_raw;
+    {
+        const int tt = min((int)li, T - 1);
+        dt_raw = tt < pd ? (winDt + oDt_win)[tt * H] : (dtp + oDt_in)[(tt - pd) * H];
     }
     __builtin_amdgcn_sched_barrier(0);
     SSMV_TP(1);
@@ -242,30 +232,51 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     }
     __builtin_amdgcn_sched_barrier(0);
     SSMV_TP(2);
-    // the token values are used from here on (the wait this needs covers the token loads only: loads return in order)
+
+    // ---- the token rows into LDS as they are (the wait this needs covers the token loads only: loads return in order); the
+    // ring append and the stash of B straight from the registers ---------------------------------------------------------
     pin(dt_raw);
-    if (xrole) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) pin(xv[i]);
-        if constexpr (CONV) {
-#pragma unroll
-            for (int m = 0; m < 11; ++m) pin(rawv[m]);
-            pin(wraw);
-            pin(bias_raw);
-        }
-    }
-    if (brole) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) pin(braw[i]);
-    }
     if (w == 0) {
+        constexpr int RPI = 64 / CX;
+        const int rfirst = CONV ? 0 : 3, nrow = 3 + T - rfirst;
 #pragma unroll
-        for (int h = 0; h < NH; ++h) {
-            pin(Bs[h]);
-            pin(Cs[h]);
-            if ((int)li >= T) Bs[h] = u4v{0u, 0u, 0u, 0u};
-            if ((int)li >= kb) Cs[h] = u4v{0u, 0u, 0u, 0u};
+        for (int it = 0; it < XIT; ++it) {
+            if (it * RPI < nrow) {
+                pin(xk[it]);
+                const int r = rfirst + it * RPI + (int)(l / CX);
+                const int j = r - 3 - pd;                // >= 0: a token of this call
+                if (r < 3 + T) {
+                    *reinterpret_cast<u4v *>(sXr + r * XRS + 8 * (l % CX)) = xk[it];
+                    if (CONV && j >= 0)
+                        *reinterpret_cast<u4v *>(ring + ring_b + (size_t)((conv_head + 1 + j) & ring_mask) * HP + 8 * (l % CX)) = xk[it];
+                }
+            }
         }
+    } else if (w == 1 || w == 2) {
+        constexpr int RPI = 64 / CB;
+        const int nrow = w == 1 ? T : kb;
+        uint16_t *dst = w == 1 ? sBr : sC;
+#pragma unroll
+        for (int it = 0; it < BIT; ++it) {
+            if (it * RPI < nrow) {
+                pin(bk[it]);
+                const int r = it * RPI + (int)(l / CB);
+                if (r < nrow) {
+                    *reinterpret_cast<u4v *>(dst + r * CS + 8 * (l % CB)) = bk[it];
+                    if (w == 1 && writes_B && r >= pd)
+                        *reinterpret_cast<u4v *>(winB_out + oB_wout + (size_t)(r - pd) * GN + 8 * (l % CB)) = bk[it];
+                }
+            }
+        }
+    } else if (CONV) {
+        pin(ck[0]);
+        if ((int)l < RW / 2) reinterpret_cast<u4v *>(sWgt)[l] = ck[0];
+        if constexpr (RW / 2 > 64) {
+            pin(ck[1]);
+            reinterpret_cast<u4v *>(sWgt)[64 + l] = ck[1];
+        }
+        pin(ck[2]);
+        if ((int)l < CX) reinterpret_cast<u4v *>(sBias)[l] = p.bias ? ck[2] : u4v{0u, 0u, 0u, 0u};
     }
     SSMV_TP(3);
 
@@ -284,58 +295,96 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const float alphaJ = __builtin_amdgcn_exp2f(cumJ), beta = __builtin_amdgcn_exp2f(cumK - cumJ);
     const float cy = lane_get(cum, min(pd + (int)li, 15));   // draft li is token pd + li
     const float alphaY = __builtin_amdgcn_exp2f(cy);
+    if (w == 0 && first_tile) {
+        if (g == 0 && (int)li >= pd && (int)li < T) winDt_out[oDt_wout + (size_t)(li - pd) * H] = (uint16_t)dt_raw;   // the raw dt: replay transforms it again
+        if (hd == 0 && tid == 0) p.last_k[b] = t0 + kb;
+    }
+    __syncthreads();
 
-    // ---- x: conv roll, stash, ring append, and the [row][token] operand ---------------------------------------------------
-    if (xrole) {
-        float wf[4] = {bf16lo(wraw.x), bf16hi(wraw.x), bf16lo(wraw.y), bf16hi(wraw.y)};
-        const float bias_f = p.bias ? bf16lo(bias_raw) : 0.f;
-        uint32_t out[8];
+    // ---- x: conv roll, stash, and the [row][token] operand.  An item is two adjacent channels x two adjacent token slots ----
+    {
+        constexpr int XI = RW * 4 / 256;                 // items per thread
+        const uint32_t *sXr32 = reinterpret_cast<const uint32_t *>(sXr);
+        uint32_t *sX32 = reinterpret_cast<uint32_t *>(sX);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int tt = xt0 + i, t = tt - pd;
-            uint32_t bits = xv[i];
-            const bool draft = tt >= pd && tt < T;
-            if constexpr (CONV) {
-                if (draft) {
-                    // width-4 causal depthwise conv, fp32 accumulate in tap order, rounded to the I/O type
-                    float s = bias_f;
-                    s = fmaf(wf[0], bf16lo(rawv[i]), s);
-                    s = fmaf(wf[1], bf16lo(rawv[i + 1]), s);
-                    s = fmaf(wf[2], bf16lo(rawv[i + 2]), s);
-                    s = fmaf(wf[3], bf16lo(rawv[i + 3]), s);
-                    if (p.conv_act == SSMV_ACT_SILU) s = s / (1.f + expf(-s));
-                    bits = f32_to_bf16_bits(s);
-                    ring[ring_b + (size_t)((conv_head + 1 + t) & ring_mask) * HP + xp] = (uint16_t)rawv[i + 3];
+        for (int it = 0; it < XI; ++it) {
+            const unsigned idx = tid + 256 * it, cp = idx % (RW / 2), u = idx / (RW / 2);
+            uint32_t outA = 0, outB = 0;                 // channel 2 cp and channel 2 cp + 1: slots 2 u, 2 u + 1
+            if ((int)(2 * u) < T) {
+                float wf[2][4], bias_f[2] = {0.f, 0.f};
+                if constexpr (CONV) {
+                    const u4v wv = reinterpret_cast<const u4v *>(sWgt)[cp];
+                    wf[0][0] = bf16lo(wv.x); wf[0][1] = bf16hi(wv.x); wf[0][2] = bf16lo(wv.y); wf[0][3] = bf16hi(wv.y);
+                    wf[1][0] = bf16lo(wv.z); wf[1][1] = bf16hi(wv.z); wf[1][2] = bf16lo(wv.w); wf[1][3] = bf16hi(wv.w);
+                    const uint32_t bv = reinterpret_cast<const uint32_t *>(sBias)[cp];
+                    bias_f[0] = bf16lo(bv); bias_f[1] = bf16hi(bv);
+                }
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int tt = 2 * (int)u + e, j = tt - pd;
+                    if (tt < T) {
+                        uint32_t bits = sXr32[(3 + tt) * (XRS / 2) + cp];
+                        if (CONV && j >= 0) {
+                            // width-4 causal depthwise conv, fp32 accumulate in tap order, rounded to the I/O type; the
+                            // three inputs before token j: earlier tokens of this call, else the ring's history rows
+                            float s0 = bias_f[0], s1 = bias_f[1];
+#pragma unroll
+                            for (int i = 0; i < 3; ++i) {
+                                const uint32_t tap = sXr32[(j + i < 3 ? j + i : tt + i) * (XRS / 2) + cp];
+                                s0 = fmaf(wf[0][i], bf16lo(tap), s0);
+                                s1 = fmaf(wf[1][i], bf16hi(tap), s1);
+                            }
+                            s0 = fmaf(wf[0][3], bf16lo(bits), s0);
+                            s1 = fmaf(wf[1][3], bf16hi(bits), s1);
+                            if (p.conv_act == SSMV_ACT_SILU) {
+                                s0 = s0 / (1.f + expf(-s0));
+                                s1 = s1 / (1.f + expf(-s1));
+                            }
+                            bits = pack_bf16x2(s0, s1);
+                        }
+                        if (j >= 0) reinterpret_cast<uint32_t *>(winX_out + oX_wout + (size_t)j * HP)[cp] = bits;
+                        outA |= (bits & 0xffffu) << (16 * e);
+                        outB |= (bits >> 16) << (16 * e);
+                    }
                 }
             }
-            if (draft) winX_out[oX_wout + (size_t)t * HP + xp] = (uint16_t)bits;
-            out[i] = tt < T ? (bits & 0xffffu) : 0u;
+            sX32[(2 * cp) * (XS / 2) + u] = outA;
+            sX32[(2 * cp + 1) * (XS / 2) + u] = outB;
         }
-        *reinterpret_cast<u4v *>(sX + xp * XS + xt0) = u4v{out[0] | (out[1] << 16), out[2] | (out[3] << 16), out[4] | (out[5] << 16), out[6] | (out[7] << 16)};
     }
 
     // ---- weighted, transposed B rows: head and tail, for the snapshot h_j (pending tokens) and for h_k (drafts) -------------
-    if (brole) {
+    if ((int)tid >= BT0) {
+        const unsigned bi = tid - BT0, bn = bi % N, bt0 = 8 * (bi / N);
         uint32_t hj[4], lj[4], hk[4], lk[4];
 #pragma unroll
         for (int ii = 0; ii < 4; ++ii) {
-            const float b0 = bf16lo(braw[2 * ii]), b1 = bf16lo(braw[2 * ii + 1]);
-            split2(lane_get(wk, bt0 + 2 * ii) * b0, lane_get(wk, bt0 + 2 * ii + 1) * b1, hk[ii], lk[ii]);
-            split2(lane_get(wj, bt0 + 2 * ii) * b0, lane_get(wj, bt0 + 2 * ii + 1) * b1, hj[ii], lj[ii]);
+            const int ta = bt0 + 2 * ii;
+            // rows past the last token hold whatever LDS held: select, do not multiply
+            const float b0 = ta < T ? bf16lo(sBr[ta * CS + bn]) : 0.f, b1 = ta + 1 < T ? bf16lo(sBr[(ta + 1) * CS + bn]) : 0.f;
+            split2(lane_get(wk, ta) * b0, lane_get(wk, ta + 1) * b1, hk[ii], lk[ii]);
+            split2(lane_get(wj, ta) * b0, lane_get(wj, ta + 1) * b1, hj[ii], lj[ii]);
         }
-        *reinterpret_cast<u4v *>(sWk + bn * XS + bt0) = u4v{hk[0], hk[1], hk[2], hk[3]};
-        *reinterpret_cast<u4v *>(sWk + (N + bn) * XS + bt0) = u4v{lk[0], lk[1], lk[2], lk[3]};
+        u2v *dk = reinterpret_cast<u2v *>(sWk + bn * XS + bt0), *dkl = reinterpret_cast<u2v *>(sWk + (N + bn) * XS + bt0);
+        dk[0] = u2v{hk[0], hk[1]}; dk[1] = u2v{hk[2], hk[3]};
+        dkl[0] = u2v{lk[0], lk[1]}; dkl[1] = u2v{lk[2], lk[3]};
         if (pd > 0) {
-            *reinterpret_cast<u4v *>(sWj + bn * XS + bt0) = u4v{hj[0], hj[1], hj[2], hj[3]};
-            *reinterpret_cast<u4v *>(sWj + (N + bn) * XS + bt0) = u4v{lj[0], lj[1], lj[2], lj[3]};
+            u2v *dj = reinterpret_cast<u2v *>(sWj + bn * XS + bt0), *djl = reinterpret_cast<u2v *>(sWj + (N + bn) * XS + bt0);
+            dj[0] = u2v{hj[0], hj[1]}; dj[1] = u2v{hj[2], hj[3]};
+            djl[0] = u2v{lj[0], lj[1]}; djl[1] = u2v{lj[2], lj[3]};
         }
     }
 
-    // ---- wave 0: G^T = B C^T on the matrix core, M^T from it; the C rows; the stash of B and dt -----------------------------
+    // ---- wave 0: G^T = B C^T on the matrix core, M^T from it ---------------------------------------------------------------
     if (w == 0) {
         v4f G = {0.f, 0.f, 0.f, 0.f};                    // lane: draft t = li, tokens s = 4 g + r
 #pragma unroll
-        for (int h = 0; h < NH; ++h) G = mfma16(as_bf8(Bs[h]), as_bf8(Cs[h]), G);
+        for (int h = 0; h < NH; ++h) {
+            u4v bs = *reinterpret_cast<const u4v *>(sBr + li * CS + 8 * g + 32 * h), cs_ = *reinterpret_cast<const u4v *>(sC + li * CS + 8 * g + 32 * h);
+            if ((int)li >= T) bs = u4v{0u, 0u, 0u, 0u};
+            if ((int)li >= kb) cs_ = u4v{0u, 0u, 0u, 0u};
+            G = mfma16(as_bf8(bs), as_bf8(cs_), G);
+        }
         const int tty = pd + (int)li;                    // draft li as a token of the launch
         float m[4];
 #pragma unroll
@@ -351,16 +400,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         split2(m[2], m[3], h1, l1);
         *reinterpret_cast<u2v *>(sM + li * XS + 4 * g) = u2v{h0, h1};
         *reinterpret_cast<u2v *>(sM + (16 + li) * XS + 4 * g) = u2v{l0, l1};
-#pragma unroll
-        for (int h = 0; h < NH; ++h) *reinterpret_cast<u4v *>(sC + li * CS + 8 * g + 32 * h) = Cs[h];
-        if ((int)li >= pd && (int)li < T) {
-            if (writes_B) {
-#pragma unroll
-                for (int h = 0; h < NH; ++h) *reinterpret_cast<u4v *>(winB_out + oB_wout + (size_t)(li - pd) * GN + 8 * g + 32 * h) = Bs[h];
-            }
-            if (first_tile && g == 0) winDt_out[oDt_wout + (size_t)(li - pd) * H] = (uint16_t)dt_raw;   // the raw dt: replay transforms it again
-        }
-        if (first_tile && hd == 0 && tid == 0) p.last_k[b] = t0 + kb;
     }
     __syncthreads();
     SSMV_TP(4);
@@ -373,10 +412,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     float *dstJ = p.state + (size_t)((cur + 1) % 3) * p.slot_stride + head_base + st_off;
     float *dstK = p.state + (size_t)((cur + 2) % 3) * p.slot_stride + head_base + st_off;
     uint16_t *yp = static_cast<uint16_t *>(p.y);
+    // a [.][16 tokens] operand row: 16 bytes at an 8-byte aligned address
+    auto row16 = [](const uint16_t *row) {
+        const u2v a = reinterpret_cast<const u2v *>(row)[0], c = reinterpret_cast<const u2v *>(row)[1];
+        return as_bf8(u4v{a.x, a.y, c.x, c.y});
+    };
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
         const unsigned ptl = w * NT + i;                 // row tile inside the workgroup
-        const bf8 Xop = as_bf8(*reinterpret_cast<const u4v *>(sX + (ptl * 16 + li) * XS + 8 * (g & 1)));
+        const bf8 Xop = row16(sX + (ptl * 16 + li) * XS + 8 * (g & 1));
         // Y1^T = h_0 C^T : rows p, columns t, contraction over n; head and tail of h_0 stacked along the contraction
         v4f Y1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -393,7 +437,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         if (pd > 0) {
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
-                const bf8 Aw = as_bf8(*reinterpret_cast<const u4v *>(sWj + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1)));
+                const bf8 Aw = row16(sWj + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1));
                 st[i][q] = mfma16(Aw, Xop, st[i][q] * alphaJ);
                 __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstJ + ((i * NQ + q) << 8)));
             }
@@ -401,12 +445,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         // (iii) + (iv): the drafts, and the snapshot h_k (Algorithm 2), unless every accepted token is to stay pending
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
-            const bf8 Aw = as_bf8(*reinterpret_cast<const u4v *>(sWk + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1)));
+            const bf8 Aw = row16(sWk + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1));
             st[i][q] = mfma16(Aw, Xop, st[i][q] * beta);
             if (p.write_hk) __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstK + ((i * NQ + q) << 8)));
         }
         // Y2^T = X^T M^T : the drafts' outputs from the tokens of this launch (D x_t on the diagonal of M)
-        const bf8 Mop = as_bf8(*reinterpret_cast<const u4v *>(sM + ((g >> 1) * 16 + li) * XS + 8 * (g & 1)));
+        const bf8 Mop = row16(sM + ((g >> 1) * 16 + li) * XS + 8 * (g & 1));
         const v4f Y2 = mfma16(Xop, Mop, v4f{0.f, 0.f, 0.f, 0.f});
         // lane: draft t = li, channels ptl*16 + 4 g .. + 3
         if ((int)li < k) {

@@ -168,20 +168,3 @@ def run_parity(wl: Workload, data: WorkloadData, layer: int = 0, x_override=None
         worst["y"], worst["xc"] = max(worst["y"], e_y), max(worst["xc"], e_xc)
     ssmv.ssmv_check(hip.cache.c)
     return worst
-
-
-def slice_workload(wl: Workload, data: WorkloadData, seqs, heads, layer: int = 0):
-    """The sub-problem made of the given sequences and heads (independent recurrences), for the oracle."""
-    assert wl.ngroups == 1
-    P = wl.headdim
-    ch = np.concatenate([np.arange(h * P, (h + 1) * P) for h in heads])
-    lp = data.layers[layer]
-    from workload.generate import LayerParams, RoundInputs
-    sub_lp = LayerParams(A=lp.A[heads], D=lp.D[heads], conv_w=lp.conv_w[ch],
-                         conv_b=None if lp.conv_b is None else lp.conv_b[ch], h0=lp.h0[seqs][:, heads])
-    sub_wl = wl.scaled(batch=len(seqs), nheads=len(heads), layers=1)
-    rounds = []
-    for rd in data.rounds:
-        rounds.append(RoundInputs(x_raw=rd.x_raw[seqs][:, :, ch], dt=[rd.dt[layer][seqs][:, :, heads]],
-                                  B=[rd.B[layer][seqs]], C=[rd.C[layer][seqs]], accepted=rd.accepted[seqs]))
-    return sub_wl, WorkloadData(wl=sub_wl, layers=[sub_lp], rounds=rounds), ch

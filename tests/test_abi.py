@@ -37,6 +37,24 @@ def test_constants_match_header():
     assert ctypes.sizeof(ssmv.ssmv_cache) == 15 * 8
 
 
+def test_engine_choice_is_a_function_of_the_dimensions():
+    mk = ssmv.make_dims
+    assert ssmv.ssmv_engine_of(mk(32, 32, 128, 64, kmax=4, io="bf16")) == 1
+    assert ssmv.ssmv_engine_of(mk(16, 32, 128, 64, kmax=8, io="bf16")) == 1
+    assert ssmv.ssmv_engine_of(mk(1, 80, 64, 128, kmax=8, io="bf16")) == 1
+    assert ssmv.ssmv_engine_of(mk(32, 32, 128, 64, kmax=4, io="bf16", engine="vector")) == 0
+    assert ssmv.ssmv_engine_of(mk(32, 32, 128, 64, kmax=9, io="bf16")) == 0                           # 8 + 9 tokens in a launch
+    assert ssmv.ssmv_engine_of(mk(32, 32, 128, 64, kmax=8, io="bf16", snapshot_mode="hj_only")) == 1  # 8 + 8
+    assert ssmv.ssmv_engine_of(mk(32, 32, 128, 64, kmax=9, io="bf16", snapshot_mode="hj_only")) == 0
+    assert ssmv.ssmv_engine_of(mk(32, 32, 128, 64, kmax=4, io="f32")) == 0
+    assert ssmv.ssmv_engine_of(mk(32, 32, 32, 64, kmax=4, io="bf16")) == 0                            # headdim not a multiple of 64
+    assert ssmv.ssmv_engine_of(mk(32, 32, 128, 16, kmax=4, io="bf16")) == 0
+    assert ssmv.ssmv_engine_of(mk(1, 8192, 1, 16, kmax=8, io="bf16", a_mode="diag")) == 0
+    d = mk(2, 4, 16, 16, kmax=4, io="f32")
+    d.engine = 7
+    assert _code(ssmv.ssmv_engine_of, d) == ssmv.SSMV_EINVAL
+
+
 def test_cache_sizes():
     d = ssmv.make_dims(32, 32, 128, 64, kmax=4, io="bf16")
     s = ssmv.ssmv_cache_sizes(d)
@@ -109,6 +127,8 @@ def test_argument_validation_precedes_any_gpu_work():
     assert _code(ssmv.ssm_block_multistep, d, c, k=2, tok0=3, xc=P, **blk) == ssmv.SSMV_EINVAL
     assert _code(ssmv.ssm_block_multistep, d, c, k=1, tok0=-1, xc=P, **blk) == ssmv.SSMV_EINVAL
     assert _code(ssmv.ssm_block_multistep, d, c, k=1, tok0=1, xc=P, k_seq=P, **blk) == ssmv.SSMV_EUNSUPPORTED
+    # a later call of a round must bring raw inputs: conv1d_state_update cannot append behind the round's earlier tokens
+    assert _code(ssmv.ssm_block_multistep, d, c, k=1, tok0=1, xc=P, **blk) == ssmv.SSMV_EUNSUPPORTED
     assert _code(ssmv.ssm_block_multistep, d, c, k=1, xc=P, dt_softplus=2, **blk) == ssmv.SSMV_EINVAL
     assert _code(ssmv.ssm_block_multistep, d, c, k=1, xc=P, z=P + 2, **blk) == ssmv.SSMV_EALIGN
     d_hj = ssmv.make_dims(2, 4, 16, 16, kmax=4, io="f32", snapshot_mode="hj_only")
@@ -124,6 +144,9 @@ def test_argument_validation_precedes_any_gpu_work():
     assert _code(ssmv.ssm_prefill_block, d_ok, c, L=8, dt_softplus=2, **pf) == ssmv.SSMV_EINVAL
     assert _code(ssmv.ssm_prefill_block, d_ok, c, L=8, z=P + 4, **pf) == ssmv.SSMV_EALIGN
     assert _code(ssmv.ssm_prefill_block, d_ok, c, L=8, seq_len=P + 2, **pf) == ssmv.SSMV_EALIGN
+    # 32-bit token offsets: the widest token row decides, here B and C (8 groups x 128) against 4 x 64 channels
+    d_wide = ssmv.make_dims(1, 8, 32, 128, ngroups=8, kmax=4, io="bf16")
+    assert _code(ssmv.ssm_prefill_chunked, d_wide, c, P, P, None, P, P, P, P, P, 3000000, P, 0) == ssmv.SSMV_EUNSUPPORTED
     d_diag = ssmv.make_dims(1, 64, 1, 16, a_mode="diag")
     assert _code(ssmv.ssm_prefill_chunked, d_diag, c, P, P, None, P, P, P, P, P, 8, P, 0) == ssmv.SSMV_EUNSUPPORTED
     # broken cache struct

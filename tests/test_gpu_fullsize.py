@@ -1,9 +1,8 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times (automatic
 launch shape, conv roll fused into the verify launch, one commit launch over the caches).
 
-The oracle is too slow for every element at these sizes, so it computes sampled (sequence, head)
-recurrences one by one -- they are independent, so the sample is exact, not approximate -- while the
-integer bookkeeping is still compared for every sequence.
+The fp64 oracle (OpenMP over sequence x head) does a cfg3 round in some tens of milliseconds, so every
+element of every round is compared at every size; the integer bookkeeping is compared for every sequence.
 """
 import numpy as np
 import pytest
@@ -13,7 +12,7 @@ import oracle
 import paper_2408_15237_amd as ssmv
 from workload import CONFIGS, generate, round_to_io
 
-from _harness import HipLayer, TOL, eager_oracle, rel_err, run_parity, slice_workload, to_dev, to_host
+from _harness import HipLayer, TOL, check_close, eager_oracle, rel_err, run_parity, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -25,47 +24,14 @@ def _auto_tuning():
     ssmv.ssmv_set_tuning(0, 0)
 
 
-def _sampled_parity(wl, data, seqs, heads, state_every=8, layer=0):
-    """Full-size GPU run; oracle on the (seqs x heads) sub-problem."""
-    tol = TOL[wl.io]
-    P, N = wl.headdim, wl.dstate
-    sub_wl, sub, ch = slice_workload(wl, data, seqs, heads, layer)
-    ora = eager_oracle(sub_wl, sub.layers[0])
-    hip = HipLayer(wl, data.layers[layer])
-    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
-    caches = [hip.cache.c]
-    worst = 0.0
-    for i, rd in enumerate(data.rounds):
-        k = rd.x_raw.shape[1]
-        srd = sub.rounds[i]
-        y_ref, xc_ref, _ = ora.verify(srd.x_raw, srd.dt[0], srd.B[0], srd.C[0])
-        y, xc = hip.conv_verify(to_dev(rd.x_raw, wl.io), to_dev(rd.dt[layer], wl.io), to_dev(rd.B[layer], wl.io),
-                                to_dev(rd.C[layer], wl.io))
-        y_s = to_host(y)[seqs][:, :, ch]
-        xc_s = to_host(xc)[seqs][:, :, ch]
-        e_y, e_xc = rel_err(y_s, y_ref), rel_err(xc_s, xc_ref)
-        assert e_y <= tol and e_xc <= tol, "round %d: y %.3g xc %.3g (bound %.3g)" % (i, e_y, e_xc, tol)
-        worst = max(worst, e_y)
-        ssmv.ssm_commit_rollback_multi(hip.dims, caches, torch.from_numpy(rd.accepted).to("cuda"))
-        ora.commit(srd.accepted)
-        bk.verify(k)
-        bk.commit(rd.accepted)
-        ints = hip.cache.ints()
-        assert ints["cur_slot"].tolist() == bk.cur and ints["pend"].tolist() == bk.pend
-        assert ints["pos"].tolist() == bk.pos and ints["conv_head"].tolist() == bk.conv_head
-        assert ints["win_par"] == bk.win_par and ints["err_flag"] == 0
-        if i % state_every == 0 or i == len(data.rounds) - 1:
-            h = to_host(hip.materialize())[seqs][:, heads]
-            e_h = rel_err(h, ora.h)
-            assert e_h <= tol, "round %d: state %.3g" % (i, e_h)
-    ssmv.ssmv_check(hip.cache.c)
-    return worst
-
-
-def test_cfg3_full_size_sampled():
-    wl = CONFIGS["cfg3"]
-    worst = _sampled_parity(wl, generate(wl), seqs=[0, 13, 31], heads=[0, 17, 31])
-    print("cfg3 full size: worst y error on the sample %.3g" % worst)
+@pytest.mark.parametrize("engine", ["auto", "vector"])
+def test_cfg3_full_size_every_element(engine):
+    """All 32 sequences x 32 heads x 64 rounds, every y and conv output, the state every 8 rounds: on the kernel the
+    library picks (matrix cores, tiled state) and on the vector kernel (row-major state)."""
+    wl = CONFIGS["cfg3"].scaled(engine=engine)
+    assert ssmv.ssmv_engine_of(ssmv.make_dims(wl.batch, wl.nheads, wl.headdim, wl.dstate, kmax=wl.k, io=wl.io, engine=engine)) == (engine == "auto")
+    worst = run_parity(wl, generate(wl), check_state_every=8, fused=True)
+    print("cfg3 full size, engine %s: worst errors %s" % (engine, {k: "%.3g" % v for k, v in worst.items()}))
 
 
 def test_cfg1_full_size_every_element():
@@ -80,55 +46,58 @@ def test_cfg2_full_size_every_element():
         run_parity(wl, generate(wl), check_state_every=8, fused=fused)
 
 
-def test_cfg4_stack_teacher_forced_from_the_oracle_chain():
-    """24 layers in sequence.  The oracle runs its own chain on two sampled sequences (layer output ->
-    rounded to bf16 -> fixed projection in fp64 -> rounded to bf16 -> next layer's raw input); each GPU layer is
-    fed the ORACLE chain's input for those sequences, so every layer is compared at single-layer tolerance and
-    nothing the GPU computed ever enters the oracle.  The other sequences follow the GPU's own chain (projection
-    glue by torch.matmul, not part of the library), which keeps every launch at its full size."""
-    wl = CONFIGS["cfg4"].scaled(rounds=6)
+def test_cfg4_stack_every_layer_every_sequence():
+    """24 layers in sequence, all 16 sequences, all 32 rounds.  The oracle runs its own chain (layer output -> rounded to
+    bf16 -> fixed projection in fp64 -> rounded to bf16 -> next layer's raw input).  Two GPU stacks run beside it:
+    * teacher-forced: every layer is fed the ORACLE chain's input, so every layer of every round is compared at
+      single-layer tolerance and nothing the GPU computed ever enters the oracle;
+    * free-running: every layer is fed the previous GPU layer's own output through the projection (torch.matmul: glue,
+      not part of the library).  A bf16 output that lands on the other side of a rounding boundary moves the next
+      layer's input by one bf16 step, so the chains drift apart by rounding noise; the last layer's output is held to
+      FREE_TOL on max|g - r| / max|r|, a bound set from the measured drift (printed) with a margin."""
+    FREE_TOL = 0.06
+    wl = CONFIGS["cfg4"]
     data = generate(wl)
     tol = TOL[wl.io]
-    seqs = [3, 12]
-    heads = list(range(wl.nheads))
     Wp64 = data.Wp.astype(np.float64)
     Wp_dev = to_dev(data.Wp, wl.io)
-    layers = [HipLayer(wl, lp) for lp in data.layers]
-    oras, subs = [], []
-    for li in range(wl.layers):
-        sub_wl, sub, _ = slice_workload(wl, data, seqs, heads, li)
-        oras.append(eager_oracle(sub_wl, sub.layers[0]))
-        subs.append(sub)
+    forced = [HipLayer(wl, lp) for lp in data.layers]
+    free = [HipLayer(wl, lp) for lp in data.layers]
+    oras = [eager_oracle(wl, lp) for lp in data.layers]
     bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
-    all_caches = [l.cache.c for l in layers]
-    worst = 0.0
+    worst, worst_free = 0.0, 0.0
     for i, rd in enumerate(data.rounds):
-        x_gpu = to_dev(rd.x_raw, wl.io)                       # layer 0 input, all sequences
-        x_ora = rd.x_raw[seqs].astype(np.float64)             # oracle chain input, sampled sequences
-        for li, layer in enumerate(layers):
-            x_gpu[seqs] = to_dev(x_ora, wl.io)                # teacher forcing: CPU values into the GPU, never back
-            srd = subs[li].rounds[i]
-            y_ref, _, _ = oras[li].verify(x_ora, srd.dt[0], srd.B[0], srd.C[0])
-            y, _ = layer.conv_verify(x_gpu, to_dev(rd.dt[li], wl.io), to_dev(rd.B[li], wl.io), to_dev(rd.C[li], wl.io))
-            e_y = rel_err(to_host(y)[seqs], y_ref)
-            assert e_y <= tol, "round %d layer %d: y error %.3g > %.3g" % (i, li, e_y, tol)
+        x_ora = rd.x_raw.astype(np.float64)                   # the oracle chain's input to layer 0
+        x_free = to_dev(rd.x_raw, wl.io)
+        for li in range(wl.layers):
+            dt, Bm, Cm = (to_dev(v[li], wl.io) for v in (rd.dt, rd.B, rd.C))
+            y_ref, _, _ = oras[li].verify(x_ora, rd.dt[li], rd.B[li], rd.C[li])
+            y, _ = forced[li].conv_verify(to_dev(x_ora, wl.io), dt, Bm, Cm)           # CPU values into the GPU, never back
+            e_y, _ = check_close(to_host(y), y_ref, tol, "round %d layer %d: y" % (i, li))
             worst = max(worst, e_y)
+            y_f, _ = free[li].conv_verify(x_free, dt, Bm, Cm)
+            if li == wl.layers - 1:
+                m = float(np.max(np.abs(to_host(y_f) - y_ref)) / np.max(np.abs(y_ref)))
+                worst_free = max(worst_free, m)
+                assert m <= FREE_TOL, "round %d: free-running chain, last layer: %.3g" % (i, m)
             # hand-off to the next layer
-            x_gpu = torch.matmul(y, Wp_dev.t()).contiguous()
+            x_free = torch.matmul(y_f, Wp_dev.t()).contiguous()
             x_ora = oracle.round_io(oracle.round_io(y_ref, wl.io) @ Wp64.T, wl.io)
         acc = torch.from_numpy(rd.accepted).to("cuda")
-        ssmv.ssm_commit_rollback_multi(layers[0].dims, all_caches, acc)
+        for stack in (forced, free):
+            ssmv.ssm_commit_rollback_multi(stack[0].dims, [l.cache.c for l in stack], acc)
         bk.verify(wl.k)
         bk.commit(rd.accepted)
-        for li, layer in enumerate(layers):
-            oras[li].commit(rd.accepted[seqs])
-            ints = layer.cache.ints()
-            assert ints["cur_slot"].tolist() == bk.cur and ints["pend"].tolist() == bk.pend and ints["pos"].tolist() == bk.pos
-        if i == len(data.rounds) - 1:
+        for li in range(wl.layers):
+            oras[li].commit(rd.accepted)
+            for stack in (forced, free):
+                ints = stack[li].cache.ints()
+                assert ints["cur_slot"].tolist() == bk.cur and ints["pend"].tolist() == bk.pend and ints["pos"].tolist() == bk.pos
+                assert ints["conv_head"].tolist() == bk.conv_head and ints["err_flag"] == 0
+        if i % 8 == 7 or i == len(data.rounds) - 1:
             for li in (0, 11, 23):
-                e_h = rel_err(to_host(layers[li].materialize())[seqs], oras[li].h)
-                assert e_h <= tol, "layer %d final state error %.3g" % (li, e_h)
-    print("cfg4 stack: worst y error %.3g" % worst)
+                check_close(to_host(forced[li].materialize()), oras[li].h, tol, "round %d layer %d: state" % (i, li))
+    print("cfg4 stack: worst y error, teacher-forced %.3g; free-running last layer max|g-r|/max|r| %.3g" % (worst, worst_free))
 
 
 def test_one_round_as_a_hip_graph_replayed_with_eager_work_in_between():

@@ -330,6 +330,30 @@ def test_device_error_flag_paths():
     assert ints["conv_head"].tolist() == bk.conv_head and ints["err_flag"] == bk.err == 1
 
 
+def test_commit_is_per_sequence_when_some_have_no_verify_pending():
+    """The 'no verify pending' rule per sequence, against the integer model: last_k is cleared by hand for some
+    sequences after a verify, then one commit covers all of them."""
+    wl = Workload("mix", "scalar", batch=4, nheads=1, headdim=16, dstate=16, k=3, rounds=1, io="f32", accept="uniform", seed=17)
+    data = generate(wl)
+    lp, rd = data.layers[0], data.rounds[0]
+    for mask in ([1, 0, 1, 0], [0, 1, 1, 1], [0, 0, 0, 0]):
+        hip = HipLayer(wl, lp)
+        xc = hip.conv(to_dev(rd.x_raw, wl.io))
+        hip.verify(xc, to_dev(rd.dt[0], wl.io), to_dev(rd.B[0], wl.io), to_dev(rd.C[0], wl.io))
+        lk = hip.cache.buffers["last_k"].view(torch.int32)
+        lk[:wl.batch] = lk[:wl.batch] * torch.tensor(mask, dtype=torch.int32, device="cuda")
+        acc = np.array([3, 1, 2, 0], dtype=np.int32)
+        hip.commit(torch.from_numpy(acc).to("cuda"))
+        bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
+        bk.verify(wl.k)
+        bk.last_k = [wl.k * m for m in mask]
+        bk.commit(acc)
+        ints = hip.cache.ints()
+        assert ints["cur_slot"].tolist() == bk.cur and ints["pend"].tolist() == bk.pend and ints["pos"].tolist() == bk.pos
+        assert ints["conv_head"].tolist() == bk.conv_head and ints["last_k"].tolist() == bk.last_k
+        assert ints["win_par"] == bk.win_par and ints["err_flag"] == bk.err == 1
+
+
 def test_first_conflict_bit_exact():
     rng = np.random.default_rng(16)
     for batch, k in [(1, 1), (7, 4), (300, 8), (1025, 16)]:
