@@ -55,6 +55,9 @@ def parse_args():
     ap.add_argument("--draft", action="store_true",
                     help="the draft side: a round is fed by k single-token calls (the first one replays the tokens accepted "
                          "last round), one commit per round; implies the general entry point")
+    ap.add_argument("--ceiling", action="store_true",
+                    help="measure what the memory system gives plain streams (read, write, copy; three footprints, three piece "
+                         "sizes, persistent grids) and the floor of a launch, and print the table as JSON")
     ap.add_argument("--prefill", type=int, default=0, metavar="L",
                     help="measure the chunked prefill instead: a step = one call over L prompt tokens of every sequence")
     ap.add_argument("--prefill-io", choices=["f32", "bf16"], default=None,
@@ -103,6 +106,25 @@ def round_bytes(wl, pend, k, fused, gate=False, calls=1):
         return verify_bytes(wl, pend, k, True, gate, calls)
     conv = len(pend) * (k * wl.conv_channels * 3 + 3 * wl.conv_channels + 5 * wl.conv_channels) * e
     return verify_bytes(wl, pend, k, False) + conv
+
+
+def step_plan(wl, accepted_rounds, k, n_inst, warmup, steps, fused, gate=False, calls=1):
+    """Which steps are primed, warmed up and timed, and what they move.  Step s works on cache s % n_inst in round
+    s // n_inst (the workload's rounds, cyclically).  Whatever `warmup` is, three untimed rounds through every cache come
+    first, so that the pending counts - and with them the replay work and the h_j stores - have the workload's mix when
+    the timed region starts: round 0 on fresh caches has nothing pending and is 22 % lighter than a steady-state round.
+    Returns the step ranges, the mean algorithmic bytes of a timed step, and the workload's own mean over its rounds in
+    the steady state (every round but the first)."""
+    n_rounds = len(accepted_rounds)
+    prime = 3 * n_inst
+    first_timed = prime + warmup
+    rounds_run = max((first_timed + steps + n_inst - 1) // n_inst + 1, n_rounds)
+    sched = pend_after([accepted_rounds[i % n_rounds] for i in range(rounds_run)], [k] * rounds_run, hj_only=wl.snapshot_mode == "hj_only")
+    step_bytes = lambda s: round_bytes(wl, sched[s // n_inst], k, fused, gate=gate, calls=calls)
+    workload = sum(step_bytes(r * n_inst) for r in range(1, max(2, n_rounds))) / max(1, n_rounds - 1)
+    timed = sum(step_bytes(s) for s in range(first_timed, first_timed + steps)) / steps
+    return {"prime": prime, "first_timed": first_timed, "timed_bytes": timed, "workload_bytes": workload,
+            "slack": 0.02 if steps >= 20 else 0.08}     # a handful of steps sees one round's realised pending counts
 
 
 PEAK_MFMA_F32_TFLOPS = 157.3     # MI355X published dense fp32 matrix rate
@@ -218,6 +240,49 @@ def bench_prefill(args):
         "cpu_baseline": cpu}))
 
 
+def bench_ceiling():
+    """The ceilings the roofline figures are read against: ssmv_stream_probe in every direction, launches back to back in a
+    HIP graph (as the verify launches are timed), rotating over enough buffers that every launch finds its data in HBM."""
+    import torch
+
+    import paper_2408_15237_amd as ssmv
+    torch.cuda.set_device(0)
+    ssmv.load_library()
+    rows = []
+    for mib in (32, 96, 1024):
+        S = mib << 20
+        n_buf = max(2, (3 << 30) // (3 * S))
+        bufs = [torch.zeros(3 * S // 4, dtype=torch.float32, device="cuda") for _ in range(n_buf)]
+        for mode, traffic in (("read", 1), ("write", 1), ("r1w1", 2), ("r1w2", 3), ("empty", 0)):
+            for piece, grid in ((4, 0), (8, 0), (32, 0), (32, 1024), (32, 2048)):
+                if mode == "empty" and (piece != 32 or grid == 2048):
+                    continue
+                n = max(8, min(256, (64 << 30) // (S * max(1, traffic))))
+
+                def launch(i):
+                    p0 = bufs[i % n_buf].data_ptr()
+                    ssmv.ssmv_stream_probe(mode, p0, p0 + S, p0 + 2 * S, S, piece, grid)
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.stream(side):
+                    g.capture_begin()
+                    for i in range(n):
+                        launch(i)
+                    g.capture_end()
+                torch.cuda.current_stream().wait_stream(side)
+                g.replay()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(); g.replay(); e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / n
+                rows.append({"mode": mode, "source_mib": mib, "piece_kib": piece, "grid": grid or "one workgroup per piece",
+                             "us_per_launch": round(us, 2), "gbps": round(traffic * S / us / 1e3, 1)})
+        del bufs
+    print(json.dumps({"ceiling": rows, "peak_gbps": PEAK_HBM_GBPS}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -234,6 +299,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
+    if args.ceiling:
+        bench_ceiling()
+        return
     if args.prefill > 0:
         bench_prefill(args)
         return
@@ -339,7 +407,7 @@ def main():
             ssmv.ssm_commit_rollback(dims, c, r["acc"])
 
     def finish(s_end):
-        """Commit the layers of a round that the timed region cut short (fused path only)."""
+        """Commit the layers of a round that the timed region cut short (fused path only; after the timed region)."""
         done = s_end % n_inst
         if fused and done:
             part = (ssmv.ssmv_cache * done)(*[c.c for c in caches[:done]])
@@ -347,16 +415,8 @@ def main():
 
     K = args.steps if args.steps > 0 else n_inst * n_rounds
     W = args.warmup if args.warmup >= 0 else max(3, n_inst)
-    # Whatever --warmup is: three untimed rounds through every cache first, so that the pending counts (and with them
-    # the replay work and the h_j stores) have the workload's mix when the timed region starts.  Round 0 on fresh caches
-    # has nothing pending and is 22 % lighter than a steady-state round.
-    PRIME = 3 * n_inst
-    rounds_run = (PRIME + W + K + n_inst - 1) // n_inst + 1
-    pend_sched = pend_after([data.rounds[i % n_rounds].accepted for i in range(rounds_run)], [k] * rounds_run,
-                            hj_only=wl.snapshot_mode == "hj_only")
-    step_bytes = lambda s: round_bytes(wl, pend_sched[s // n_inst], k, fused, gate=args.block, calls=k if args.draft else 1)
-    # the workload's own figure: mean over its rounds in the steady state (every round but the first)
-    workload_bytes = sum(step_bytes(r * n_inst) for r in range(1, max(2, n_rounds))) / max(1, n_rounds - 1)
+    plan = step_plan(wl, [r.accepted for r in data.rounds], k, n_inst, W, K, fused, gate=args.block, calls=k if args.draft else 1)
+    PRIME, workload_bytes = plan["prime"], plan["workload_bytes"]
 
     result = {}
     for s in range(PRIME):
@@ -373,7 +433,6 @@ def main():
             ev0.record()
             for s in range(W, W + K):
                 step(s)
-            finish(W + K)
             ev1.record()
             torch.cuda.synchronize()
         else:
@@ -385,7 +444,6 @@ def main():
                 graph.capture_begin()
                 for s in range(W, W + K):
                     step(s)
-                finish(W + K)
                 graph.capture_end()
             torch.cuda.current_stream().wait_stream(side)
             torch.cuda.synchronize()
@@ -394,13 +452,13 @@ def main():
             ev1.record()
             torch.cuda.synchronize()
         total_ms = ev0.elapsed_time(ev1)
+        finish(W + K)                                    # tidy up: the timed steps hold their share of commits, one per n_inst steps
         for c in caches:
             ssmv.ssmv_check(c.c)
         # algorithmic bytes of exactly the timed steps; they must be the workload's mix
-        tot_bytes = sum(step_bytes(s) for s in range(W, W + K))
-        timed_bytes = tot_bytes / K
-        slack = 0.02 if K >= 20 else 0.08              # a handful of steps sees one round's realised pending counts
-        if abs(timed_bytes / workload_bytes - 1.0) > slack:
+        timed_bytes = plan["timed_bytes"]
+        tot_bytes = timed_bytes * K
+        if abs(timed_bytes / workload_bytes - 1.0) > plan["slack"]:
             print("bench.py: the timed steps move %.1f MB each, the workload %.1f MB: not the workload's launch mix"
                   % (timed_bytes / 1e6, workload_bytes / 1e6), file=sys.stderr)
             sys.exit(3)

@@ -316,6 +316,15 @@ int ssmv_set_tuning(int32_t rows_per_lane, int32_t waves_per_group);
  * pattern).  n_bytes must be a multiple of 16. */
 int ssmv_copy_probe(const void *src, void *dst0, void *dst1, size_t n_bytes, void *hip_stream);
 
+/* Bandwidth probe for the ceiling the measurements are held against: one launch streams n_bytes in the given direction,
+ * non-temporal like the state traffic of the verify kernel.  READ reads src (dst0 must be a valid pointer, it is not
+ * written); WRITE writes dst0; R1W1 copies src to dst0; R1W2 to dst0 and dst1; EMPTY launches the same grid and does
+ * nothing (the cost of a launch).  A workgroup takes contiguous pieces of piece_kib in {4, 8, 32} KiB; grid = 0 launches
+ * one workgroup per piece, grid > 0 that many workgroups looping over the pieces.  n_bytes: a multiple of the piece. */
+enum { SSMV_PROBE_READ = 0, SSMV_PROBE_WRITE = 1, SSMV_PROBE_R1W1 = 2, SSMV_PROBE_R1W2 = 3, SSMV_PROBE_EMPTY = 4 };
+int ssmv_stream_probe(int32_t mode, const void *src, void *dst0, void *dst1, size_t n_bytes, int32_t piece_kib, int32_t grid,
+                      void *hip_stream);
+
 const char *ssmv_last_error(void);
 const char *ssmv_version(void);
 

@@ -5,7 +5,7 @@ The product is the C-ABI library ``libssmv.so`` (hand-written HIP for gfx950, de
 """
 from .binding import (  # noqa: F401
     SsmvError, ssmv_dims, ssmv_cache, ssmv_step_args, LayerCache, make_dims, load_library, LIB_PATH, EXPORTS,
-    ssmv_engine_of, ssmv_cache_sizes, ssmv_cache_reset, conv1d_state_update, ssm_verify_multistep, ssm_conv_verify_multistep, ssm_commit_rollback,
+    ssmv_engine_of, ssmv_stream_probe, ssmv_cache_sizes, ssmv_cache_reset, conv1d_state_update, ssm_verify_multistep, ssm_conv_verify_multistep, ssm_commit_rollback,
     ssm_commit_rollback_multi, ssm_block_multistep, ssmv_materialize_block, ssm_prefill_chunked, ssm_prefill_block, ssmv_prefill_args,
     ssmv_materialize, ssmv_first_conflict, ssmv_gated_rmsnorm, ssmv_check, ssmv_set_tuning, ssmv_copy_probe, ssmv_version,
     SSMV_OK, SSMV_EINVAL, SSMV_EUNSUPPORTED, SSMV_EALIGN, SSMV_ESEQUENCE, SSMV_EHIP,

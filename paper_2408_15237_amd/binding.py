@@ -34,7 +34,7 @@ ENGINE_CODES = {"auto": SSMV_ENGINE_AUTO, "vector": SSMV_ENGINE_VECTOR}
 EXPORTS = [
     "ssmv_cache_sizes", "ssmv_cache_reset", "conv1d_state_update", "ssm_verify_multistep",
     "ssm_conv_verify_multistep", "ssm_block_multistep", "ssmv_materialize_block", "ssm_prefill_chunked", "ssm_prefill_block", "ssm_commit_rollback", "ssm_commit_rollback_multi", "ssmv_materialize", "ssmv_first_conflict", "ssmv_gated_rmsnorm", "ssmv_check",
-    "ssmv_set_tuning", "ssmv_copy_probe", "ssmv_engine_of", "ssmv_last_error", "ssmv_version",
+    "ssmv_set_tuning", "ssmv_copy_probe", "ssmv_stream_probe", "ssmv_engine_of", "ssmv_last_error", "ssmv_version",
 ]
 
 
@@ -87,12 +87,13 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
-        if not build_if_missing:
-            raise SsmvError(SSMV_EHIP, "libssmv.so is not built (%s)" % LIB_PATH)
+    path = os.environ.get("SSMV_LIBRARY") or LIB_PATH     # another build of the same library (a sanitizer or profiling build)
+    if not os.path.exists(path):
+        if not build_if_missing or path != LIB_PATH:
+            raise SsmvError(SSMV_EHIP, "libssmv.so is not built (%s)" % path)
         from .build import build
         build()
-    lib = ctypes.CDLL(LIB_PATH)
+    lib = ctypes.CDLL(path)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     dp, cp = ctypes.POINTER(ssmv_dims), ctypes.POINTER(ssmv_cache)
     lib.ssmv_cache_sizes.argtypes = [dp, ctypes.POINTER(sz)]
@@ -113,6 +114,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.ssmv_check.argtypes = [cp, vp]
     lib.ssmv_set_tuning.argtypes = [i32, i32]
     lib.ssmv_copy_probe.argtypes = [vp, vp, vp, sz, vp]
+    lib.ssmv_stream_probe.argtypes = [i32, vp, vp, vp, sz, i32, i32, vp]
     for name in EXPORTS[:-2]:
         getattr(lib, name).restype = ctypes.c_int
     lib.ssmv_last_error.restype = ctypes.c_char_p
@@ -250,6 +252,14 @@ def ssmv_set_tuning(rows_per_lane: int = 0, waves_per_group: int = 0) -> None:
 
 def ssmv_copy_probe(src, dst0, dst1, n_bytes: int, stream=None) -> None:
     _ck(load_library().ssmv_copy_probe(_ptr(src), _ptr(dst0), _ptr(dst1), n_bytes, _stream(stream)))
+
+
+PROBE_MODES = {"read": 0, "write": 1, "r1w1": 2, "r1w2": 3, "empty": 4}
+
+
+def ssmv_stream_probe(mode, src, dst0, dst1, n_bytes: int, piece_kib: int = 32, grid: int = 0, stream=None) -> None:
+    _ck(load_library().ssmv_stream_probe(PROBE_MODES[mode] if isinstance(mode, str) else mode, _ptr(src), _ptr(dst0), _ptr(dst1),
+                                         n_bytes, piece_kib, grid, _stream(stream)))
 
 
 def ssmv_version() -> str:

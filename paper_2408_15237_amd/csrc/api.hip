@@ -183,8 +183,9 @@ void fill_verify(VerifyParams &p, const ssmv_dims *d, const ssmv_cache *c)
 #ifdef SSMV_TRACE
 // Profiling builds (-DSSMV_TRACE) only, no part of the library's interface: a device buffer of 8 wall-clock stamps per
 // workgroup of the matrix-core verify kernel.
-namespace ssmv { int set_trace_mfma(long long *buf); }
+namespace ssmv { int set_trace_mfma(long long *buf); int set_trace_prefill(long long *buf); }
 extern "C" int ssmv_debug_set_trace(long long *buf) { return ssmv::set_trace_mfma(buf); }
+extern "C" int ssmv_debug_set_trace_prefill(long long *buf) { return ssmv::set_trace_prefill(buf); }
 #endif
 
 extern "C" {
@@ -514,6 +515,22 @@ int ssmv_gated_rmsnorm(const void *y, const void *z, const float *weight, int32_
     if ((rc = check_ptr(out, "out")) != SSMV_OK) return rc;
     const int hc = launch_gated_rmsnorm(y, z, weight, rows, channels, group_size, eps, io_dtype, out, (hipStream_t)hip_stream);
     return hc == 0 ? SSMV_OK : hip_fail(hc, "ssmv_gated_rmsnorm");
+}
+
+int ssmv_stream_probe(int32_t mode, const void *src, void *dst0, void *dst1, size_t n_bytes, int32_t piece_kib, int32_t grid,
+                      void *hip_stream)
+{
+    int rc;
+    if (mode < SSMV_PROBE_READ || mode > SSMV_PROBE_EMPTY) return fail(SSMV_EINVAL, "mode %d unknown", mode);
+    if (piece_kib != 4 && piece_kib != 8 && piece_kib != 32) return fail(SSMV_EINVAL, "piece_kib %d not in {4, 8, 32}", piece_kib);
+    if (grid < 0) return fail(SSMV_EINVAL, "grid %d < 0", grid);
+    if (n_bytes == 0 || n_bytes % ((size_t)piece_kib * 1024) != 0)
+        return fail(SSMV_EINVAL, "n_bytes %zu must be a positive multiple of the piece size", n_bytes);
+    if (mode != SSMV_PROBE_WRITE && mode != SSMV_PROBE_EMPTY && (rc = check_ptr(src, "src")) != SSMV_OK) return rc;
+    if ((rc = check_ptr(dst0, "dst0")) != SSMV_OK) return rc;
+    if (mode == SSMV_PROBE_R1W2 && (rc = check_ptr(dst1, "dst1")) != SSMV_OK) return rc;
+    const int hc = launch_stream_probe(mode, src, dst0, dst1, n_bytes, piece_kib, grid, (hipStream_t)hip_stream);
+    return hc == 0 ? SSMV_OK : hip_fail(hc, "ssmv_stream_probe");
 }
 
 int ssmv_copy_probe(const void *src, void *dst0, void *dst1, size_t n_bytes, void *hip_stream)

@@ -302,6 +302,61 @@ int launch_gated_rmsnorm(const void *y, const void *z, const float *weight, int 
     return (int)hipGetLastError();
 }
 
+// ---- bandwidth probe: what the memory system gives a plain stream of a given direction and shape --------------------------
+// MODE 0 read only, 1 write only, 2 read 1 / write 1, 3 read 1 / write 2, 4 nothing (the floor of a launch).  A workgroup of
+// 256 threads takes contiguous pieces of U x 4 KiB (a wave instruction = 1 KiB), non-temporal as the verify kernel's state.
+template <int MODE, int U>
+__global__ __launch_bounds__(256) void stream_probe_kernel(const copy_v4f *__restrict__ src, copy_v4f *__restrict__ dst0,
+                                                           copy_v4f *__restrict__ dst1, size_t n16)
+{
+    if (MODE == 4) return;
+    const size_t tiles = n16 / (U * 256);
+    for (size_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        const size_t base = tile * (U * 256) + threadIdx.x;
+        copy_v4f v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = MODE == 1 ? copy_v4f{(float)tile, 1.f, 2.f, 3.f} : __builtin_nontemporal_load(src + base + u * 256);
+        if (MODE == 0) {
+            float a = 0.f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) a += v[u].x + v[u].y + v[u].z + v[u].w;
+            if (a == 123.456f) dst0[base] = v[0];            // keeps the loads alive; practically never taken
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                __builtin_nontemporal_store(v[u], dst0 + base + u * 256);
+                if (MODE == 3) __builtin_nontemporal_store(v[u], dst1 + base + u * 256);
+            }
+        }
+    }
+}
+
+template <int MODE>
+static void launch_probe_u(int u, unsigned grid, const copy_v4f *s, copy_v4f *d0, copy_v4f *d1, size_t n16, hipStream_t stream)
+{
+    if (u == 1) hipLaunchKernelGGL((stream_probe_kernel<MODE, 1>), dim3(grid), dim3(256), 0, stream, s, d0, d1, n16);
+    else if (u == 2) hipLaunchKernelGGL((stream_probe_kernel<MODE, 2>), dim3(grid), dim3(256), 0, stream, s, d0, d1, n16);
+    else hipLaunchKernelGGL((stream_probe_kernel<MODE, 8>), dim3(grid), dim3(256), 0, stream, s, d0, d1, n16);
+}
+
+int launch_stream_probe(int mode, const void *src, void *dst0, void *dst1, size_t n_bytes, int piece_kib, int grid, hipStream_t stream)
+{
+    const size_t n16 = n_bytes / 16;
+    const int u = piece_kib / 4;
+    const size_t tiles = n16 / ((size_t)u * 256);
+    const unsigned g = grid > 0 ? (unsigned)grid : (unsigned)(tiles > 0x7fffffff ? 0x7fffffff : tiles);
+    const copy_v4f *s = reinterpret_cast<const copy_v4f *>(src);
+    copy_v4f *d0 = reinterpret_cast<copy_v4f *>(dst0), *d1 = reinterpret_cast<copy_v4f *>(dst1);
+    switch (mode) {
+        case 0: launch_probe_u<0>(u, g, s, d0, d1, n16, stream); break;
+        case 1: launch_probe_u<1>(u, g, s, d0, d1, n16, stream); break;
+        case 2: launch_probe_u<2>(u, g, s, d0, d1, n16, stream); break;
+        case 3: launch_probe_u<3>(u, g, s, d0, d1, n16, stream); break;
+        default: launch_probe_u<4>(u, g, s, d0, d1, n16, stream); break;
+    }
+    return (int)hipGetLastError();
+}
+
 int launch_copy_probe(const void *src, void *dst0, void *dst1, size_t n_bytes, hipStream_t stream)
 {
     const size_t n16 = n_bytes / 16;

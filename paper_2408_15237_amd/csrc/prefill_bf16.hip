@@ -126,6 +126,11 @@ __device__ __forceinline__ float prefix32(float v)
 
 __device__ __forceinline__ int swap23(int i) { return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1); }
 
+#ifdef SSMV_TRACE
+// Profiling builds only: per workgroup, the shader-clock and the 100 MHz wall-clock ticks the kernel took.
+__device__ long long *pf_trace_buf_ = nullptr;
+#endif
+
 }  // namespace
 
 // Two waves per SIMD (256 registers each, and then the compiler keeps the accumulators in ordinary registers: no copies
@@ -157,6 +162,9 @@ void prefill_bf16_kernel(const PrefillParams p)
     uint32_t *sCar = reinterpret_cast<uint32_t *>(lds + Ld::oCar);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+#ifdef SSMV_TRACE
+    const long long tr_c0 = clock64(), tr_w0 = wall_clock64();
+#endif
     const int li = lane & 31, lh = lane >> 5;           // MFMA: row/column index and k half of this lane
     const int lperm = swap23(li);
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
@@ -536,6 +544,12 @@ void prefill_bf16_kernel(const PrefillParams p)
         for (int tg = (L - (W - 1) > 0 ? L - (W - 1) : 0); tg < L; ++tg)
             Vec::store_raw1(p.ring, ((size_t)b * p.ring_len + ((conv_head + 1 + tg) & mask)) * HP + ch, raw_bits(tg));
     }
+#ifdef SSMV_TRACE
+    if (pf_trace_buf_ && tid == 0) {
+        pf_trace_buf_[2 * blockIdx.x] = clock64() - tr_c0;
+        pf_trace_buf_[2 * blockIdx.x + 1] = wall_clock64() - tr_w0;
+    }
+#endif
 }
 
 template <int P, int N>
@@ -559,6 +573,10 @@ static int launch_p(const PrefillParams &p, hipStream_t stream)
         default: return (int)hipErrorInvalidConfiguration;
     }
 }
+
+#ifdef SSMV_TRACE
+int set_trace_prefill(long long *buf) { return (int)hipMemcpyToSymbol(HIP_SYMBOL(pf_trace_buf_), &buf, sizeof(buf)); }
+#endif
 
 // the main kernel only; the caller appends the bookkeeping launch
 int launch_prefill_bf16(const PrefillParams &p, hipStream_t stream)

@@ -148,6 +148,7 @@ int launch_reset(const ResetParams &p, hipStream_t stream);
 int launch_first_conflict(const int32_t *draft, const int32_t *target, int batch, int k, int32_t *accepted,
                           hipStream_t stream);
 int launch_copy_probe(const void *src, void *dst0, void *dst1, size_t n_bytes, hipStream_t stream);
+int launch_stream_probe(int mode, const void *src, void *dst0, void *dst1, size_t n_bytes, int piece_kib, int grid, hipStream_t stream);
 int launch_gated_rmsnorm(const void *y, const void *z, const float *weight, int rows, int channels, int group, float eps, int io,
                          void *out, hipStream_t stream);
 

@@ -53,6 +53,22 @@ def test_algorithmic_bytes_of_a_launch_by_hand():
     assert bench.round_bytes(wl, [0], k, fused=False) == bench.verify_bytes(wl, [0], k, fused=False) + conv_launch
 
 
+@pytest.mark.parametrize("steps,warmup", [(20, 5), (21 * 64, 21), (1, 0), (100, 3)])
+def test_timed_steps_carry_the_workloads_launch_mix(steps, warmup):
+    """Whatever the step counts (the first pair is what the harness passes), the timed steps come after three
+    priming rounds through every cache and move the workload's steady-state bytes: 94-95 MB per step on cfg3, not the
+    73.5 MB of a round on fresh caches."""
+    from workload import generate
+    wl = CONFIGS["cfg3"]
+    acc = [r.accepted for r in generate(wl).rounds]
+    plan = bench.step_plan(wl, acc, wl.k, 21, warmup, steps, fused=True)
+    assert plan["prime"] == 63 and plan["first_timed"] == 63 + warmup
+    assert 92e6 < plan["workload_bytes"] < 96e6
+    assert abs(plan["timed_bytes"] / plan["workload_bytes"] - 1.0) <= plan["slack"]
+    fresh = bench.round_bytes(wl, np.zeros(wl.batch, dtype=np.int64), wl.k, True)
+    assert fresh < 0.8 * plan["workload_bytes"]
+
+
 def test_more_than_one_gpu_is_refused_with_a_message():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
