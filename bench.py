@@ -53,8 +53,11 @@ def parse_args():
     ap.add_argument("--block", action="store_true",
                     help="the launch as a whole Mamba block's recurrence: dt = softplus(raw + bias) ahead of it, SiLU gate behind it")
     ap.add_argument("--draft", action="store_true",
-                    help="the draft side: a round is fed by k single-token calls (the first one replays the tokens accepted "
-                         "last round), one commit per round; implies the general entry point")
+                    help="the draft side: a round is fed by k single-token calls, one commit per round (implies the general "
+                         "entry point).  On the matrix-core engine every call recomputes from the live slot and only the "
+                         "last one stores the snapshots (replay_round); else, or with --draft-carry, the calls carry the "
+                         "state through the h_k slot")
+    ap.add_argument("--draft-carry", action="store_true", help="with --draft: carry the state through the h_k slot on every call")
     ap.add_argument("--ceiling", action="store_true",
                     help="measure what the memory system gives plain streams (read, write, copy; three footprints, three piece "
                          "sizes, persistent grids) and the floor of a launch, and print the table as JSON")
@@ -76,7 +79,7 @@ def pend_after(accepted_rounds, k_rounds, hj_only=False):
     return out
 
 
-def verify_bytes(wl, pend, k, fused, gate=False, calls=1):
+def verify_bytes(wl, pend, k, fused, gate=False, calls=1, replay=False):
     """Algorithmic HBM bytes of one verify launch: state read once, h_k written, h_j written where
     tokens were pending, token inputs read, y and the stash written, pending tokens re-read; with the
     conv roll fused in: the raw inputs instead of xc, the ring append, 3 history rows, weights and bias."""
@@ -94,21 +97,24 @@ def verify_bytes(wl, pend, k, fused, gate=False, calls=1):
             total += (k * Cx + calls * (3 * Cx + 5 * Cx)) * e   # ring append; per call: ring history, conv weights + bias
         if gate:
             total += k * Cx * e                     # z in
-        total += (calls - 1) * 2 * S                # every later call of a round: state in, state out
+        if replay:                                  # every later call: state in; the pending and the round's earlier tokens again
+            total += (calls - 1) * S + ((calls - 1) * int(pd) + (calls - 1) * calls // 2) * (Cx + H + GN) * e
+        else:
+            total += (calls - 1) * 2 * S            # every later call of a round: state in, state out
     return int(total)
 
 
-def round_bytes(wl, pend, k, fused, gate=False, calls=1):
+def round_bytes(wl, pend, k, fused, gate=False, calls=1, replay=False):
     """Whole round.  Split path: the verify launch plus the conv launch (x_raw in, ring append, xc out, 3
     history rows and weights in).  Fused path: the one launch."""
     e = 2 if wl.io == "bf16" else 4
     if fused:
-        return verify_bytes(wl, pend, k, True, gate, calls)
+        return verify_bytes(wl, pend, k, True, gate, calls, replay)
     conv = len(pend) * (k * wl.conv_channels * 3 + 3 * wl.conv_channels + 5 * wl.conv_channels) * e
     return verify_bytes(wl, pend, k, False) + conv
 
 
-def step_plan(wl, accepted_rounds, k, n_inst, warmup, steps, fused, gate=False, calls=1):
+def step_plan(wl, accepted_rounds, k, n_inst, warmup, steps, fused, gate=False, calls=1, replay=False):
     """Which steps are primed, warmed up and timed, and what they move.  Step s works on cache s % n_inst in round
     s // n_inst (the workload's rounds, cyclically).  Whatever `warmup` is, three untimed rounds through every cache come
     first, so that the pending counts - and with them the replay work and the h_j stores - have the workload's mix when
@@ -120,7 +126,7 @@ def step_plan(wl, accepted_rounds, k, n_inst, warmup, steps, fused, gate=False, 
     first_timed = prime + warmup
     rounds_run = max((first_timed + steps + n_inst - 1) // n_inst + 1, n_rounds)
     sched = pend_after([accepted_rounds[i % n_rounds] for i in range(rounds_run)], [k] * rounds_run, hj_only=wl.snapshot_mode == "hj_only")
-    step_bytes = lambda s: round_bytes(wl, sched[s // n_inst], k, fused, gate=gate, calls=calls)
+    step_bytes = lambda s: round_bytes(wl, sched[s // n_inst], k, fused, gate=gate, calls=calls, replay=replay)
     workload = sum(step_bytes(r * n_inst) for r in range(1, max(2, n_rounds))) / max(1, n_rounds - 1)
     timed = sum(step_bytes(s) for s in range(first_timed, first_timed + steps)) / steps
     return {"prime": prime, "first_timed": first_timed, "timed_bytes": timed, "workload_bytes": workload,
@@ -349,8 +355,9 @@ def main():
     if general and not fused:
         print("bench.py: --block/--draft use the fused launch; not with --split/--naive", file=sys.stderr)
         sys.exit(2)
-    if args.draft and args.single_snapshot:
-        print("bench.py: a round fed by several calls needs the h_k slot; not with --single-snapshot", file=sys.stderr)
+    replay = args.draft and matrix_engine and not args.draft_carry and args.rows == 0 and args.waves == 0
+    if args.draft and args.single_snapshot and not replay:
+        print("bench.py: a round whose calls carry the state needs the h_k slot; not with --single-snapshot", file=sys.stderr)
         sys.exit(2)
     blk = {}
     if args.block:
@@ -388,7 +395,7 @@ def main():
         elif args.draft:
             for t in range(k):
                 ssmv.ssm_block_multistep(dims, c, x_raw=r["x1"][t], conv_wgt=conv_w, conv_bias=conv_b, dt=r["dt1"][t], Bm=r["B1"][t],
-                                         Cm=r["C1"][t], A=A, D=D, k=1, tok0=t, y_out=y1_buf,
+                                         Cm=r["C1"][t], A=A, D=D, k=1, tok0=t, y_out=y1_buf, replay_round=replay, last_call=replay and t == k - 1,
                                          z=r["z1"][t] if args.block else None, **blk)
             if i == n_inst - 1:
                 ssmv.ssm_commit_rollback_multi(dims, all_caches, r["acc"])
@@ -415,7 +422,7 @@ def main():
 
     K = args.steps if args.steps > 0 else n_inst * n_rounds
     W = args.warmup if args.warmup >= 0 else max(3, n_inst)
-    plan = step_plan(wl, [r.accepted for r in data.rounds], k, n_inst, W, K, fused, gate=args.block, calls=k if args.draft else 1)
+    plan = step_plan(wl, [r.accepted for r in data.rounds], k, n_inst, W, K, fused, gate=args.block, calls=k if args.draft else 1, replay=replay)
     PRIME, workload_bytes = plan["prime"], plan["workload_bytes"]
 
     result = {}
@@ -480,9 +487,10 @@ def main():
     r0 = rounds[0]
 
     def dominant(c):
-        if args.draft:      # a later call of a round: one token, state read and written in place
+        if args.draft:      # a later call of a round: one token; state read and written in place, or (replayed round) read only
             ssmv.ssm_block_multistep(dims, c, x_raw=r0["x1"][1], conv_wgt=conv_w, conv_bias=conv_b, dt=r0["dt1"][1], Bm=r0["B1"][1],
-                                     Cm=r0["C1"][1], A=A, D=D, k=1, tok0=1, y_out=y1_buf, z=r0["z1"][1] if args.block else None, **blk)
+                                     Cm=r0["C1"][1], A=A, D=D, k=1, tok0=1, y_out=y1_buf, z=r0["z1"][1] if args.block else None,
+                                     replay_round=replay, **blk)
         elif general:
             ssmv.ssm_block_multistep(dims, c, x_raw=r0["x"], conv_wgt=conv_w, conv_bias=conv_b, dt=r0["dt"], Bm=r0["B"], Cm=r0["C"],
                                      A=A, D=D, k=k, y_out=y_buf, z=r0["z"], **blk)
@@ -497,8 +505,11 @@ def main():
     if args.draft:
         e_io = 2 if wl.io == "bf16" else 4
         Cx_, H_, GN_ = wl.conv_channels, wl.nheads, wl.ngroups * wl.dstate
-        per_seq = 2 * wl.state_elems * 4 + ((Cx_ + H_ + 2 * GN_) + Cx_ + (Cx_ + H_ + GN_) + Cx_ + 8 * Cx_ + (Cx_ if args.block else 0)) * e_io
-        kbytes = per_seq * wl.batch * n_meas
+        per_seq = ((Cx_ + H_ + 2 * GN_) + Cx_ + (Cx_ + H_ + GN_) + Cx_ + 8 * Cx_ + (Cx_ if args.block else 0)) * e_io
+        if replay:
+            kbytes = sum(int(np.sum(wl.state_elems * 4 + per_seq + (pend_now[i % n_inst] + 1) * (Cx_ + H_ + GN_) * e_io)) for i in range(n_meas))
+        else:
+            kbytes = (2 * wl.state_elems * 4 + per_seq) * wl.batch * n_meas
     else:
         kbytes = sum(verify_bytes(wl, pend_now[i % n_inst], k, fused, gate=args.block) for i in range(n_meas))
     side2 = torch.cuda.Stream()
@@ -598,7 +609,8 @@ def main():
                    "batch": wl.batch, "k": k, "rounds": n_rounds, "instances": n_inst,
                    "launch": "hip-graph" if not args.no_graph else "eager",
                    "snapshots": "h_j only (single-snapshot variant)" if wl.snapshot_mode == "hj_only" else "h_j and h_k (Algorithm 2)",
-                   "path": ("draft side: k single-token calls per layer-round (first one replays), one commit launch per round" if args.draft else
+                   "path": ("draft side: k single-token calls per layer-round, every call recomputing from the live slot, snapshots stored by the last; one commit launch per round" if replay else
+                            "draft side: k single-token calls per layer-round carrying the state through the h_k slot (first one replays), one commit launch per round" if args.draft else
                             "fused conv+verify launch per layer, one commit launch per round over all caches") +
                            (", softplus(dt+bias) and SiLU gate fused" if args.block else "") if fused
                            else ("naive: snapshot copy + k single-token (conv, verify, commit) rounds per layer" if args.naive

@@ -186,6 +186,15 @@ int ssm_conv_verify_multistep(const ssmv_dims *dims, const ssmv_cache *cache, co
  *     (the rounding order inside a launch depends on how many tokens it holds), so ssm_commit_rollback
  *     applies unchanged.
  *     tok0 + k <= kmax; not with SSMV_SNAP_HJ_ONLY (SSMV_EUNSUPPORTED); a later call is NOT idempotent.
+ *   - replay_round = 1 (matrix-core engine only, SSMV_EUNSUPPORTED otherwise): the other way to feed a round by
+ *     several calls, the one Section 4.3 describes for the draft model - recompute from the cache instead of
+ *     carrying the state through memory.  EVERY call of the round starts from the live slot, replays the pending
+ *     tokens and the tok0 tokens the round has been fed so far (their conv outputs, dt and B sit in the round's
+ *     half of the window), then takes its k tokens; it stores no state unless last_call = 1, which stores h_j and
+ *     h_k as one call with all tok0 + k tokens would.  A call then reads the state once and writes it only at the
+ *     end of the round (the default above reads and writes it on every call).  Calls are idempotent.  All calls
+ *     of a round must agree on replay_round, and the round must end with a last_call = 1 before its commit.
+ *     Works with SSMV_SNAP_HJ_ONLY too.
  *   - k_seq (device int32 [batch], or NULL): ragged draft counts.  Sequence b takes only the first
  *     kb = clamp(k_seq[b], 1, k) of the k tokens given (at least one: last_k = 0 means "no verify"
  *     to the commit; a sequence with nothing to verify passes one token and accepts none) (the arrays keep the stride k): its outputs
@@ -210,6 +219,8 @@ typedef struct ssmv_step_args {
     int32_t k;
     int32_t tok0;
     int32_t dt_softplus;
+    int32_t replay_round;   /* 0 | 1 */
+    int32_t last_call;      /* with replay_round = 1: 1 on the round's last call */
 } ssmv_step_args;
 int ssm_block_multistep(const ssmv_dims *dims, const ssmv_cache *cache, const ssmv_step_args *args,
                         void *hip_stream);

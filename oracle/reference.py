@@ -291,15 +291,20 @@ class LazyMirror:
             g = snap[pd]
         return g[0]
 
-    def verify(self, x_raw, dt, Bm, Cm, tok0: int = 0):
+    def verify(self, x_raw, dt, Bm, Cm, tok0: int = 0, replay_round: bool = False, last_call: bool = False):
         """tok0 > 0: a later call of a round that several calls feed (the draft side of Section 4.3 produces its
-        tokens one call at a time).  It continues from the state the earlier calls left in the h_k slot, advances that
-        slot in place, replays nothing, and appends its tokens to the round's stash and ring behind the tok0 earlier ones."""
+        tokens one call at a time).  By default it continues from the state the earlier calls left in the h_k slot,
+        advances that slot in place, replays nothing, and appends its tokens to the round's stash and ring behind the
+        tok0 earlier ones.  With replay_round every call of the round instead starts from the live slot and recomputes:
+        the pending tokens, then the round's tok0 earlier tokens out of the round's stash, then its own; no slot is
+        written before the call that says last_call, which writes h_j and h_k as one call with all tokens would."""
         x_raw, dt, Bm, Cm = map(_c, (x_raw, dt, Bm, Cm))
+        assert not last_call or replay_round
         bk, W, R = self.bk, self.W, self.R
         k = x_raw.shape[1]
         assert 1 <= k and 0 <= tok0 and tok0 + k <= self.kmax
-        assert tok0 == 0 or not self.hj_only
+        assert tok0 == 0 or replay_round or not self.hj_only
+        npar_ = bk.win_par ^ 1
         raw = np.empty((self.batch, W - 1 + k, self.Cx))
         for b in range(self.batch):
             head = (bk.conv_head[b] + tok0) & (R - 1)  # newest raw input fed so far
@@ -311,16 +316,22 @@ class LazyMirror:
         y = np.empty((self.batch, k, self.Cx))
         for b in range(self.batch):
             cur = bk.cur[b]
-            if tok0 == 0:
+            stores = not replay_round or last_call
+            if tok0 == 0 or replay_round:
                 g = self._replayed(b)
-                if bk.pend[b] > 0:
+                if bk.pend[b] > 0 and stores:
                     self.slots[(cur + 1) % 3, b] = g                 # snapshot h_j
+                if replay_round and tok0 > 0:                        # the round's earlier tokens, again, no outputs
+                    zeros_c = np.zeros((1, tok0, self.G, self.N))
+                    _, snap0 = scan_tokens(self.a_mode, g[None], self.win_xc[npar_, b:b + 1, :tok0], self.win_dt[npar_, b:b + 1, :tok0],
+                                           self.win_B[npar_, b:b + 1, :tok0], zeros_c, self.A, self.D)
+                    g = snap0[tok0, 0]
             else:
                 g = self.slots[(cur + 2) % 3, b]                     # where the earlier calls of the round stopped
             yb, snap = scan_tokens(self.a_mode, g[None], xc[b:b + 1], dt[b:b + 1], Bm[b:b + 1], Cm[b:b + 1],
                                    self.A, self.D)
             y[b] = yb[0]
-            if not self.hj_only:
+            if not self.hj_only and stores:
                 self.slots[(cur + 2) % 3, b] = snap[k, 0]            # snapshot h_k
         npar = bk.win_par ^ 1
         self.win_xc[npar, :, tok0:tok0 + k] = xc

@@ -41,7 +41,7 @@ EXPORTS = [
 class ssmv_step_args(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in (
         "x_raw", "xc", "conv_wgt", "conv_bias", "dt", "dt_bias", "Bm", "Cm", "z", "A", "D", "k_seq", "y_out")] + [
-        (n, ctypes.c_int32) for n in ("k", "tok0", "dt_softplus")]
+        (n, ctypes.c_int32) for n in ("k", "tok0", "dt_softplus", "replay_round", "last_call")]
 
 
 class ssmv_prefill_args(ctypes.Structure):
@@ -195,9 +195,10 @@ def ssm_conv_verify_multistep(dims, cache, x_raw, wgt, bias, dt, Bm, Cm, A, D, k
 
 
 def ssm_block_multistep(dims, cache, *, dt, Bm, Cm, A, D, k: int, y_out, x_raw=None, xc=None, conv_wgt=None, conv_bias=None,
-                        dt_bias=None, dt_softplus: bool = False, z=None, tok0: int = 0, k_seq=None, stream=None) -> None:
+                        dt_bias=None, dt_softplus: bool = False, z=None, tok0: int = 0, k_seq=None, replay_round: bool = False,
+                        last_call: bool = False, stream=None) -> None:
     a = ssmv_step_args(_ptr(x_raw), _ptr(xc), _ptr(conv_wgt), _ptr(conv_bias), _ptr(dt), _ptr(dt_bias), _ptr(Bm), _ptr(Cm),
-                       _ptr(z), _ptr(A), _ptr(D), _ptr(k_seq), _ptr(y_out), k, tok0, int(dt_softplus))
+                       _ptr(z), _ptr(A), _ptr(D), _ptr(k_seq), _ptr(y_out), k, tok0, int(dt_softplus), int(replay_round), int(last_call))
     _ck(load_library().ssm_block_multistep(ctypes.byref(dims), ctypes.byref(cache), ctypes.byref(a), _stream(stream)))
 
 

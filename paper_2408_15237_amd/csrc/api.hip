@@ -280,8 +280,14 @@ static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const ssmv_ste
     const int k = a->k;
     if ((rc = check_k(d, k)) != SSMV_OK) return rc;
     if (a->tok0 < 0 || a->tok0 + k > d->kmax) return fail(SSMV_EINVAL, "tok0 %d + k %d outside [0, kmax=%d]", a->tok0, k, d->kmax);
-    if (a->tok0 > 0 && d->snapshot_mode == SSMV_SNAP_HJ_ONLY)
-        return fail(SSMV_EUNSUPPORTED, "a round fed by several calls needs the h_k slot (not with SSMV_SNAP_HJ_ONLY)");
+    if ((a->replay_round != 0 && a->replay_round != 1) || (a->last_call != 0 && a->last_call != 1))
+        return fail(SSMV_EINVAL, "replay_round %d and last_call %d must be 0 or 1", a->replay_round, a->last_call);
+    if (a->last_call && !a->replay_round) return fail(SSMV_EINVAL, "last_call is a flag of replay_round = 1");
+    const bool replay = a->replay_round == 1;
+    if (replay && (!state_tiled(d) || g_tune_rows.load() != 0 || g_tune_waves.load() != 0))
+        return fail(SSMV_EUNSUPPORTED, "replay_round needs the matrix-core engine (see ssmv_engine_of) and no forced launch shape");
+    if (a->tok0 > 0 && !replay && d->snapshot_mode == SSMV_SNAP_HJ_ONLY)
+        return fail(SSMV_EUNSUPPORTED, "a round fed by several calls needs the h_k slot (not with SSMV_SNAP_HJ_ONLY) unless replay_round = 1");
     if (a->tok0 > 0 && a->k_seq)
         return fail(SSMV_EUNSUPPORTED, "ragged draft counts in a round fed by several calls (a sequence's window entries would not be contiguous)");
     if (a->dt_softplus != 0 && a->dt_softplus != 1) return fail(SSMV_EINVAL, "dt_softplus %d not in {0,1}", a->dt_softplus);
@@ -309,15 +315,17 @@ static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const ssmv_ste
     fill_verify(p, d, c);
     p.k = k;
     p.tok0 = a->tok0;
-    p.pend_mask = a->tok0 > 0 ? 0 : ~0;
-    p.src_add = a->tok0 > 0 ? 2 : 0;
+    p.pend_mask = (a->tok0 > 0 && !replay) ? 0 : ~0;
+    p.src_add = (a->tok0 > 0 && !replay) ? 2 : 0;
+    p.replay_tok = replay ? a->tok0 : 0;
+    p.store_state = (replay && !a->last_call) ? 0 : 1;
     p.dt_softplus = a->dt_softplus;
     p.dt_bias = a->dt_bias;
     p.z = a->z;
     p.k_seq = a->k_seq;
     p.pend_max = pend_max_of(d);
     p.write_hk = d->snapshot_mode != SSMV_SNAP_HJ_ONLY;
-    p.lds_tokens = (a->tok0 > 0 ? 0 : p.pend_max) + k;
+    p.lds_tokens = ((a->tok0 > 0 && !replay) ? 0 : p.pend_max) + p.replay_tok + k;
     p.xc = a->xc; p.dt = a->dt; p.Bm = a->Bm; p.Cm = a->Cm; p.A = a->A; p.D = a->D; p.y = a->y_out; p.h_out = nullptr;
     p.x_raw = a->x_raw; p.wgt = a->conv_wgt; p.bias = a->conv_bias;
     // tiled caches: the matrix-core kernel, unless a launch shape of the vector kernel was asked for explicitly

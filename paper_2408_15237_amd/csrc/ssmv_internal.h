@@ -23,6 +23,8 @@ struct VerifyParams {
     int tok0;            // tokens earlier calls have already fed to this round (0: first call)
     int pend_mask;       // tok0 > 0 ? 0 : ~0  (a later call replays nothing)
     int src_add;         // tok0 > 0 ? 2 : 0   (a later call continues in the h_k slot)
+    int replay_tok;      // tokens of this round that the call replays out of the round's own stash (0, or tok0)
+    int store_state;     // 0: a call of a replayed round that is not its last stores no snapshot
     int dt_softplus;     // 1: dt <- softplus(dt + dt_bias) before use
     const float *dt_bias;  // [nheads] or null
     const void *z;       // gate input [batch][k][channels] or null

@@ -127,7 +127,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const int par = p.win_par[0] & 1;
     int kb = k;
     if constexpr (EXTRA) if (p.k_seq) kb = min(max(p.k_seq[b], 1), k);
-    const int T = pd + kb;                               // <= 16: the host launches this kernel only if pend_max + k <= 16
+    // replayed round (Section 4.3, the draft model's recomputation): the pe tokens that earlier calls fed to this round are
+    // taken again out of the round's own half of the window, behind the pending ones and ahead of this call's
+    const int pe = EXTRA ? p.replay_tok : 0;
+    const int pq = pd + pe;                              // tokens that come out of the stash
+    const int T = pq + kb;                               // <= 16: the host launches this kernel only if pend_max + kmax <= 16
     // per-head parameters: read here, as scalar loads beside the bookkeeping (further down they would become vector loads
     // queued behind the state)
     const float A2 = p.A[hd] * 1.4426950408889634f, D_h = p.D[hd];
@@ -151,6 +155,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     auto half = [&](void *const (&w2)[2], int which) { return static_cast<uint16_t *>(which ? w2[1] : w2[0]); };
     const uint16_t *winB = half(p.win_B, par), *winX = half(p.win_xc, par), *winDt = half(p.win_dt, par);
     uint16_t *winB_out = half(p.win_B, par ^ 1), *winX_out = half(p.win_xc, par ^ 1), *winDt_out = half(p.win_dt, par ^ 1);
+    // token tt < pd: pending, half `par`, entry tt; pd <= tt < pq: fed earlier to this round, the other half, entry tt - pd
+    auto stashed = [&](const uint16_t *cur_half, const uint16_t *round_half, size_t o_win, int tt, int stride) {
+        return tt < pd ? cur_half + o_win + (size_t)tt * stride : round_half + o_win + (size_t)(tt - pd) * stride;
+    };
     const uint16_t *Bmp = static_cast<const uint16_t *>(p.Bm), *Cmp = static_cast<const uint16_t *>(p.Cm);
     const uint16_t *dtp = static_cast<const uint16_t *>(p.dt);
     const uint16_t *xin = static_cast<const uint16_t *>(CONV ? p.x_raw : p.xc);
@@ -177,7 +185,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
                 const int r = min(rfirst + it * RPI + (int)(l / CX), 2 + T);       // row of sXr
                 const int tt = r - 3;
                 const uint16_t *src = r < 3 ? ring + ring_b + (size_t)((conv_head - 2 + r) & ring_mask) * HP
-                                     : tt < pd ? winX + oX_win + (size_t)tt * HP : xin + oX_in + (size_t)(tt - pd) * HP;
+                                     : tt < pq ? stashed(winX, winX_out, oX_win, tt, HP) : xin + oX_in + (size_t)(tt - pq) * HP;
                 xk[it] = *reinterpret_cast<const u4v *>(src + 8 * (l % CX));
             }
         }
@@ -188,7 +196,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         for (int it = 0; it < BIT; ++it) {
             if (it * RPI < nrow) {
                 const int r = min(it * RPI + (int)(l / CB), nrow - 1);
-                const uint16_t *src = w == 2 ? Cmp + oB_in + (size_t)r * GN : r < pd ? winB + oB_win + (size_t)r * GN : Bmp + oB_in + (size_t)(r - pd) * GN;
+                const uint16_t *src = w == 2 ? Cmp + oB_in + (size_t)r * GN : r < pq ? stashed(winB, winB_out, oB_win, r, GN) : Bmp + oB_in + (size_t)(r - pq) * GN;
                 bk[it] = *reinterpret_cast<const u4v *>(src + 8 * (l % CB));
             }
         }
@@ -203,7 +211,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     uint32_t dt_raw;
     {
         const int tt = min((int)li, T - 1);
-        dt_raw = tt < pd ? (winDt + oDt_win)[tt * H] : (dtp + oDt_in)[(tt - pd) * H];
+        dt_raw = tt < pq ? *stashed(winDt, winDt_out, oDt_win, tt, H) : (dtp + oDt_in)[(tt - pq) * H];
     }
     __builtin_amdgcn_sched_barrier(0);
     SSMV_TP(1);
@@ -244,7 +252,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             if (it * RPI < nrow) {
                 pin(xk[it]);
                 const int r = rfirst + it * RPI + (int)(l / CX);
-                const int j = r - 3 - pd;                // >= 0: a token of this call
+                const int j = r - 3 - pq;                // >= 0: a token of this call
                 if (r < 3 + T) {
                     *reinterpret_cast<u4v *>(sXr + r * XRS + 8 * (l % CX)) = xk[it];
                     if (CONV && j >= 0)
@@ -263,8 +271,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
                 const int r = it * RPI + (int)(l / CB);
                 if (r < nrow) {
                     *reinterpret_cast<u4v *>(dst + r * CS + 8 * (l % CB)) = bk[it];
-                    if (w == 1 && writes_B && r >= pd)
-                        *reinterpret_cast<u4v *>(winB_out + oB_wout + (size_t)(r - pd) * GN + 8 * (l % CB)) = bk[it];
+                    if (w == 1 && writes_B && r >= pq)
+                        *reinterpret_cast<u4v *>(winB_out + oB_wout + (size_t)(r - pq) * GN + 8 * (l % CB)) = bk[it];
                 }
             }
         }
@@ -293,10 +301,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const float wj = (int)li < pd ? dtv * __builtin_amdgcn_exp2f(cumJ - cum) : 0.f;
     const float wk = ((int)li >= pd && (int)li < T) ? dtv * __builtin_amdgcn_exp2f(cumK - cum) : 0.f;
     const float alphaJ = __builtin_amdgcn_exp2f(cumJ), beta = __builtin_amdgcn_exp2f(cumK - cumJ);
-    const float cy = lane_get(cum, min(pd + (int)li, 15));   // draft li is token pd + li
+    const float cy = lane_get(cum, min(pq + (int)li, 15));   // draft li is token pq + li
     const float alphaY = __builtin_amdgcn_exp2f(cy);
     if (w == 0 && first_tile) {
-        if (g == 0 && (int)li >= pd && (int)li < T) winDt_out[oDt_wout + (size_t)(li - pd) * H] = (uint16_t)dt_raw;   // the raw dt: replay transforms it again
+        if (g == 0 && (int)li >= pq && (int)li < T) winDt_out[oDt_wout + (size_t)(li - pq) * H] = (uint16_t)dt_raw;   // the raw dt: replay transforms it again
         if (hd == 0 && tid == 0) p.last_k[b] = t0 + kb;
     }
     __syncthreads();
@@ -321,7 +329,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
                 }
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
-                    const int tt = 2 * (int)u + e, j = tt - pd;
+                    const int tt = 2 * (int)u + e, j = tt - pq;
                     if (tt < T) {
                         uint32_t bits = sXr32[(3 + tt) * (XRS / 2) + cp];
                         if (CONV && j >= 0) {
@@ -385,7 +393,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             if ((int)li >= kb) cs_ = u4v{0u, 0u, 0u, 0u};
             G = mfma16(as_bf8(bs), as_bf8(cs_), G);
         }
-        const int tty = pd + (int)li;                    // draft li as a token of the launch
+        const int tty = pq + (int)li;                    // draft li as a token of the launch
         float m[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -433,21 +441,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             const u2v c2 = *reinterpret_cast<const u2v *>(sC + li * CS + 16 * q + 4 * g);
             Y1 = mfma16(as_bf8(a), as_bf8(u4v{c2.x, c2.y, c2.x, c2.y}), Y1);
         }
-        // (i) + (ii): fold the pending tokens in and store the snapshot h_j
-        if (pd > 0) {
+        // (a call of a replayed round that is not its last needs the outputs only: no snapshot is formed)
+        if (!EXTRA || p.store_state) {
+            // (i) + (ii): fold the pending tokens in and store the snapshot h_j
+            if (pd > 0) {
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) {
-                const bf8 Aw = row16(sWj + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1));
-                st[i][q] = mfma16(Aw, Xop, st[i][q] * alphaJ);
-                __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstJ + ((i * NQ + q) << 8)));
+                for (int q = 0; q < NQ; ++q) {
+                    const bf8 Aw = row16(sWj + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1));
+                    st[i][q] = mfma16(Aw, Xop, st[i][q] * alphaJ);
+                    __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstJ + ((i * NQ + q) << 8)));
+                }
             }
-        }
-        // (iii) + (iv): the drafts, and the snapshot h_k (Algorithm 2), unless every accepted token is to stay pending
+            // (iii) + (iv): the drafts, and the snapshot h_k (Algorithm 2), unless every accepted token is to stay pending
+            if (p.write_hk) {
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            const bf8 Aw = row16(sWk + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1));
-            st[i][q] = mfma16(Aw, Xop, st[i][q] * beta);
-            if (p.write_hk) __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstK + ((i * NQ + q) << 8)));
+                for (int q = 0; q < NQ; ++q) {
+                    const bf8 Aw = row16(sWk + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1));
+                    st[i][q] = mfma16(Aw, Xop, st[i][q] * beta);
+                    __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstK + ((i * NQ + q) << 8)));
+                }
+            }
         }
         // Y2^T = X^T M^T : the drafts' outputs from the tokens of this launch (D x_t on the diagonal of M)
         const bf8 Mop = row16(sM + ((g >> 1) * 16 + li) * XS + 8 * (g & 1));
@@ -478,7 +491,7 @@ int launch_shape(const VerifyParams &p, hipStream_t stream)
 {
     const dim3 grid(p.P / (64 * NT), p.H, p.batch), block(256);
     const bool conv = p.x_raw != nullptr;
-    const bool extra = p.tok0 > 0 || p.dt_softplus || p.dt_bias || p.z || p.k_seq;
+    const bool extra = p.tok0 > 0 || p.dt_softplus || p.dt_bias || p.z || p.k_seq || !p.store_state;
     if (conv) {
         if (extra) hipLaunchKernelGGL((verify_mfma_kernel<N, NT, true, true>), grid, block, 0, stream, p);
         else hipLaunchKernelGGL((verify_mfma_kernel<N, NT, true, false>), grid, block, 0, stream, p);

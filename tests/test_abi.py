@@ -129,6 +129,15 @@ def test_argument_validation_precedes_any_gpu_work():
     assert _code(ssmv.ssm_block_multistep, d, c, k=1, tok0=1, xc=P, k_seq=P, **blk) == ssmv.SSMV_EUNSUPPORTED
     # a later call of a round must bring raw inputs: conv1d_state_update cannot append behind the round's earlier tokens
     assert _code(ssmv.ssm_block_multistep, d, c, k=1, tok0=1, xc=P, **blk) == ssmv.SSMV_EUNSUPPORTED
+    # replayed rounds: flag values; last_call only with replay_round; only on the matrix-core engine
+    assert _code(ssmv.ssm_block_multistep, d, c, k=1, x_raw=P, conv_wgt=P, last_call=True, **blk) == ssmv.SSMV_EINVAL
+    assert _code(ssmv.ssm_block_multistep, d, c, k=1, x_raw=P, conv_wgt=P, replay_round=True, **blk) == ssmv.SSMV_EUNSUPPORTED
+    d_mx = ssmv.make_dims(2, 4, 64, 64, kmax=4, io="bf16")
+    ssmv.ssmv_set_tuning(4, 4)
+    try:
+        assert _code(ssmv.ssm_block_multistep, d_mx, c, k=1, x_raw=P, conv_wgt=P, replay_round=True, **blk) == ssmv.SSMV_EUNSUPPORTED
+    finally:
+        ssmv.ssmv_set_tuning(0, 0)
     assert _code(ssmv.ssm_block_multistep, d, c, k=1, xc=P, dt_softplus=2, **blk) == ssmv.SSMV_EINVAL
     assert _code(ssmv.ssm_block_multistep, d, c, k=1, xc=P, z=P + 2, **blk) == ssmv.SSMV_EALIGN
     d_hj = ssmv.make_dims(2, 4, 16, 16, kmax=4, io="f32", snapshot_mode="hj_only")

@@ -155,6 +155,75 @@ def test_round_fed_by_several_calls_equals_one_call(name, split):
     ssmv.ssmv_check(many.cache.c)
 
 
+REPLAY_CASES = {
+    "cfg1_small": CONFIGS["cfg1"].scaled(nheads=4, batch=3, rounds=10),
+    "k8_narrow_heads": CONFIGS["cfg1"].scaled(nheads=3, headdim=64, dstate=128, batch=2, k=8, rounds=10, ngroups=1),
+    "cfg1_small_hj": CONFIGS["cfg1"].scaled(nheads=4, batch=3, rounds=10, snapshot_mode="hj_only"),
+    "groups_silu": CONFIGS["cfg1"].scaled(nheads=4, headdim=64, dstate=32, ngroups=2, batch=5, rounds=8, conv_act="silu"),
+}
+REPLAY_SPLITS = {"ones": None, "2+2": [2, 2], "1+3": [1, 3], "3+1": [3, 1], "1+5+2": [1, 5, 2]}
+
+
+@pytest.mark.parametrize("split", sorted(REPLAY_SPLITS))
+@pytest.mark.parametrize("name", sorted(REPLAY_CASES))
+def test_replayed_round_equals_one_call(name, split):
+    """replay_round: every call of a round recomputes from the live slot (pending tokens, then the round's earlier
+    tokens out of the round's stash), only the last one stores h_j and h_k.  Outputs, window, ring, integers and - after
+    the last call - the slots must be what ONE call with all the tokens leaves; no slot changes before the last call;
+    a call repeated gives the same outputs."""
+    wl = REPLAY_CASES[name]
+    parts0 = REPLAY_SPLITS[split]
+    if parts0 is not None and sum(parts0) != wl.k:
+        pytest.skip("split does not add up to this case's k")
+    data = generate(wl)
+    lp = data.layers[0]
+    tol = TOL[wl.io]
+    one, many = HipLayer(wl, lp), HipLayer(wl, lp)
+    assert ssmv.ssmv_engine_of(many.dims) == 1
+    ora = oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.conv_act, wl.ngroups)
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width, hj_only=wl.snapshot_mode == "hj_only")
+    for i, rd in enumerate(data.rounds):
+        k = rd.x_raw.shape[1]
+        parts = parts0 if parts0 is not None else [1] * k
+        d_x, d_dt, d_B, d_C = (to_dev(v, wl.io) for v in (rd.x_raw, rd.dt[0], rd.B[0], rd.C[0]))
+        y_one, _ = one.conv_verify(d_x, d_dt, d_B, d_C)
+        y_ref, _, _ = ora.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
+        slots_before = many.cache.state_view().clone()
+        t0, ys = 0, []
+        for ci, n in enumerate(parts):
+            sl = slice(t0, t0 + n)
+            last = ci == len(parts) - 1
+            outs = []
+            for rep in range(2):                           # every call twice: idempotent
+                y = torch.empty_like(d_x[:, sl])
+                ssmv.ssm_block_multistep(many.dims, many.cache.c, x_raw=d_x[:, sl].contiguous(), conv_wgt=many.conv_w,
+                                         conv_bias=many.conv_b, dt=d_dt[:, sl].contiguous(), Bm=d_B[:, sl].contiguous(),
+                                         Cm=d_C[:, sl].contiguous(), A=many.A, D=many.D, k=n, tok0=t0, y_out=y,
+                                         replay_round=True, last_call=last)
+                outs.append(y)
+            assert torch.equal(outs[0], outs[1]), "round %d call %d is not idempotent" % (i, ci)
+            if not last:
+                assert torch.equal(many.cache.state_view(), slots_before), "round %d call %d touched a slot" % (i, ci)
+            bk.verify(n, tok0=t0)
+            ys.append(outs[0])
+            t0 += n
+        y_many = torch.cat(ys, dim=1)
+        assert rel_err(to_host(y_many), y_ref) <= tol, "round %d" % i
+        assert rel_err(to_host(y_many), to_host(y_one)) <= tol
+        assert many.cache.ints()["last_k"].tolist() == [k] * wl.batch
+        # the slots after the last call against the single call's (2^-17 per product, and the split decides which are formed)
+        assert rel_err(to_host(many.cache.state_view()), to_host(one.cache.state_view())) <= 1e-4, "round %d: slots" % i
+        acc = torch.from_numpy(rd.accepted.astype(np.int32)).to("cuda")
+        one.commit(acc); many.commit(acc)
+        ora.commit(rd.accepted)
+        bk.commit(rd.accepted)
+        _check_ints(many, bk, "round %d" % i)
+        for nm in ("conv_ring", "win_xc0", "win_xc1", "win_dt0", "win_dt1", "win_B0", "win_B1"):
+            assert torch.equal(many.cache.buffers[nm], one.cache.buffers[nm]), nm
+        assert rel_err(to_host(many.materialize()), ora.h) <= tol
+    ssmv.ssmv_check(many.cache.c)
+
+
 def test_draft_model_round_trip_with_rejections():
     """A draft-side round as the paper describes it: k single-token calls (the first recomputes the tokens
     accepted last round), then the verifier's verdict rolls the draft's own cache back."""

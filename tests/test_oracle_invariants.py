@@ -283,14 +283,18 @@ def _compositions(n):
             yield (first,) + rest
 
 
-@pytest.mark.parametrize("wl", [TINY, TINY_DIAG.scaled(k=4)], ids=lambda w: w.name)
-def test_round_fed_by_several_calls_equals_one_call(wl):
+@pytest.mark.parametrize("replay", [False, True], ids=["carry", "replay"])
+@pytest.mark.parametrize("wl", [TINY, TINY_DIAG.scaled(k=4), TINY_HJ], ids=lambda w: w.name)
+def test_round_fed_by_several_calls_equals_one_call(wl, replay):
     """Section 4.3, draft side: a round whose k tokens arrive over several calls leaves the cache exactly where one
-    k-token call would, for every way of splitting k <= 4, over rounds with ragged acceptance in between."""
+    k-token call would, for every way of splitting k <= 4, over rounds with ragged acceptance in between - whether the
+    calls carry the state through the h_k slot or every call recomputes from the live slot (replay_round)."""
+    if wl.snapshot_mode == "hj_only" and not replay:
+        pytest.skip("carrying the state needs the h_k slot")
     data = generate(wl.scaled(rounds=4))
     lp = data.layers[0]
     mk = lambda: oracle.LazyMirror(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.kmax_eff, wl.ring_len,
-                                   wl.conv_act, wl.ngroups)
+                                   wl.conv_act, wl.ngroups, hj_only=wl.snapshot_mode == "hj_only")
     for split in _compositions(wl.k):
         one, many = mk(), mk()
         eager = _eager(wl, data)
@@ -298,9 +302,17 @@ def test_round_fed_by_several_calls_equals_one_call(wl):
             y1, xc1 = one.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
             ye, _, _ = eager.verify(rd.x_raw, rd.dt[0], rd.B[0], rd.C[0])
             t0, ys, xcs = 0, [], []
-            for n in split:
+            slots_before = many.slots.copy()
+            for ci, n in enumerate(split):
                 s = slice(t0, t0 + n)
-                y, xc = many.verify(rd.x_raw[:, s], rd.dt[0][:, s], rd.B[0][:, s], rd.C[0][:, s], tok0=t0)
+                last = ci == len(split) - 1
+                y, xc = many.verify(rd.x_raw[:, s], rd.dt[0][:, s], rd.B[0][:, s], rd.C[0][:, s], tok0=t0,
+                                    replay_round=replay, last_call=replay and last)
+                if replay:                                    # idempotent, and no slot is touched before the last call
+                    y2, _ = many.verify(rd.x_raw[:, s], rd.dt[0][:, s], rd.B[0][:, s], rd.C[0][:, s], tok0=t0,
+                                        replay_round=True, last_call=last)
+                    assert np.array_equal(y, y2)
+                    assert last or np.array_equal(many.slots, slots_before)
                 ys.append(y); xcs.append(xc)
                 t0 += n
                 assert many.bk.last_k == [t0] * wl.batch
