@@ -44,6 +44,9 @@ def parse_args():
                          "vector: the vector-ALU kernel on a row-major state")
     ap.add_argument("--single-snapshot", action="store_true",
                     help="the single-snapshot variant: h_k is never stored, every accepted token is replayed next round")
+    ap.add_argument("--deferred-advance", action="store_true",
+                    help="the deferred-advance variant: h_k is never stored and h_j only when the 16-token window is about to "
+                         "fill up; most rounds only read the state")
     ap.add_argument("--naive", action="store_true",
                     help="the unfused baseline the paper starts from: one state snapshot copy, then k single-token rounds "
                          "(conv, verify with k=1, commit of 1) per layer-round; rollback work is not even included")
@@ -68,14 +71,26 @@ def parse_args():
     return ap.parse_args()
 
 
-def pend_after(accepted_rounds, k_rounds, hj_only=False):
+WINDOW = 16     # tokens a verify launch can take (deferred advance)
+
+
+def pend_hi_of(wl):
+    """A verify stores h_j iff it meets more pending tokens than this."""
+    return WINDOW - 2 * wl.kmax_eff if wl.snapshot_mode == "defer" else 0
+
+
+def pend_after(accepted_rounds, k_rounds, hj_only=False, mode=None, kmax=0):
     """Host-side accounting of the pending-token count per sequence before each round (for byte counts only)."""
     import numpy as np
+    mode = mode or ("hj_only" if hj_only else "both")
     pend = np.zeros_like(accepted_rounds[0])
     out = []
     for acc, k in zip(accepted_rounds, k_rounds):
         out.append(pend.copy())
-        pend = acc.copy() if hj_only else np.where(acc == k, 0, acc)
+        if mode == "defer":
+            pend = np.where(pend > WINDOW - 2 * kmax, acc, pend + acc)
+        else:
+            pend = acc.copy() if mode == "hj_only" else np.where(acc == k, 0, acc)
     return out
 
 
@@ -87,8 +102,9 @@ def verify_bytes(wl, pend, k, fused, gate=False, calls=1, replay=False):
     S = wl.state_elems * 4
     Cx, H, GN = wl.conv_channels, wl.nheads, wl.ngroups * wl.dstate
     total = 0
+    hi = pend_hi_of(wl)
     for pd in pend:
-        total += S * ((1 if wl.snapshot_mode == "hj_only" else 2) + (1 if pd > 0 else 0))
+        total += S * ((2 if wl.snapshot_mode == "both" else 1) + (1 if pd > hi else 0))
         total += k * (Cx + H + 2 * GN) * e          # xc (or x_raw), dt, B, C in
         total += k * Cx * e                         # y out
         total += k * (Cx + H + GN) * e              # stash out
@@ -125,7 +141,7 @@ def step_plan(wl, accepted_rounds, k, n_inst, warmup, steps, fused, gate=False, 
     prime = 3 * n_inst
     first_timed = prime + warmup
     rounds_run = max((first_timed + steps + n_inst - 1) // n_inst + 1, n_rounds)
-    sched = pend_after([accepted_rounds[i % n_rounds] for i in range(rounds_run)], [k] * rounds_run, hj_only=wl.snapshot_mode == "hj_only")
+    sched = pend_after([accepted_rounds[i % n_rounds] for i in range(rounds_run)], [k] * rounds_run, mode=wl.snapshot_mode, kmax=wl.kmax_eff)
     step_bytes = lambda s: round_bytes(wl, sched[s // n_inst], k, fused, gate=gate, calls=calls, replay=replay)
     workload = sum(step_bytes(r * n_inst) for r in range(1, max(2, n_rounds))) / max(1, n_rounds - 1)
     timed = sum(step_bytes(s) for s in range(first_timed, first_timed + steps)) / steps
@@ -320,6 +336,11 @@ def main():
         wl = wl.scaled(layers=1)           # the metric is per SSM layer; the stack is covered by the parity tests
     if args.single_snapshot:
         wl = wl.scaled(snapshot_mode="hj_only")
+    if args.deferred_advance:
+        if args.single_snapshot or 2 * wl.kmax_eff > WINDOW:
+            print("bench.py: --deferred-advance needs 2*kmax <= %d and excludes --single-snapshot" % WINDOW, file=sys.stderr)
+            sys.exit(2)
+        wl = wl.scaled(snapshot_mode="defer")
     data = generate(wl)
     lp = data.layers[0]
     io_t = torch.bfloat16 if wl.io == "bf16" else torch.float32
@@ -356,8 +377,8 @@ def main():
         print("bench.py: --block/--draft use the fused launch; not with --split/--naive", file=sys.stderr)
         sys.exit(2)
     replay = args.draft and matrix_engine and not args.draft_carry and args.rows == 0 and args.waves == 0
-    if args.draft and args.single_snapshot and not replay:
-        print("bench.py: a round whose calls carry the state needs the h_k slot; not with --single-snapshot", file=sys.stderr)
+    if args.draft and wl.snapshot_mode != "both" and not replay:
+        print("bench.py: a round whose calls carry the state needs the h_k slot; not with --single-snapshot or --deferred-advance", file=sys.stderr)
         sys.exit(2)
     blk = {}
     if args.block:
@@ -608,7 +629,8 @@ def main():
                                   n_rounds, n_inst, n_inst * cache_bytes / 2 ** 30),
                    "batch": wl.batch, "k": k, "rounds": n_rounds, "instances": n_inst,
                    "launch": "hip-graph" if not args.no_graph else "eager",
-                   "snapshots": "h_j only (single-snapshot variant)" if wl.snapshot_mode == "hj_only" else "h_j and h_k (Algorithm 2)",
+                   "snapshots": {"both": "h_j and h_k (Algorithm 2)", "hj_only": "h_j only (single-snapshot variant)",
+                                 "defer": "h_j only, and only when the 16-token window fills up (deferred advance)"}[wl.snapshot_mode],
                    "path": ("draft side: k single-token calls per layer-round, every call recomputing from the live slot, snapshots stored by the last; one commit launch per round" if replay else
                             "draft side: k single-token calls per layer-round carrying the state through the h_k slot (first one replays), one commit launch per round" if args.draft else
                             "fused conv+verify launch per layer, one commit launch per round over all caches") +

@@ -61,8 +61,15 @@ enum { SSMV_ACT_NONE = 0, SSMV_ACT_SILU = 1 };  /* conv_act                     
 /* snapshot_mode.  BOTH is Algorithm 2 as printed: verify stores h_j (when tokens were pending) and h_k, and a
  * fully accepted round makes h_k the live state.  HJ_ONLY never stores h_k: every accepted token, also those of
  * a fully accepted round, stays pending and is replayed by the next verify.  Same outputs and same logical
- * state; about a third fewer bytes per round for up to k more replay steps. */
-enum { SSMV_SNAP_BOTH = 0, SSMV_SNAP_HJ_ONLY = 1 };
+ * state; about a third fewer bytes per round for up to k more replay steps.
+ * DEFER goes one step further along Section 4.2's lazy advance ("maintains only one hidden state in the cache and
+ * advances it lazily"): h_k is never stored, and h_j only when it has to be.  A verify recomputes up to SSMV_WINDOW
+ * tokens from the cached state, so the live slot stays put and the accepted tokens collect behind it for as long as the
+ * next round is sure to fit: a verify stores h_j (and its commit moves the live slot there) only if it meets
+ * pend > SSMV_WINDOW - 2*kmax.  kmax <= SSMV_WINDOW/2; with kmax = SSMV_WINDOW/2 this is HJ_ONLY.  Same outputs and same
+ * logical state; most rounds then only READ the state (kmax = 4, acceptance uniform in [0,4]: a store about every
+ * fifth round).  The pending tokens of a sequence sit in a ring of SSMV_WINDOW entries (see ssmv_cache). */
+enum { SSMV_SNAP_BOTH = 0, SSMV_SNAP_HJ_ONLY = 1, SSMV_SNAP_DEFER = 2 };
 /* engine.  AUTO lets the library pick the kernel and with it the layout of the state slots: scalar-A mode with bf16
  * tokens, headdim a multiple of 64, dstate in {32, 64, 128} and kmax <= 8 (HJ_ONLY: pend can reach kmax, so 2*kmax <= 16)
  * runs the launch of Section 4.3 on the matrix cores and keeps each (sequence, head) block of a slot in 16x16 tiles;
@@ -70,6 +77,7 @@ enum { SSMV_SNAP_BOTH = 0, SSMV_SNAP_HJ_ONLY = 1 };
 enum { SSMV_ENGINE_AUTO = 0, SSMV_ENGINE_VECTOR = 1 };
 
 #define SSMV_KMAX_LIMIT 16      /* largest supported kmax                   */
+#define SSMV_WINDOW 16          /* SSMV_SNAP_DEFER: tokens (pending + drafts) a verify can take, and entries of the window ring */
 #define SSMV_CONV_WIDTH 4       /* the only supported conv width            */
 #define SSMV_CACHE_NPTR 15      /* number of pointers in ssmv_cache         */
 
@@ -86,7 +94,7 @@ typedef struct {
     int32_t io_dtype;       /* SSMV_F32 | SSMV_BF16                                               */
     int32_t a_mode;         /* SSMV_A_SCALAR | SSMV_A_DIAG                                        */
     int32_t conv_act;       /* SSMV_ACT_NONE | SSMV_ACT_SILU                                      */
-    int32_t snapshot_mode;  /* SSMV_SNAP_BOTH | SSMV_SNAP_HJ_ONLY                                 */
+    int32_t snapshot_mode;  /* SSMV_SNAP_BOTH | SSMV_SNAP_HJ_ONLY | SSMV_SNAP_DEFER               */
     int32_t engine;         /* SSMV_ENGINE_AUTO | SSMV_ENGINE_VECTOR                              */
 } ssmv_dims;
 
@@ -100,8 +108,11 @@ typedef struct {
     void    *win_xc[2];    /* [batch][kmax][Cx]   io_dtype: conv outputs of a round (ping-pong)     */
     void    *win_dt[2];    /* [batch][kmax][H]    io_dtype                                          */
     void    *win_B[2];     /* [batch][kmax][G][N] io_dtype                                          */
+                           /* SSMV_SNAP_DEFER: win_*[0] is [batch][SSMV_WINDOW][..], a ring per sequence in which
+                            * token q of the sequence (q = pos .. pos+pend-1 pending, then the round's) sits at
+                            * entry q % SSMV_WINDOW; win_*[1] is not used (ssmv_cache_sizes asks for one granule) */
     int32_t *cur_slot;     /* [batch] in {0,1,2}: the live slot, holds the state at `pos`           */
-    int32_t *pend;         /* [batch] in [0,kmax) (HJ_ONLY: [0,kmax]): accepted tokens not yet folded  */
+    int32_t *pend;         /* [batch] in [0,kmax) (HJ_ONLY: [0,kmax]; DEFER: [0,SSMV_WINDOW-kmax]): accepted tokens not yet folded  */
     int64_t *pos;          /* [batch] tokens folded into state[cur_slot]                            */
     int32_t *conv_head;    /* [batch] ring index of the newest COMMITTED raw input                  */
     int32_t *last_k;       /* [batch] k of the verify that has not been committed yet, else 0       */
@@ -141,11 +152,11 @@ int conv1d_state_update(const ssmv_dims *dims, const ssmv_cache *cache, const vo
 
 /* MultiStep of Section 4.2 fused as Section 4.3 asks: in ONE kernel launch, per
  * sequence, (i) load the live state h_pos and replay the pend[b] pending tokens
- * from the window, (ii) if pend[b] > 0 store that state h_j into slot
+ * from the window, (ii) if pend[b] > 0 (SSMV_SNAP_DEFER: > SSMV_WINDOW - 2*kmax) store that state h_j into slot
  * (cur+1)%3, (iii) run the k draft tokens
  *   h <- exp(dt_t*A) * h + (dt_t * x_t) (x) B_t ,   y_t = C_t . h + D * x_t
- * (Eq. 1; fp32 state and arithmetic), (iv) store h_k into slot (cur+2)%3 (not with
- * SSMV_SNAP_HJ_ONLY) and this round's (xc, dt, B) into the other half of the window.  Intermediate
+ * (Eq. 1; fp32 state and arithmetic), (iv) store h_k into slot (cur+2)%3 (SSMV_SNAP_BOTH
+ * only) and this round's (xc, dt, B) into the other half of the window (DEFER: behind the pending ones in the ring).  Intermediate
  * states and the discrete parameters live in registers/LDS only.
  *   xc [batch][k][H*P], dt [batch][k][H], Bm, Cm [batch][k][G][N]: io_dtype, device;
  *   dt is the final positive step size; A [H] or [H][N] (negative reals) and D [H]:
@@ -185,7 +196,7 @@ int ssm_conv_verify_multistep(const ssmv_dims *dims, const ssmv_cache *cache, co
  *     call with all tok0+k tokens would have left, the slots and the outputs the same up to fp32 rounding
  *     (the rounding order inside a launch depends on how many tokens it holds), so ssm_commit_rollback
  *     applies unchanged.
- *     tok0 + k <= kmax; not with SSMV_SNAP_HJ_ONLY (SSMV_EUNSUPPORTED); a later call is NOT idempotent.
+ *     tok0 + k <= kmax; SSMV_SNAP_BOTH only (SSMV_EUNSUPPORTED otherwise); a later call is NOT idempotent.
  *   - replay_round = 1 (matrix-core engine only, SSMV_EUNSUPPORTED otherwise): the other way to feed a round by
  *     several calls, the one Section 4.3 describes for the draft model - recompute from the cache instead of
  *     carrying the state through memory.  EVERY call of the round starts from the live slot, replays the pending
@@ -194,7 +205,7 @@ int ssm_conv_verify_multistep(const ssmv_dims *dims, const ssmv_cache *cache, co
  *     h_k as one call with all tok0 + k tokens would.  A call then reads the state once and writes it only at the
  *     end of the round (the default above reads and writes it on every call).  Calls are idempotent.  All calls
  *     of a round must agree on replay_round, and the round must end with a last_call = 1 before its commit.
- *     Works with SSMV_SNAP_HJ_ONLY too.
+ *     Works with SSMV_SNAP_HJ_ONLY and SSMV_SNAP_DEFER too.
  *   - k_seq (device int32 [batch], or NULL): ragged draft counts.  Sequence b takes only the first
  *     kb = clamp(k_seq[b], 1, k) of the k tokens given (at least one: last_k = 0 means "no verify"
  *     to the commit; a sequence with nothing to verify passes one token and accepts none) (the arrays keep the stride k): its outputs
@@ -279,7 +290,9 @@ int ssm_prefill_block(const ssmv_dims *dims, const ssmv_cache *cache, const ssmv
  *   always      : conv_head <- (conv_head+a) & (R-1), last_k <- 0
  * and win_par flips once.  A commit with no verify pending changes nothing and
  * sets err_flag.  With SSMV_SNAP_HJ_ONLY the first case does not exist: pend > 0
- * moves to h_j as above, and pend <- a in every case. */
+ * moves to h_j as above, and pend <- a in every case.  With SSMV_SNAP_DEFER:
+ *   pend > SSMV_WINDOW - 2*kmax : cur <- (cur+1)%3, pos <- pos+pend, pend <- a      (the verify stored h_j)
+ *   otherwise                   :                                    pend <- pend+a */
 int ssm_commit_rollback(const ssmv_dims *dims, const ssmv_cache *cache, const int32_t *accepted,
                         void *hip_stream);
 

@@ -204,14 +204,30 @@ class BookkeepingModel:
     Global: ``win_par`` (which half of the pending-token window is current),
     ``err`` (sticky).  Verify writes h_j to slot (cur+1)%3 when pend>0 and h_k to
     slot (cur+2)%3 and touches no integer except last_k.
+
+    mode "hj_only": the single-snapshot variant.  h_k is never stored; every accepted token stays pending,
+    also after a fully accepted round, and is replayed by the next verify.
+    mode "defer": h_k is never stored and h_j only when it has to be.  A verify can replay up to WINDOW - k
+    tokens, so the live slot stays where it is, and the accepted tokens pile up behind it, for as long as the
+    NEXT round is sure to fit: pend + a + kmax <= WINDOW for every a <= kmax, i.e. pend <= WINDOW - 2 kmax = pend_hi.
+    Only a verify that meets pend > pend_hi stores h_j (the state after the pending tokens), and its commit moves
+    the live slot there.  The pending tokens of a sequence sit in a ring of WINDOW entries, token q of the sequence
+    (counted from its start) at entry q mod WINDOW.
     """
 
-    def __init__(self, batch: int, ring_len: int, conv_width: int = 4, hj_only: bool = False):
+    WINDOW = 16
+
+    def __init__(self, batch: int, ring_len: int, conv_width: int = 4, hj_only: bool = False, mode: str = None, kmax: int = 0):
         assert ring_len & (ring_len - 1) == 0
         self.batch, self.R = batch, ring_len
-        # hj_only: the single-snapshot variant.  h_k is never stored; every accepted token stays pending,
-        # also after a fully accepted round, and is replayed by the next verify.
-        self.hj_only = hj_only
+        self.mode = mode if mode is not None else ("hj_only" if hj_only else "both")
+        assert self.mode in ("both", "hj_only", "defer")
+        self.hj_only = self.mode == "hj_only"
+        self.defer = self.mode == "defer"
+        self.pend_hi = 0
+        if self.defer:
+            assert 1 <= kmax and 2 * kmax <= self.WINDOW, "defer mode: the window must hold two rounds"
+            self.pend_hi = self.WINDOW - 2 * kmax
         self.cur = [0] * batch
         self.pend = [0] * batch
         self.pos = [0] * batch
@@ -237,7 +253,14 @@ class BookkeepingModel:
             if a < 0 or a > lk:
                 self.err = 1
                 a = min(max(a, 0), lk)
-            if a == lk and not self.hj_only:
+            if self.defer:
+                if self.pend[b] > self.pend_hi:       # this round's verify stored h_j: move there
+                    self.cur[b] = (self.cur[b] + 1) % 3
+                    self.pos[b] += self.pend[b]
+                    self.pend[b] = a
+                else:                                 # the live slot stays; the window grows
+                    self.pend[b] += a
+            elif a == lk and not self.hj_only:
                 self.cur[b] = (self.cur[b] + 2) % 3
                 self.pos[b] += self.pend[b] + a
                 self.pend[b] = 0
@@ -257,7 +280,7 @@ class LazyMirror:
     """O3: fp64 mirror of the lazy three-slot policy (CPU only; proves lazy == eager)."""
 
     def __init__(self, a_mode: str, A, D, conv_w, conv_b, h0, io: str, kmax: int, ring_len: int,
-                 act: str = "none", ngroups: int = 1, conv_init=None, hj_only: bool = False):
+                 act: str = "none", ngroups: int = 1, conv_init=None, hj_only: bool = False, mode: str = None):
         self.a_mode, self.io, self.act, self.G = a_mode, io, act, ngroups
         self.A, self.D = _c(A), _c(D)
         self.conv_w = _c(conv_w)
@@ -272,24 +295,38 @@ class LazyMirror:
         self.ring = np.zeros((self.batch, ring_len, self.Cx))
         if conv_init is not None:
             self.ring[:, : self.W - 1] = _c(conv_init)
-        self.win_xc = np.zeros((2, self.batch, kmax, self.Cx))
-        self.win_dt = np.zeros((2, self.batch, kmax, self.H))
-        self.win_B = np.zeros((2, self.batch, kmax, ngroups, self.N))
-        self.hj_only = hj_only
-        self.bk = BookkeepingModel(self.batch, ring_len, self.W, hj_only=hj_only)
+        self.bk = BookkeepingModel(self.batch, ring_len, self.W, hj_only=hj_only, mode=mode, kmax=kmax)
+        self.hj_only, self.defer = self.bk.hj_only, self.bk.defer
+        # both / hj_only: two halves of kmax entries (pending tokens in half win_par, the round's in the other);
+        # defer: one ring of WINDOW entries per sequence (kept as "half 0"), token q of the sequence at entry q mod WINDOW
+        went = self.bk.WINDOW if self.defer else kmax
+        self.win_xc = np.zeros((2, self.batch, went, self.Cx))
+        self.win_dt = np.zeros((2, self.batch, went, self.H))
+        self.win_B = np.zeros((2, self.batch, went, ngroups, self.N))
+
+    def _entries(self, b: int, first: int, count: int, of_round: bool):
+        """(half, entry indices) of `count` window tokens of sequence b: the pending ones from `first` on, or, with
+        of_round, the ones the current round has been fed from its token `first` on."""
+        bk = self.bk
+        if self.defer:
+            base = bk.pos[b] + (bk.pend[b] if of_round else 0) + first
+            return 0, [(base + i) % bk.WINDOW for i in range(count)]
+        return (bk.win_par ^ 1 if of_round else bk.win_par), list(range(first, first + count))
+
+    def _scan_window(self, b: int, g: np.ndarray, count: int, of_round: bool) -> np.ndarray:
+        """g advanced over `count` window tokens (no outputs)."""
+        if count == 0:
+            return g
+        half, idx = self._entries(b, 0, count, of_round)
+        zeros_c = np.zeros((1, count, self.G, self.N))
+        _, snap = scan_tokens(self.a_mode, g[None], self.win_xc[half, b][idx][None], self.win_dt[half, b][idx][None],
+                              self.win_B[half, b][idx][None], zeros_c, self.A, self.D)
+        return snap[count, 0]
 
     def _replayed(self, b: int) -> np.ndarray:
         """State of sequence b at pos+pend: live slot with the pending tokens folded in."""
         bk = self.bk
-        g = self.slots[bk.cur[b], b][None]
-        pd = bk.pend[b]
-        if pd > 0:
-            par = bk.win_par
-            zeros_c = np.zeros((1, pd, self.G, self.N))
-            _, snap = scan_tokens(self.a_mode, g, self.win_xc[par, b:b + 1, :pd], self.win_dt[par, b:b + 1, :pd],
-                                  self.win_B[par, b:b + 1, :pd], zeros_c, self.A, self.D)
-            g = snap[pd]
-        return g[0]
+        return self._scan_window(b, self.slots[bk.cur[b], b], bk.pend[b], of_round=False)
 
     def verify(self, x_raw, dt, Bm, Cm, tok0: int = 0, replay_round: bool = False, last_call: bool = False):
         """tok0 > 0: a later call of a round that several calls feed (the draft side of Section 4.3 produces its
@@ -303,8 +340,7 @@ class LazyMirror:
         bk, W, R = self.bk, self.W, self.R
         k = x_raw.shape[1]
         assert 1 <= k and 0 <= tok0 and tok0 + k <= self.kmax
-        assert tok0 == 0 or replay_round or not self.hj_only
-        npar_ = bk.win_par ^ 1
+        assert tok0 == 0 or replay_round or not (self.hj_only or self.defer)
         raw = np.empty((self.batch, W - 1 + k, self.Cx))
         for b in range(self.batch):
             head = (bk.conv_head[b] + tok0) & (R - 1)  # newest raw input fed so far
@@ -319,24 +355,22 @@ class LazyMirror:
             stores = not replay_round or last_call
             if tok0 == 0 or replay_round:
                 g = self._replayed(b)
-                if bk.pend[b] > 0 and stores:
+                if bk.pend[b] > bk.pend_hi and stores:               # (pend_hi = 0 unless the advance is deferred)
                     self.slots[(cur + 1) % 3, b] = g                 # snapshot h_j
                 if replay_round and tok0 > 0:                        # the round's earlier tokens, again, no outputs
-                    zeros_c = np.zeros((1, tok0, self.G, self.N))
-                    _, snap0 = scan_tokens(self.a_mode, g[None], self.win_xc[npar_, b:b + 1, :tok0], self.win_dt[npar_, b:b + 1, :tok0],
-                                           self.win_B[npar_, b:b + 1, :tok0], zeros_c, self.A, self.D)
-                    g = snap0[tok0, 0]
+                    g = self._scan_window(b, g, tok0, of_round=True)
             else:
                 g = self.slots[(cur + 2) % 3, b]                     # where the earlier calls of the round stopped
             yb, snap = scan_tokens(self.a_mode, g[None], xc[b:b + 1], dt[b:b + 1], Bm[b:b + 1], Cm[b:b + 1],
                                    self.A, self.D)
             y[b] = yb[0]
-            if not self.hj_only and stores:
+            if not (self.hj_only or self.defer) and stores:
                 self.slots[(cur + 2) % 3, b] = snap[k, 0]            # snapshot h_k
-        npar = bk.win_par ^ 1
-        self.win_xc[npar, :, tok0:tok0 + k] = xc
-        self.win_dt[npar, :, tok0:tok0 + k] = dt
-        self.win_B[npar, :, tok0:tok0 + k] = Bm
+        for b in range(self.batch):
+            half, idx = self._entries(b, tok0, k, of_round=True)
+            self.win_xc[half, b, idx] = xc[b]
+            self.win_dt[half, b, idx] = dt[b]
+            self.win_B[half, b, idx] = Bm[b]
         bk.verify(k, tok0)
         return y, xc
 

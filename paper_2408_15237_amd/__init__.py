@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     ssmv_materialize, ssmv_first_conflict, ssmv_gated_rmsnorm, ssmv_check, ssmv_set_tuning, ssmv_copy_probe, ssmv_version,
     SSMV_OK, SSMV_EINVAL, SSMV_EUNSUPPORTED, SSMV_EALIGN, SSMV_ESEQUENCE, SSMV_EHIP,
     SSMV_F32, SSMV_BF16, SSMV_A_SCALAR, SSMV_A_DIAG, SSMV_ACT_NONE, SSMV_ACT_SILU,
-    SSMV_SNAP_BOTH, SSMV_SNAP_HJ_ONLY,
+    SSMV_SNAP_BOTH, SSMV_SNAP_HJ_ONLY, SSMV_SNAP_DEFER, SSMV_WINDOW,
     SSMV_KMAX_LIMIT, SSMV_CONV_WIDTH, SSMV_CACHE_NPTR,
 )

@@ -19,7 +19,8 @@ SSMV_OK, SSMV_EINVAL, SSMV_EUNSUPPORTED, SSMV_EALIGN, SSMV_ESEQUENCE, SSMV_EHIP 
 SSMV_F32, SSMV_BF16 = 0, 1
 SSMV_A_SCALAR, SSMV_A_DIAG = 0, 1
 SSMV_ACT_NONE, SSMV_ACT_SILU = 0, 1
-SSMV_SNAP_BOTH, SSMV_SNAP_HJ_ONLY = 0, 1
+SSMV_SNAP_BOTH, SSMV_SNAP_HJ_ONLY, SSMV_SNAP_DEFER = 0, 1, 2
+SSMV_WINDOW = 16
 SSMV_KMAX_LIMIT = 16
 SSMV_CONV_WIDTH = 4
 SSMV_CACHE_NPTR = 15
@@ -27,7 +28,7 @@ SSMV_CACHE_NPTR = 15
 IO_CODES = {"f32": SSMV_F32, "bf16": SSMV_BF16}
 MODE_CODES = {"scalar": SSMV_A_SCALAR, "diag": SSMV_A_DIAG}
 ACT_CODES = {"none": SSMV_ACT_NONE, "silu": SSMV_ACT_SILU}
-SNAP_CODES = {"both": SSMV_SNAP_BOTH, "hj_only": SSMV_SNAP_HJ_ONLY}
+SNAP_CODES = {"both": SSMV_SNAP_BOTH, "hj_only": SSMV_SNAP_HJ_ONLY, "defer": SSMV_SNAP_DEFER}
 SSMV_ENGINE_AUTO, SSMV_ENGINE_VECTOR = 0, 1
 ENGINE_CODES = {"auto": SSMV_ENGINE_AUTO, "vector": SSMV_ENGINE_VECTOR}
 

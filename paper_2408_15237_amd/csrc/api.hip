@@ -42,8 +42,11 @@ int check_dims(const ssmv_dims *d)
     if (d->io_dtype != SSMV_F32 && d->io_dtype != SSMV_BF16) return fail(SSMV_EINVAL, "io_dtype %d unknown", d->io_dtype);
     if (d->a_mode != SSMV_A_SCALAR && d->a_mode != SSMV_A_DIAG) return fail(SSMV_EINVAL, "a_mode %d unknown", d->a_mode);
     if (d->conv_act != SSMV_ACT_NONE && d->conv_act != SSMV_ACT_SILU) return fail(SSMV_EINVAL, "conv_act %d unknown", d->conv_act);
-    if (d->snapshot_mode != SSMV_SNAP_BOTH && d->snapshot_mode != SSMV_SNAP_HJ_ONLY)
+    if (d->snapshot_mode != SSMV_SNAP_BOTH && d->snapshot_mode != SSMV_SNAP_HJ_ONLY && d->snapshot_mode != SSMV_SNAP_DEFER)
         return fail(SSMV_EINVAL, "snapshot_mode %d unknown", d->snapshot_mode);
+    if (d->snapshot_mode == SSMV_SNAP_DEFER && 2 * d->kmax > SSMV_WINDOW)
+        return fail(SSMV_EUNSUPPORTED, "SSMV_SNAP_DEFER keeps two rounds in a window of %d tokens: kmax %d > %d", SSMV_WINDOW, d->kmax,
+                    SSMV_WINDOW / 2);
     if (d->engine != SSMV_ENGINE_AUTO && d->engine != SSMV_ENGINE_VECTOR) return fail(SSMV_EINVAL, "engine %d unknown", d->engine);
     if (d->nheads % d->ngroups != 0) return fail(SSMV_EINVAL, "nheads %d not a multiple of ngroups %d", d->nheads, d->ngroups);
     if ((long)d->conv_channels != (long)d->nheads * d->headdim)
@@ -76,7 +79,14 @@ int check_dims(const ssmv_dims *d)
 }
 
 // Largest number of pending tokens a verify may meet.
-int pend_max_of(const ssmv_dims *d) { return d->snapshot_mode == SSMV_SNAP_HJ_ONLY ? d->kmax : d->kmax - 1; }
+int pend_max_of(const ssmv_dims *d)
+{
+    if (d->snapshot_mode == SSMV_SNAP_DEFER) return SSMV_WINDOW - d->kmax;
+    return d->snapshot_mode == SSMV_SNAP_HJ_ONLY ? d->kmax : d->kmax - 1;
+}
+// A verify stores h_j, and its commit moves the live slot there, iff it meets more pending tokens than this.  With a
+// deferred advance: as long as pend + (accepted <= kmax) + (next k <= kmax) still fits the window, nothing is stored.
+int pend_hi_of(const ssmv_dims *d) { return d->snapshot_mode == SSMV_SNAP_DEFER ? SSMV_WINDOW - 2 * d->kmax : 0; }
 
 // Whether the caches of these dimensions keep their state slots in 16x16 tiles (state_off4) and their verify launches run
 // on the matrix cores: scalar-A mode, bf16 tokens, a shape that kernel is built for, and never more than 16 tokens
@@ -172,8 +182,16 @@ void fill_verify(VerifyParams &p, const ssmv_dims *d, const ssmv_cache *c)
     p.io = d->io_dtype;
     p.state = c->state;
     p.slot_stride = (size_t)d->batch * d->nheads * d->headdim * d->dstate;
-    for (int i = 0; i < 2; ++i) { p.win_xc[i] = c->win_xc[i]; p.win_dt[i] = c->win_dt[i]; p.win_B[i] = c->win_B[i]; }
-    p.cur_slot = c->cur_slot; p.pend = c->pend; p.last_k = c->last_k; p.win_par = c->win_par;
+    p.win_ring = d->snapshot_mode == SSMV_SNAP_DEFER;
+    p.win_tokens = p.win_ring ? SSMV_WINDOW : d->kmax;
+    // (the ring is the first array of each pair; the kernels pick "the half" by the window parity and find the same array)
+    for (int i = 0; i < 2; ++i) {
+        const int j = p.win_ring ? 0 : i;
+        p.win_xc[i] = c->win_xc[j]; p.win_dt[i] = c->win_dt[j]; p.win_B[i] = c->win_B[j];
+    }
+    p.pend_max = pend_max_of(d);
+    p.pend_hi = pend_hi_of(d);
+    p.cur_slot = c->cur_slot; p.pend = c->pend; p.last_k = c->last_k; p.win_par = c->win_par; p.pos = c->pos;
     p.ring = c->conv_ring; p.conv_head = c->conv_head; p.ring_len = d->ring_len; p.conv_act = d->conv_act;
     p.tiled = state_tiled(d);
 }
@@ -221,9 +239,16 @@ int ssmv_cache_sizes(const ssmv_dims *d, size_t out_bytes[SSMV_CACHE_NPTR])
     size_t *o = out_bytes;
     o[0] = 3 * B * H * P * N * sizeof(float);
     o[1] = B * d->ring_len * Cx * e;
-    o[2] = o[3] = B * K * Cx * e;
-    o[4] = o[5] = B * K * H * e;
-    o[6] = o[7] = B * K * G * N * e;
+    if (d->snapshot_mode == SSMV_SNAP_DEFER) {   // one ring of SSMV_WINDOW entries per sequence; the second arrays are not used
+        o[2] = B * SSMV_WINDOW * Cx * e;
+        o[4] = B * SSMV_WINDOW * H * e;
+        o[6] = B * SSMV_WINDOW * G * N * e;
+        o[3] = o[5] = o[7] = 256;
+    } else {
+        o[2] = o[3] = B * K * Cx * e;
+        o[4] = o[5] = B * K * H * e;
+        o[6] = o[7] = B * K * G * N * e;
+    }
     o[8] = B * sizeof(int32_t);   // cur_slot
     o[9] = B * sizeof(int32_t);   // pend
     o[10] = B * sizeof(int64_t);  // pos
@@ -286,8 +311,8 @@ static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const ssmv_ste
     const bool replay = a->replay_round == 1;
     if (replay && (!state_tiled(d) || g_tune_rows.load() != 0 || g_tune_waves.load() != 0))
         return fail(SSMV_EUNSUPPORTED, "replay_round needs the matrix-core engine (see ssmv_engine_of) and no forced launch shape");
-    if (a->tok0 > 0 && !replay && d->snapshot_mode == SSMV_SNAP_HJ_ONLY)
-        return fail(SSMV_EUNSUPPORTED, "a round fed by several calls needs the h_k slot (not with SSMV_SNAP_HJ_ONLY) unless replay_round = 1");
+    if (a->tok0 > 0 && !replay && d->snapshot_mode != SSMV_SNAP_BOTH)
+        return fail(SSMV_EUNSUPPORTED, "a round fed by several calls needs the h_k slot (SSMV_SNAP_BOTH) unless replay_round = 1");
     if (a->tok0 > 0 && a->k_seq)
         return fail(SSMV_EUNSUPPORTED, "ragged draft counts in a round fed by several calls (a sequence's window entries would not be contiguous)");
     if (a->dt_softplus != 0 && a->dt_softplus != 1) return fail(SSMV_EINVAL, "dt_softplus %d not in {0,1}", a->dt_softplus);
@@ -323,8 +348,7 @@ static int verify_common(const ssmv_dims *d, const ssmv_cache *c, const ssmv_ste
     p.dt_bias = a->dt_bias;
     p.z = a->z;
     p.k_seq = a->k_seq;
-    p.pend_max = pend_max_of(d);
-    p.write_hk = d->snapshot_mode != SSMV_SNAP_HJ_ONLY;
+    p.write_hk = d->snapshot_mode == SSMV_SNAP_BOTH;
     p.lds_tokens = ((a->tok0 > 0 && !replay) ? 0 : p.pend_max) + p.replay_tok + k;
     p.xc = a->xc; p.dt = a->dt; p.Bm = a->Bm; p.Cm = a->Cm; p.A = a->A; p.D = a->D; p.y = a->y_out; p.h_out = nullptr;
     p.x_raw = a->x_raw; p.wgt = a->conv_wgt; p.bias = a->conv_bias;
@@ -380,7 +404,6 @@ int ssmv_materialize_block(const ssmv_dims *d, const ssmv_cache *c, const float 
     p.pend_mask = ~0;
     p.dt_softplus = dt_softplus;
     p.dt_bias = dt_bias;
-    p.pend_max = pend_max_of(d);
     p.write_hk = 0;
     p.lds_tokens = p.pend_max > 0 ? p.pend_max : 1;
     p.A = A; p.D = A;   // D is not read when k == 0
@@ -466,7 +489,8 @@ int ssm_commit_rollback_multi(const ssmv_dims *d, const ssmv_cache *caches, int3
     for (int first = 0; first < n_caches; first += kCommitMaxCaches) {
         CommitParams p{};
         p.batch = d->batch; p.R = d->ring_len; p.accepted = accepted;
-        p.hj_only = d->snapshot_mode == SSMV_SNAP_HJ_ONLY;
+        p.mode = d->snapshot_mode;
+        p.pend_hi = pend_hi_of(d);
         p.n_caches = n_caches - first < kCommitMaxCaches ? n_caches - first : kCommitMaxCaches;
         for (int i = 0; i < p.n_caches; ++i) {
             const ssmv_cache &c = caches[first + i];

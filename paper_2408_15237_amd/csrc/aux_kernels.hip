@@ -106,7 +106,15 @@ __global__ __launch_bounds__(256) void commit_kernel(const CommitParams p)
         *c.err_flag = 1;
         a = a < 0 ? 0 : lk;
     }
-    if (a == lk && !p.hj_only) {         // every draft accepted: h_k becomes the live state
+    if (p.mode == SSMV_SNAP_DEFER) {     // deferred advance: the live slot moves only when the verify stored h_j
+        if (pd > p.pend_hi) {
+            c.cur_slot[b] = (cur + 1) % 3;
+            c.pos[b] = pos + pd;
+            c.pend[b] = a;
+        } else {
+            c.pend[b] = pd + a;
+        }
+    } else if (a == lk && p.mode == SSMV_SNAP_BOTH) {   // every draft accepted: h_k becomes the live state
         c.cur_slot[b] = (cur + 2) % 3;
         c.pos[b] = pos + pd + a;
         c.pend[b] = 0;

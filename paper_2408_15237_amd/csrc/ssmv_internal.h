@@ -18,8 +18,12 @@ struct VerifyParams {
     int rows_wg;         // state rows one workgroup owns
     int tiles;           // scalar mode: tiles per head; diag mode: tiles per sequence
     int lds_tokens;      // tokens the dynamic LDS was sized for (pend_max + k)
-    int pend_max;        // largest legal pend: kmax-1, or kmax when h_k is never stored
-    int write_hk;        // 0: SSMV_SNAP_HJ_ONLY
+    int pend_max;        // largest legal pend: kmax-1, kmax when h_k is never stored, SSMV_WINDOW-kmax with a deferred advance
+    int pend_hi;         // h_j is stored (and the commit moves the live slot there) iff pend > pend_hi; 0 unless SSMV_SNAP_DEFER
+    int write_hk;        // 1: SSMV_SNAP_BOTH
+    int win_ring;        // 1 (SSMV_SNAP_DEFER): the window is ONE ring of SSMV_WINDOW entries per sequence (both "halves" point
+                         // to it), token q of the sequence at entry q % SSMV_WINDOW; 0: two halves of kmax entries
+    int win_tokens;      // window entries per sequence and array: SSMV_WINDOW or kmax
     int tok0;            // tokens earlier calls have already fed to this round (0: first call)
     int pend_mask;       // tok0 > 0 ? 0 : ~0  (a later call replays nothing)
     int src_add;         // tok0 > 0 ? 2 : 0   (a later call continues in the h_k slot)
@@ -46,6 +50,7 @@ struct VerifyParams {
     const int32_t *pend;
     int32_t *last_k;
     const int32_t *win_par;
+    const int64_t *pos;  // read with win_ring only
     // round inputs / outputs
     const void *xc, *dt, *Bm, *Cm;
     const float *A, *D;
@@ -90,7 +95,9 @@ struct CacheInts {
 constexpr int kCommitMaxCaches = 32;     // caches one commit launch covers (kernel argument space)
 
 struct CommitParams {
-    int batch, R, n_caches, hj_only;
+    int batch, R, n_caches;
+    int mode;                // SSMV_SNAP_*
+    int pend_hi;             // SSMV_SNAP_DEFER: the live slot moves iff pend > pend_hi
     const int32_t *accepted;
     CacheInts c[kCommitMaxCaches];
 };

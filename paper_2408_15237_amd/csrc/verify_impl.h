@@ -144,6 +144,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const int pd = min(max(p.pend[b], 0), p.pend_max) & (EXTRA ? p.pend_mask : ~0);
     const int src_slot = EXTRA ? (cur + p.src_add) % 3 : cur;
     const int par = p.win_par[0] & 1;
+    // deferred advance: the window is a ring per sequence, token q of the sequence at entry q % 16, the first pending one
+    // is token pos[b]; h_j is stored only when more than pend_hi tokens are pending (pend_hi = 0 otherwise)
+    const int wp = (int)p.pos[b] & (SSMV_WINDOW - 1);
+    const bool wring = p.win_ring != 0;
+    auto slot_in = [&](int tt) { return wring ? (wp + tt) & (SSMV_WINDOW - 1) : tt; };               // pending token tt
+    auto slot_out = [&](int t) { return wring ? (wp + pd + t) & (SSMV_WINDOW - 1) : t0 + t; };       // token t of this call
 
     // ---- state loads first: uniform base pointer + 32-bit lane offsets -------------------------------
     v4f h[R][V];
@@ -210,7 +216,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const bool writes_B = !materialize && first_tile && first_head_of_group;
     const int ch0 = DIAG ? row0 : hd * p.P + row0;       // first x / conv channel of this workgroup
     const int dth0 = DIAG ? row0 : hd;                   // first dt entry of this workgroup
-    const size_t tok_in = (size_t)b * k, tok_win = (size_t)b * p.kmax;   // first token row of this sequence
+    const size_t tok_in = (size_t)b * k, tok_win = (size_t)b * p.win_tokens;   // first token row of this sequence
     // pending window (read: half `par`; written: the other half) and this round's inputs
     const void *winB = p.win_B[par];
     void *winB_out = p.win_B[par ^ 1];
@@ -226,7 +232,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     auto m24 = [](int a, int b_) { return __mul24(a, b_); };
     const size_t ring_b = (size_t)b * p.ring_len * HP + ch0;            // this sequence's ring rows, this workgroup's channels
     const int ring_mask = p.ring_len - 1;
-    const size_t oB_wout = oB_win + (size_t)t0 * GN, oX_wout = oX_win + (size_t)t0 * HP, oDt_wout = oDt_win + (size_t)t0 * H;
     // optional softplus(dt + dt_bias) ahead of the discretisation (Section 2.2: dt is the positive step)
     const float dtb_h = (EXTRA && !DIAG && p.dt_bias) ? p.dt_bias[hd] : 0.f;
     auto dt_fix = [&](float d, float bias) {
@@ -278,7 +283,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     auto b_load = [&](const BReq &q) {                   // B of token tt (pending window or this round's input)
         uint4 r = make_uint4(0, 0, 0, 0);
         const bool old = q.tt < pd;
-        if (q.on) r = Vec::load_raw(old ? winB : p.Bm, (old ? oB_win + m24(q.tt, GN) : oB_in + m24(q.tt - pd, GN)) + q.n);
+        if (q.on) r = Vec::load_raw(old ? winB : p.Bm, (old ? oB_win + m24(slot_in(q.tt), GN) : oB_in + m24(q.tt - pd, GN)) + q.n);
         return r;
     };
     auto c_load = [&](const BReq &q) {
@@ -299,7 +304,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         // the [batch][k][channels] layout.  Two exclusive branches with a load each would share registers and
         // make the second wait for the first.
         const bool fresh = CONV && !old;
-        r.x = XV::load(fresh ? p.x_raw : (old ? winX : p.xc), (old ? oX_win + m24(q.tt, HP) : oX_in + m24(t, HP)) + q.i);
+        r.x = XV::load(fresh ? p.x_raw : (old ? winX : p.xc), (old ? oX_win + m24(slot_in(q.tt), HP) : oX_in + m24(t, HP)) + q.i);
         if (fresh) {
             // older taps from earlier inputs of the round or the ring
 #pragma unroll
@@ -312,13 +317,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             r.wv = Vec::load_raw(p.wgt, (size_t)(ch0 + q.i) * W);           // XW channels x W taps = 16 bytes
             r.bias = p.bias ? XV::load(p.bias, ch0 + q.i) : XV::zero();
         }
-        if constexpr (DIAG) r.dt = XV::load(old ? winDt : p.dt, (old ? oDt_win + m24(q.tt, H) : oDt_in + m24(t, H)) + q.i);
+        if constexpr (DIAG) r.dt = XV::load(old ? winDt : p.dt, (old ? oDt_win + m24(slot_in(q.tt), H) : oDt_in + m24(t, H)) + q.i);
         if (gated && !old) r.z = XV::load(p.z, oX_in + m24(t, HP) + q.i);
         return r;
     };
     auto b_use = [&](const BReq &q, uint4 raw) {
         if (!q.on) return;
-        if (q.tt >= pd && writes_B) Vec::store_raw(winB_out, oB_wout + m24(q.tt - pd, GN) + q.n, raw);
+        if (q.tt >= pd && writes_B) Vec::store_raw(winB_out, oB_win + m24(slot_out(q.tt - pd), GN) + q.n, raw);
         float v[EV];
         Vec::decode(raw, v);
 #pragma unroll
@@ -375,8 +380,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
 #pragma unroll
         for (int e = 0; e < XW; ++e) Dv[e] = DIAG ? p.D[row0 + q.i + e] : D_h;
         if (t >= 0 && !materialize) {
-            XV::store(winX_out, oX_wout + m24(t, HP) + q.i, xbits);
-            if (DIAG) XV::store(winDt_out, oDt_wout + m24(t, H) + q.i, r.dt);      // the raw dt: replay applies dt_fix again
+            XV::store(winX_out, oX_win + m24(slot_out(t), HP) + q.i, xbits);
+            if (DIAG) XV::store(winDt_out, oDt_win + m24(slot_out(t), H) + q.i, r.dt);      // the raw dt: replay applies dt_fix again
         }
 #pragma unroll
         for (int e = 0; e < XW; ++e) {
@@ -387,10 +392,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     };
     auto dec_load = [&](int tt) {                        // scalar mode: dt of token tt for the decay factor
         const bool old = tt < pd || T == 0;
-        return Vec::load_raw1(old ? winDt : p.dt, old ? oDt_win + m24(tt, H) : oDt_in + m24(tt - pd, H));
+        return Vec::load_raw1(old ? winDt : p.dt, old ? oDt_win + m24(slot_in(tt), H) : oDt_in + m24(tt - pd, H));
     };
     auto dec_use = [&](int tt, uint32_t raw) {
-        if (tt >= pd && first_tile && !materialize) Vec::store_raw1(winDt_out, oDt_wout + m24(tt - pd, H), raw);
+        if (tt >= pd && first_tile && !materialize) Vec::store_raw1(winDt_out, oDt_win + m24(slot_out(tt - pd), H), raw);
         const float d = dt_fix(Vec::decode1(raw), dtb_h);
         sDtF[tt] = d;
     };
@@ -438,8 +443,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
             if (row0 + i < rows_dom) {
                 const size_t dti = DIAG ? i : 0;
                 if (t < 0) {
-                    xv = load_io(winX, oX_win + tt * HP + i, IO);
-                    dtv = load_io(winDt, oDt_win + tt * H + dti, IO);
+                    xv = load_io(winX, oX_win + slot_in(tt) * HP + i, IO);
+                    dtv = load_io(winDt, oDt_win + slot_in(tt) * H + dti, IO);
                 } else {
                     if constexpr (CONV) {
                         float s = p.bias ? load_io(p.bias, ch0 + i, IO) : 0.f;
@@ -459,8 +464,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
                     }
                     dtv = load_io(p.dt, oDt_in + t * H + dti, IO);
                     if (!materialize) {
-                        store_io(winX_out, oX_wout + t * HP + i, xv, IO);
-                        if (DIAG) store_io(winDt_out, oDt_wout + t * H + dti, dtv, IO);
+                        store_io(winX_out, oX_win + slot_out(t) * HP + i, xv, IO);
+                        if (DIAG) store_io(winDt_out, oDt_win + slot_out(t) * H + dti, dtv, IO);
                     }
                 }
                 dtv = DIAG ? dt_fix(dtv, dt_bias_of(row0 + i)) : 1.f;
@@ -597,7 +602,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         return;
     }
     // (ii) snapshot h_j
-    if (pd > 0) store_state(p.state + (size_t)((cur + 1) % 3) * p.slot_stride, true);
+    if (pd > p.pend_hi) store_state(p.state + (size_t)((cur + 1) % 3) * p.slot_stride, true);
     // (iii) the k draft tokens
     for (int t = 0; t < kb; ++t) {
         advance(pd + t);

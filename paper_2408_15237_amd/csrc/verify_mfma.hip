@@ -121,24 +121,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     // tok0 > 0: a later call of a round that an earlier call began (draft side, Section 4.3): continue from the h_k slot,
     // in place, replay nothing, append to the round's stash and ring behind the tok0 earlier tokens.
     const int t0 = EXTRA ? p.tok0 : 0;
-    const int cur = (int)((unsigned)p.cur_slot[b] % 3u);
-    const int pd = min(max(p.pend[b], 0), p.pend_max) & (EXTRA ? p.pend_mask : ~0);
+    // every data-dependent scalar is requested here, ahead of the first use of any of them: scalar loads return out of
+    // order, so the first use waits for all that have been issued - left to itself the compiler issues some of them behind
+    // that wait, and each such level is one more round trip to memory at the head of the launch
+    // (readfirstlane: free for a value that already sits in a scalar register, and it keeps the constraint below legal in
+    // builds where a store ahead of these loads turns them into vector loads)
+    auto uni = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
+    int cur_raw = uni(p.cur_slot[b]), pd_raw = uni(p.pend[b]), par_raw = uni(p.win_par[0]);
+    int pos_raw = uni(reinterpret_cast<const int *>(p.pos)[2 * b]);       // the low half: only pos % 16 is needed
+    int A_bits = uni(__float_as_int(p.A[hd])), D_bits = uni(__float_as_int(p.D[hd]));
+    int ch_raw = 0, ks_raw = k, dtb_bits = 0;
+    if constexpr (CONV) ch_raw = uni(p.conv_head[b]);
+    if constexpr (EXTRA) {
+        if (p.k_seq) ks_raw = uni(p.k_seq[b]);
+        if (p.dt_bias) dtb_bits = uni(__float_as_int(p.dt_bias[hd]));
+    }
+    asm volatile("" : "+s"(cur_raw), "+s"(pd_raw), "+s"(par_raw), "+s"(pos_raw), "+s"(A_bits), "+s"(D_bits), "+s"(ch_raw), "+s"(ks_raw), "+s"(dtb_bits));
+    const float A_raw = __int_as_float(A_bits), D_h = __int_as_float(D_bits), dtb_h = __int_as_float(dtb_bits);
+    const int cur = (int)((unsigned)cur_raw % 3u);
+    const int pd = min(max(pd_raw, 0), p.pend_max) & (EXTRA ? p.pend_mask : ~0);
     const int src_slot = EXTRA ? (cur + p.src_add) % 3 : cur;
-    const int par = p.win_par[0] & 1;
-    int kb = k;
-    if constexpr (EXTRA) if (p.k_seq) kb = min(max(p.k_seq[b], 1), k);
+    const int par = par_raw & 1;
+    // deferred advance: the window is a ring per sequence, token q of the sequence at entry q % 16, the first pending one
+    // is token pos[b]; h_j is stored only when more than pend_hi tokens are pending (pend_hi = 0 otherwise)
+    const int wp = pos_raw & (SSMV_WINDOW - 1);
+    const bool adv = pd > p.pend_hi;
+    const int kb = min(max(ks_raw, 1), k);
     // replayed round (Section 4.3, the draft model's recomputation): the pe tokens that earlier calls fed to this round are
     // taken again out of the round's own half of the window, behind the pending ones and ahead of this call's
     const int pe = EXTRA ? p.replay_tok : 0;
     const int pq = pd + pe;                              // tokens that come out of the stash
     const int T = pq + kb;                               // <= 16: the host launches this kernel only if pend_max + kmax <= 16
-    // per-head parameters: read here, as scalar loads beside the bookkeeping (further down they would become vector loads
-    // queued behind the state)
-    const float A2 = p.A[hd] * 1.4426950408889634f, D_h = p.D[hd];
-    float dtb_h = 0.f;
-    if constexpr (EXTRA) if (p.dt_bias) dtb_h = p.dt_bias[hd];
-    int conv_head = 0;
-    if constexpr (CONV) conv_head = (p.conv_head[b] + t0) & (p.ring_len - 1);      // newest raw input fed so far
+    const float A2 = A_raw * 1.4426950408889634f;
+    const int conv_head = (ch_raw + t0) & (p.ring_len - 1);      // newest raw input fed so far
 
     int grp = 0;
     bool first_head_of_group = true;
@@ -150,15 +165,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const bool first_tile = tile == 0;
     const bool writes_B = first_tile && first_head_of_group;
     const int ch0 = hd * P + tile * RW;                  // first channel of this workgroup
-    const size_t tok_in = (size_t)b * k, tok_win = (size_t)b * p.kmax;
+    const size_t tok_in = (size_t)b * k, tok_win = (size_t)b * p.win_tokens;
     // both halves of the window are kernel arguments; a select, not an indexed load that would wait for `par`
     auto half = [&](void *const (&w2)[2], int which) { return static_cast<uint16_t *>(which ? w2[1] : w2[0]); };
     const uint16_t *winB = half(p.win_B, par), *winX = half(p.win_xc, par), *winDt = half(p.win_dt, par);
     uint16_t *winB_out = half(p.win_B, par ^ 1), *winX_out = half(p.win_xc, par ^ 1), *winDt_out = half(p.win_dt, par ^ 1);
     // token tt < pd: pending, half `par`, entry tt; pd <= tt < pq: fed earlier to this round, the other half, entry tt - pd
+    // (ring: both halves are the one ring, entry (wp + tt) % 16)
     auto stashed = [&](const uint16_t *cur_half, const uint16_t *round_half, size_t o_win, int tt, int stride) {
-        return tt < pd ? cur_half + o_win + (size_t)tt * stride : round_half + o_win + (size_t)(tt - pd) * stride;
+        const int e = p.win_ring ? (wp + tt) & (SSMV_WINDOW - 1) : (tt < pd ? tt : tt - pd);
+        return (tt < pd ? cur_half : round_half) + o_win + (size_t)e * stride;
     };
+    // window entry that token j of this call goes to
+    auto out_entry = [&](int j) { return p.win_ring ? (wp + pq + j) & (SSMV_WINDOW - 1) : t0 + j; };
     const uint16_t *Bmp = static_cast<const uint16_t *>(p.Bm), *Cmp = static_cast<const uint16_t *>(p.Cm);
     const uint16_t *dtp = static_cast<const uint16_t *>(p.dt);
     const uint16_t *xin = static_cast<const uint16_t *>(CONV ? p.x_raw : p.xc);
@@ -166,7 +185,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const size_t oB_win = tok_win * GN + (size_t)grp * N, oB_in = tok_in * GN + (size_t)grp * N;
     const size_t oX_win = tok_win * HP + ch0, oX_in = tok_in * HP + ch0;
     const size_t oDt_win = tok_win * H + hd, oDt_in = tok_in * H + hd;
-    const size_t oB_wout = oB_win + (size_t)t0 * GN, oX_wout = oX_win + (size_t)t0 * HP, oDt_wout = oDt_win + (size_t)t0 * H;
     const size_t ring_b = (size_t)b * p.ring_len * HP + ch0;
     const int ring_mask = p.ring_len - 1;
 
@@ -272,7 +290,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
                 if (r < nrow) {
                     *reinterpret_cast<u4v *>(dst + r * CS + 8 * (l % CB)) = bk[it];
                     if (w == 1 && writes_B && r >= pq)
-                        *reinterpret_cast<u4v *>(winB_out + oB_wout + (size_t)(r - pq) * GN + 8 * (l % CB)) = bk[it];
+                        *reinterpret_cast<u4v *>(winB_out + oB_win + (size_t)out_entry(r - pq) * GN + 8 * (l % CB)) = bk[it];
                 }
             }
         }
@@ -304,7 +322,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     const float cy = lane_get(cum, min(pq + (int)li, 15));   // draft li is token pq + li
     const float alphaY = __builtin_amdgcn_exp2f(cy);
     if (w == 0 && first_tile) {
-        if (g == 0 && (int)li >= pq && (int)li < T) winDt_out[oDt_wout + (size_t)(li - pq) * H] = (uint16_t)dt_raw;   // the raw dt: replay transforms it again
+        if (g == 0 && (int)li >= pq && (int)li < T) winDt_out[oDt_win + (size_t)out_entry(li - pq) * H] = (uint16_t)dt_raw;   // the raw dt: replay transforms it again
         if (hd == 0 && tid == 0) p.last_k[b] = t0 + kb;
     }
     __syncthreads();
@@ -350,7 +368,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
                             }
                             bits = pack_bf16x2(s0, s1);
                         }
-                        if (j >= 0) reinterpret_cast<uint32_t *>(winX_out + oX_wout + (size_t)j * HP)[cp] = bits;
+                        if (j >= 0) reinterpret_cast<uint32_t *>(winX_out + oX_win + (size_t)out_entry(j) * HP)[cp] = bits;
                         outA |= (bits & 0xffffu) << (16 * e);
                         outB |= (bits >> 16) << (16 * e);
                     }
@@ -411,10 +429,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     }
     __syncthreads();
     SSMV_TP(4);
-#ifdef SSMV_TRACE
+    // Every wave of the workgroup has its whole share of the state before any of them starts to store: a wave that stores
+    // its first tile while the loads of its second one (or of its neighbours) are still under way makes the launch 1-2 %
+    // slower (measured; reads and writes mixed finely are served worse than a read phase followed by a write phase).
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     SSMV_TP(5);
-#endif
+    __builtin_amdgcn_s_barrier();
 
     // ---- the products, tile by tile ------------------------------------------------------------------------------------------
     float *dstJ = p.state + (size_t)((cur + 1) % 3) * p.slot_stride + head_base + st_off;
@@ -443,13 +463,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
         }
         // (a call of a replayed round that is not its last needs the outputs only: no snapshot is formed)
         if (!EXTRA || p.store_state) {
-            // (i) + (ii): fold the pending tokens in and store the snapshot h_j
-            if (pd > 0) {
+            // (i) + (ii): fold the pending tokens in and store the snapshot h_j (a deferred advance stores it only when the
+            // window is about to fill up; until then it is needed, unstored, as the start of h_k or not at all)
+            if (adv || (pd > 0 && p.write_hk)) {
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) {
                     const bf8 Aw = row16(sWj + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1));
                     st[i][q] = mfma16(Aw, Xop, st[i][q] * alphaJ);
-                    __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstJ + ((i * NQ + q) << 8)));
+                    if (adv) __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstJ + ((i * NQ + q) << 8)));
                 }
             }
             // (iii) + (iv): the drafts, and the snapshot h_k (Algorithm 2), unless every accepted token is to stay pending

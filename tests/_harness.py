@@ -54,6 +54,16 @@ def to_host(t) -> np.ndarray:
     return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
 
 
+def untile_state(t):
+    """A (..., P, N) view of raw slot memory of the matrix-core engine -> the (..., P, N) state it stands for.  Inside a
+    (sequence, head) block, tile (p/16, n/16) is 256 consecutive floats and the four floats n%16 in [4g, 4g+4) of row
+    p%16 are the float4 number 16 g + p%16 of the tile."""
+    lead, (P, N) = t.shape[:-2], t.shape[-2:]
+    v = t.reshape(*lead, P // 16, N // 16, 4, 16, 4)          # tile row, tile column, g, p%16, n%4
+    n = len(lead)
+    return v.permute(*range(n), n, n + 3, n + 1, n + 2, n + 4).reshape(*lead, P, N)
+
+
 def dims_of(wl: Workload):
     return ssmv.make_dims(wl.batch, wl.nheads, wl.headdim, wl.dstate, ngroups=wl.ngroups, kmax=wl.kmax_eff,
                           ring_len=wl.ring_len, io=wl.io, a_mode=wl.a_mode, conv_act=wl.conv_act,
@@ -100,7 +110,15 @@ class HipLayer:
     def stashed_xc(self, k):
         """This round's conv outputs as the verify kernel stashed them (the half that commit makes current)."""
         wl = self.wl
-        par = self.cache.ints()["win_par"]
+        ints = self.cache.ints()
+        if wl.snapshot_mode == "defer":                   # one ring per sequence: token q of the sequence at entry q % 16
+            Wn = ssmv.SSMV_WINDOW
+            n = wl.batch * Wn * wl.conv_channels
+            t = self.cache.buffers["win_xc0"].view(TORCH_IO[wl.io])[:n].view(wl.batch, Wn, wl.conv_channels)
+            first = ints["pos"] + ints["pend"]
+            idx = torch.from_numpy(np.stack([(int(first[b]) + np.arange(k)) % Wn for b in range(wl.batch)])).to("cuda")
+            return torch.gather(t, 1, idx[:, :, None].expand(-1, -1, wl.conv_channels)).clone()
+        par = ints["win_par"]
         buf = self.cache.buffers["win_xc%d" % (par ^ 1)]
         n = wl.batch * wl.kmax_eff * wl.conv_channels
         t = buf.view(TORCH_IO[wl.io])[:n].view(wl.batch, wl.kmax_eff, wl.conv_channels)
@@ -128,7 +146,7 @@ def run_parity(wl: Workload, data: WorkloadData, layer: int = 0, x_override=None
     tol = TOL[wl.io]
     hip = HipLayer(wl, lp, conv_init=conv_init)
     ora = eager_oracle(wl, lp, conv_init=conv_init)
-    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width, hj_only=wl.snapshot_mode == "hj_only")
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width, mode=wl.snapshot_mode, kmax=wl.kmax_eff)
     worst = {"y": 0.0, "xc": 0.0, "h": 0.0, "y_max": 0.0, "h_max": 0.0}
     for i, rd in enumerate(data.rounds):
         x_raw = rd.x_raw if x_override is None else x_override[i]

@@ -46,6 +46,8 @@ def test_engine_choice_is_a_function_of_the_dimensions():
     assert ssmv.ssmv_engine_of(mk(32, 32, 128, 64, kmax=9, io="bf16")) == 0                           # 8 + 9 tokens in a launch
     assert ssmv.ssmv_engine_of(mk(32, 32, 128, 64, kmax=8, io="bf16", snapshot_mode="hj_only")) == 1  # 8 + 8
     assert ssmv.ssmv_engine_of(mk(32, 32, 128, 64, kmax=9, io="bf16", snapshot_mode="hj_only")) == 0
+    assert ssmv.ssmv_engine_of(mk(32, 32, 128, 64, kmax=4, io="bf16", snapshot_mode="defer")) == 1    # 12 + 4
+    assert ssmv.ssmv_engine_of(mk(32, 32, 128, 64, kmax=8, io="bf16", snapshot_mode="defer")) == 1
     assert ssmv.ssmv_engine_of(mk(32, 32, 128, 64, kmax=4, io="f32")) == 0
     assert ssmv.ssmv_engine_of(mk(32, 32, 32, 64, kmax=4, io="bf16")) == 0                            # headdim not a multiple of 64
     assert ssmv.ssmv_engine_of(mk(32, 32, 128, 16, kmax=4, io="bf16")) == 0
@@ -67,6 +69,10 @@ def test_cache_sizes():
     assert s[0] == 3 * 8192 * 16 * 4 and s[1] == 16 * 8192 * 4
     d = ssmv.make_dims(1, 1, 3, 16, kmax=1, io="bf16")
     assert ssmv.ssmv_cache_sizes(d) == [768, 256] + [256] * 13
+    # deferred advance: one window ring of 16 entries per sequence, the second arrays one granule
+    d = ssmv.make_dims(32, 32, 128, 64, kmax=4, io="bf16", snapshot_mode="defer")
+    s = ssmv.ssmv_cache_sizes(d)
+    assert s[2] == 32 * 16 * 4096 * 2 and s[4] == 32 * 16 * 32 * 2 and s[6] == 32 * 16 * 64 * 2 and s[3] == s[5] == s[7] == 256
 
 
 def _code(fn, *a, **kw):
@@ -90,7 +96,8 @@ def test_dims_validation():
     assert _code(sizes, mk(1, 4, 2, 16, a_mode="diag")) == ssmv.SSMV_EINVAL        # diag needs headdim 1
     assert _code(sizes, mk(1, 4, 1, 128, a_mode="diag")) == ssmv.SSMV_EUNSUPPORTED
     assert _code(sizes, mk(1, 4, 16, 16, io=7)) == ssmv.SSMV_EINVAL
-    assert _code(sizes, mk(1, 4, 16, 16, snapshot_mode=2)) == ssmv.SSMV_EINVAL
+    assert _code(sizes, mk(1, 4, 16, 16, snapshot_mode=3)) == ssmv.SSMV_EINVAL
+    assert _code(sizes, mk(1, 4, 16, 16, kmax=9, snapshot_mode="defer")) == ssmv.SSMV_EUNSUPPORTED   # two rounds must fit the window
     assert "dstate" in ssmv.load_library().ssmv_last_error().decode() or True
 
 
@@ -142,6 +149,8 @@ def test_argument_validation_precedes_any_gpu_work():
     assert _code(ssmv.ssm_block_multistep, d, c, k=1, xc=P, z=P + 2, **blk) == ssmv.SSMV_EALIGN
     d_hj = ssmv.make_dims(2, 4, 16, 16, kmax=4, io="f32", snapshot_mode="hj_only")
     assert _code(ssmv.ssm_block_multistep, d_hj, c, k=1, tok0=1, xc=P, **blk) == ssmv.SSMV_EUNSUPPORTED
+    d_df = ssmv.make_dims(2, 4, 16, 16, kmax=4, io="f32", snapshot_mode="defer")       # no h_k slot to carry a round in either
+    assert _code(ssmv.ssm_block_multistep, d_df, c, k=1, tok0=1, x_raw=P, conv_wgt=P, **blk) == ssmv.SSMV_EUNSUPPORTED
     assert _code(ssmv.ssmv_materialize_block, d, c, P, None, 3, P, 0) == ssmv.SSMV_EINVAL
     # prefill: length, mode and shape
     assert _code(ssmv.ssm_prefill_chunked, d, c, P, P, None, P, P, P, P, P, 0, P, 0) == ssmv.SSMV_EINVAL

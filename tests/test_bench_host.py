@@ -15,16 +15,16 @@ sys.path.insert(0, ROOT)
 import bench  # noqa: E402
 
 
-@pytest.mark.parametrize("hj_only", [False, True])
-def test_pending_schedule_matches_the_integer_model(hj_only):
+@pytest.mark.parametrize("mode,k", [("both", 4), ("hj_only", 4), ("defer", 4), ("defer", 7)])
+def test_pending_schedule_matches_the_integer_model(mode, k):
     """bench.pend_after predicts, per round, how many accepted tokens each sequence still has to replay; the kernels'
     byte counts hang on it.  The integer model of the cache (commit rules of Algorithm 2 with lazy folding) is the
     authority: run it over the same acceptance history."""
     rng = np.random.default_rng(5)
-    batch, k, rounds = 7, 4, 40
+    batch, rounds = 7, 40
     accepted = [rng.integers(0, k + 1, size=batch) for _ in range(rounds)]
-    sched = bench.pend_after(accepted, [k] * rounds, hj_only=hj_only)
-    bk = oracle.BookkeepingModel(batch, ring_len=8, conv_width=4, hj_only=hj_only)
+    sched = bench.pend_after(accepted, [k] * rounds, mode=mode, kmax=k)
+    bk = oracle.BookkeepingModel(batch, ring_len=16, conv_width=4, mode=mode, kmax=k)
     for r in range(rounds):
         assert sched[r].tolist() == list(bk.pend), "before round %d" % r
         bk.verify(k)
@@ -48,6 +48,10 @@ def test_algorithmic_bytes_of_a_launch_by_hand():
     assert bench.verify_bytes(wl, [2], k, fused=True) == bench.verify_bytes(wl, [2], k, fused=False) + fused_extra
     # the single-snapshot variant never writes h_k
     assert bench.verify_bytes(wl.scaled(snapshot_mode="hj_only"), [2], k, fused=False) == bench.verify_bytes(wl, [2], k, fused=False) - S
+    # deferred advance: no h_k either, and h_j only beyond 16 - 2*4 = 8 pending tokens
+    wd = wl.scaled(snapshot_mode="defer")
+    assert bench.verify_bytes(wd, [8], k, fused=False) == S + tokens_in + y_out + stash_out + 4 * pending_in
+    assert bench.verify_bytes(wd, [9], k, fused=False) == 2 * S + tokens_in + y_out + stash_out + 9 * pending_in // 2
     # a whole split round = the verify launch plus the conv launch (raw in, ring append, xc out, history, weights)
     conv_launch = (k * Cx * 3 + 3 * Cx + 5 * Cx) * e
     assert bench.round_bytes(wl, [0], k, fused=False) == bench.verify_bytes(wl, [0], k, fused=False) + conv_launch

@@ -159,6 +159,7 @@ REPLAY_CASES = {
     "cfg1_small": CONFIGS["cfg1"].scaled(nheads=4, batch=3, rounds=10),
     "k8_narrow_heads": CONFIGS["cfg1"].scaled(nheads=3, headdim=64, dstate=128, batch=2, k=8, rounds=10, ngroups=1),
     "cfg1_small_hj": CONFIGS["cfg1"].scaled(nheads=4, batch=3, rounds=10, snapshot_mode="hj_only"),
+    "cfg1_small_defer": CONFIGS["cfg1"].scaled(nheads=4, batch=3, rounds=14, snapshot_mode="defer"),
     "groups_silu": CONFIGS["cfg1"].scaled(nheads=4, headdim=64, dstate=32, ngroups=2, batch=5, rounds=8, conv_act="silu"),
 }
 REPLAY_SPLITS = {"ones": None, "2+2": [2, 2], "1+3": [1, 3], "3+1": [3, 1], "1+5+2": [1, 5, 2]}
@@ -181,7 +182,7 @@ def test_replayed_round_equals_one_call(name, split):
     one, many = HipLayer(wl, lp), HipLayer(wl, lp)
     assert ssmv.ssmv_engine_of(many.dims) == 1
     ora = oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.conv_act, wl.ngroups)
-    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width, hj_only=wl.snapshot_mode == "hj_only")
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width, mode=wl.snapshot_mode, kmax=wl.kmax_eff)
     for i, rd in enumerate(data.rounds):
         k = rd.x_raw.shape[1]
         parts = parts0 if parts0 is not None else [1] * k

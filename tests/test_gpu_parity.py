@@ -11,7 +11,7 @@ import oracle
 import paper_2408_15237_amd as ssmv
 from workload import CONFIGS, Workload, generate
 
-from _harness import HipLayer, TOL, dims_of, rel_err, run_parity, to_dev, to_host
+from _harness import HipLayer, TOL, dims_of, rel_err, run_parity, to_dev, to_host, untile_state
 
 pytestmark = pytest.mark.gpu
 
@@ -195,6 +195,81 @@ def test_single_snapshot_variant(case, fused):
     if case == "mixed":
         data.rounds[0].accepted[:] = [0, 1, 2, 3, 4, 5, 6, 6, 0]
     run_parity(wl, data, fused=fused, reverify=True)
+
+
+DEFER_CASES = {
+    # matrix-core engine (bf16, tiled slots): pend_hi = 8, pend up to 12
+    "cfg1": (CONFIGS["cfg1"].scaled(nheads=4, batch=5, rounds=40, snapshot_mode="defer"), None),
+    "cfg1_all": (CONFIGS["cfg1"].scaled(nheads=2, batch=2, rounds=9, snapshot_mode="defer", accept="all"), None),
+    "cfg1_none": (CONFIGS["cfg1"].scaled(nheads=2, batch=2, rounds=5, snapshot_mode="defer", accept="none"), None),
+    "groups_n32_silu": (CONFIGS["cfg1"].scaled(nheads=4, headdim=64, dstate=32, ngroups=2, batch=5, rounds=24, conv_act="silu",
+                                               snapshot_mode="defer"), None),
+    "n128_k6": (CONFIGS["cfg1"].scaled(nheads=3, headdim=64, dstate=128, batch=2, k=6, rounds=20, snapshot_mode="defer"), None),
+    "k8_is_single_snapshot": (CONFIGS["cfg1"].scaled(nheads=2, batch=3, k=8, rounds=10, snapshot_mode="defer"), None),
+    "kmax5_varying_k": (CONFIGS["cfg1"].scaled(nheads=2, batch=3, k=4, kmax=5, rounds=16, snapshot_mode="defer"),
+                        [5, 1, 5, 5, 2, 3, 5, 1, 1, 4, 5, 5, 2, 5, 3, 5]),
+    # vector engine: the same shape forced, fp32 tokens, diagonal A
+    "cfg1_vector": (CONFIGS["cfg1"].scaled(nheads=4, batch=3, rounds=24, snapshot_mode="defer", engine="vector"), None),
+    "f32_k3": (Workload("df32", "scalar", batch=4, nheads=2, headdim=48, dstate=16, k=3, rounds=30, io="f32", accept="uniform",
+                        ngroups=2, seed=35, snapshot_mode="defer"), None),
+    "cfg2_k5": (CONFIGS["cfg2"].scaled(nheads=1000, batch=2, k=5, rounds=20, snapshot_mode="defer"), None),
+}
+
+
+@FUSED
+@pytest.mark.parametrize("case", sorted(DEFER_CASES))
+def test_deferred_advance_variant(case, fused):
+    """SSMV_SNAP_DEFER: h_k is never stored and h_j only by a verify that meets pend > 16 - 2 kmax; until then the
+    accepted tokens collect in the window ring behind the live slot.  Outputs, logical state and the integer model's
+    bookkeeping must match the eager oracle on both engines; the schedules are long enough to reach the rounds that
+    store, and for the ring to wrap."""
+    wl, ks = DEFER_CASES[case]
+    data = generate(wl, k_schedule=ks)
+    run_parity(wl, data, fused=fused, reverify=True)
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width, mode="defer", kmax=wl.kmax_eff)
+    moved, top = 0, 0
+    for i, rd in enumerate(data.rounds):
+        bk.verify(rd.x_raw.shape[1])
+        before = list(bk.cur)
+        bk.commit(rd.accepted)
+        moved += sum(a != b for a, b in zip(before, bk.cur))
+        top = max(top, max(bk.pend))
+    if "none" not in case:
+        assert moved > 0, "the schedule never reached a round that stores h_j"
+        assert top > wl.kmax_eff or 2 * wl.kmax_eff == 16, "the window never held more than one round"
+
+
+def test_deferred_advance_stores_a_state_only_when_the_window_fills():
+    """Slot writes of SSMV_SNAP_DEFER on the matrix-core engine: the h_k slot is never written, the h_j slot exactly
+    in the rounds that meet pend > 16 - 2 kmax, and then it holds the state at pos + pend."""
+    wl = CONFIGS["cfg1"].scaled(nheads=2, batch=4, rounds=30, snapshot_mode="defer")
+    data = generate(wl)
+    hip = HipLayer(wl, data.layers[0])
+    assert ssmv.ssmv_engine_of(hip.dims) == 1
+    pend_hi = ssmv.SSMV_WINDOW - 2 * wl.kmax_eff
+    stored = 0
+    for rd in data.rounds:
+        ints = hip.cache.ints()
+        cur = torch.from_numpy(ints["cur_slot"]).long()
+        pend = ints["pend"]
+        seqs = torch.arange(wl.batch)
+        hip.cache.state_view()[(cur + 1) % 3, seqs] = 123.0       # sentinels in both non-live slots
+        hip.cache.state_view()[(cur + 2) % 3, seqs] = 321.0
+        want_hj = hip.materialize()                                # state at pos + pend, before the round
+        dx, ddt, dB, dC = (to_dev(v, wl.io) for v in (rd.x_raw, rd.dt[0], rd.B[0], rd.C[0]))
+        hip.conv_verify(dx, ddt, dB, dC)
+        sv = hip.cache.state_view()
+        for b in range(wl.batch):
+            c = int(cur[b])
+            assert torch.all(sv[(c + 2) % 3, b] == 321.0)
+            if pend[b] > pend_hi:
+                stored += 1
+                assert rel_err(to_host(untile_state(sv[(c + 1) % 3, b])), to_host(want_hj[b])) <= 1e-4
+            else:
+                assert torch.all(sv[(c + 1) % 3, b] == 123.0)
+        hip.commit(torch.from_numpy(rd.accepted).to("cuda"))
+    assert stored > 0
+    ssmv.ssmv_check(hip.cache.c)
 
 
 def test_single_snapshot_never_writes_the_third_slot():

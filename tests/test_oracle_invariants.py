@@ -33,7 +33,12 @@ def _eager(wl, data, layer=0):
 def _lazy(wl, data, layer=0):
     lp = data.layers[layer]
     return oracle.LazyMirror(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.kmax_eff, wl.ring_len,
-                             wl.conv_act, wl.ngroups, hj_only=wl.snapshot_mode == "hj_only")
+                             wl.conv_act, wl.ngroups, mode=wl.snapshot_mode)
+
+
+def _pend_limit(bk, k):
+    """Largest pend the integer model may show after a commit."""
+    return bk.WINDOW - k if bk.defer else (k if bk.hj_only else k - 1)
 
 
 @pytest.mark.parametrize("wl", [TINY, TINY_DIAG], ids=lambda w: w.name)
@@ -128,7 +133,7 @@ def _run_both(wl, data, accepted_per_round, ks=None):
         assert np.allclose(lazy.materialize(), eager.h, rtol=1e-12, atol=1e-13)
         for b in range(wl.batch):
             assert bk.pos[b] + bk.pend[b] == total[b] == eager.j[b]
-            assert bk.cur[b] in (0, 1, 2) and 0 <= bk.pend[b] <= (k if bk.hj_only else k - 1)
+            assert bk.cur[b] in (0, 1, 2) and 0 <= bk.pend[b] <= _pend_limit(bk, wl.kmax_eff)
             assert bk.conv_head[b] == (wl.conv_width - 2 + total[b]) % wl.ring_len
             assert bk.last_k[b] == 0
         assert bk.win_par == (i + 1) % 2 and bk.err == 0
@@ -137,15 +142,17 @@ def _run_both(wl, data, accepted_per_round, ks=None):
 
 TINY_HJ = TINY.scaled(name="tiny_hj", snapshot_mode="hj_only")
 TINY_DIAG_HJ = TINY_DIAG.scaled(name="tinyd_hj", snapshot_mode="hj_only")
+TINY_DEFER = TINY.scaled(name="tiny_defer", snapshot_mode="defer", rounds=24)
+TINY_DIAG_DEFER = TINY_DIAG.scaled(name="tinyd_defer", snapshot_mode="defer", rounds=24)
 
 
-@pytest.mark.parametrize("wl", [TINY, TINY_DIAG, TINY_HJ, TINY_DIAG_HJ], ids=lambda w: w.name)
+@pytest.mark.parametrize("wl", [TINY, TINY_DIAG, TINY_HJ, TINY_DIAG_HJ, TINY_DEFER, TINY_DIAG_DEFER], ids=lambda w: w.name)
 def test_lazy_policy_equals_eager_on_random_schedule(wl):
     data = generate(wl)
     _run_both(wl, data, [rd.accepted for rd in data.rounds])
 
 
-@pytest.mark.parametrize("snap", ["both", "hj_only"])
+@pytest.mark.parametrize("snap", ["both", "hj_only", "defer"])
 def test_lazy_policy_with_varying_k_and_kmax(snap):
     wl = TINY.scaled(kmax=6, rounds=12, seed=9, snapshot_mode=snap)
     ks = [1, 6, 3, 6, 2, 5, 1, 1, 6, 4, 2, 6]
@@ -155,7 +162,7 @@ def test_lazy_policy_with_varying_k_and_kmax(snap):
     _run_both(wl, data, acc)
 
 
-@pytest.mark.parametrize("snap", ["both", "hj_only"])
+@pytest.mark.parametrize("snap", ["both", "hj_only", "defer"])
 def test_lazy_policy_all_accept_and_all_reject_streaks(snap):
     wl = TINY.scaled(rounds=9, snapshot_mode=snap)
     data = generate(wl)
@@ -164,7 +171,7 @@ def test_lazy_policy_all_accept_and_all_reject_streaks(snap):
     _run_both(wl, data, acc)
 
 
-@pytest.mark.parametrize("snap", ["both", "hj_only"])
+@pytest.mark.parametrize("snap", ["both", "hj_only", "defer"])
 def test_bruteforce_every_acceptance_sequence(snap):
     """All (k+1)^rounds acceptance sequences for k<=3 over 4 rounds: lazy state == eager state, ints consistent."""
     for k in (1, 2, 3):
@@ -173,6 +180,20 @@ def test_bruteforce_every_acceptance_sequence(snap):
         data = generate(wl)
         for seq in itertools.product(range(k + 1), repeat=wl.rounds):
             _run_both(wl, data, [[a] for a in seq])
+
+
+def test_bruteforce_deferred_advance_through_the_advance_round():
+    """Deferred advance with kmax = 7 and 6 (pend_hi = 2 and 4): four and five rounds reach the rounds that store h_j and
+    move the live slot, for every acceptance sequence; the window ring (16 entries) wraps on the way."""
+    for k, rounds in ((7, 4), (6, 4)):
+        wl = Workload("bfd", "scalar", batch=1, nheads=2, headdim=2, dstate=3, k=k, rounds=rounds, io="f32",
+                      accept="uniform", seed=40 + k, snapshot_mode="defer")
+        data = generate(wl)
+        moved = 0
+        for seq in itertools.product(range(k + 1), repeat=wl.rounds):
+            _, lazy = _run_both(wl, data, [[a] for a in seq])
+            moved += lazy.bk.cur[0] != 0
+        assert moved > 0
 
 
 def test_bookkeeping_slot_semantics_bruteforce():
@@ -216,6 +237,53 @@ def test_bookkeeping_slot_semantics_bruteforce_single_snapshot():
                 assert slot_pos[bk.cur[0]] == bk.pos[0]
                 assert bk.pos[0] + bk.pend[0] == total and 0 <= bk.pend[0] <= k
                 assert bk.conv_head[0] == (2 + total) % R
+
+
+def test_bookkeeping_slot_semantics_bruteforce_deferred_advance():
+    """Deferred advance: h_j is written only by a verify that meets pend > pend_hi, and only then does the commit move
+    the live slot; the live slot must always stand for `pos`, a verify must never need more than WINDOW tokens, and no
+    window entry that is still pending may be overwritten by the round's own tokens."""
+    R = 16
+    for kmax, rounds in ((8, 4), (5, 6), (4, 7), (3, 7)):
+        for seq in itertools.product(range(kmax + 1), repeat=rounds):
+            bk = oracle.BookkeepingModel(1, R, 4, mode="defer", kmax=kmax)
+            Wn = bk.WINDOW
+            assert bk.pend_hi == Wn - 2 * kmax
+            slot_pos = {0: 0}
+            total = 0
+            owner = {}                                            # window entry -> token index it holds
+            for a in seq:
+                cur, pend, pos = bk.cur[0], bk.pend[0], bk.pos[0]
+                assert pend + kmax <= Wn                          # the verify fits the window
+                for i in range(pend):                             # every pending token is still in its entry
+                    assert owner[(pos + i) % Wn] == pos + i
+                bk.verify(kmax)
+                for t in range(kmax):                             # the round's tokens behind the pending ones
+                    e = (pos + pend + t) % Wn
+                    assert not (e in owner and pos <= owner[e] < pos + pend)
+                    owner[e] = pos + pend + t
+                if pend > bk.pend_hi:
+                    slot_pos[(cur + 1) % 3] = pos + pend          # h_j written, nothing else
+                bk.commit([a])
+                total += a
+                assert slot_pos[bk.cur[0]] == bk.pos[0]
+                assert (bk.cur[0] != cur) == (pend > bk.pend_hi)
+                assert bk.pos[0] + bk.pend[0] == total and 0 <= bk.pend[0] <= Wn - kmax
+                assert bk.conv_head[0] == (2 + total) % R
+
+
+def test_deferred_advance_with_the_smallest_window_is_the_single_snapshot_rule():
+    """kmax = 8: pend_hi = 0, so h_j is stored whenever anything is pending - the single-snapshot integer rule."""
+    rng = np.random.default_rng(5)
+    a_bk = oracle.BookkeepingModel(3, 16, 4, mode="defer", kmax=8)
+    b_bk = oracle.BookkeepingModel(3, 16, 4, hj_only=True)
+    for _ in range(200):
+        k = int(rng.integers(1, 9))
+        acc = rng.integers(0, k + 1, size=3)
+        a_bk.verify(k); b_bk.verify(k)
+        a_bk.commit(acc); b_bk.commit(acc)
+        for name in ("cur", "pend", "pos", "conv_head", "last_k", "win_par", "err"):
+            assert getattr(a_bk, name) == getattr(b_bk, name), name
 
 
 def test_bookkeeping_error_paths():
@@ -284,17 +352,17 @@ def _compositions(n):
 
 
 @pytest.mark.parametrize("replay", [False, True], ids=["carry", "replay"])
-@pytest.mark.parametrize("wl", [TINY, TINY_DIAG.scaled(k=4), TINY_HJ], ids=lambda w: w.name)
+@pytest.mark.parametrize("wl", [TINY, TINY_DIAG.scaled(k=4), TINY_HJ, TINY_DEFER], ids=lambda w: w.name)
 def test_round_fed_by_several_calls_equals_one_call(wl, replay):
     """Section 4.3, draft side: a round whose k tokens arrive over several calls leaves the cache exactly where one
     k-token call would, for every way of splitting k <= 4, over rounds with ragged acceptance in between - whether the
     calls carry the state through the h_k slot or every call recomputes from the live slot (replay_round)."""
-    if wl.snapshot_mode == "hj_only" and not replay:
+    if wl.snapshot_mode != "both" and not replay:
         pytest.skip("carrying the state needs the h_k slot")
-    data = generate(wl.scaled(rounds=4))
+    data = generate(wl.scaled(rounds=8 if wl.snapshot_mode == "defer" else 4))
     lp = data.layers[0]
     mk = lambda: oracle.LazyMirror(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.kmax_eff, wl.ring_len,
-                                   wl.conv_act, wl.ngroups, hj_only=wl.snapshot_mode == "hj_only")
+                                   wl.conv_act, wl.ngroups, mode=wl.snapshot_mode)
     for split in _compositions(wl.k):
         one, many = mk(), mk()
         eager = _eager(wl, data)

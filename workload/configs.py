@@ -27,7 +27,7 @@ class Workload:
     conv_width: int = 4
     conv_act: str = "none"   # "none" | "silu"
     conv_bias: bool = True
-    snapshot_mode: str = "both"   # "both": h_j and h_k as Algorithm 2 | "hj_only": single-snapshot variant
+    snapshot_mode: str = "both"   # "both": h_j and h_k as Algorithm 2 | "hj_only": single-snapshot variant | "defer": h_j only when the window fills up
     engine: str = "auto"     # "auto": the library picks the kernel | "vector": the vector-ALU kernel and row-major state
     kmax: int = 0        # 0 -> k
     layers: int = 1
