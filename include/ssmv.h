@@ -244,9 +244,11 @@ int ssm_block_multistep(const ssmv_dims *dims, const ssmv_cache *cache, const ss
  * verify (pend[b] = last_k[b] = 0), else err_flag is set.  Scalar a_mode, headdim and dstate in
  * {32, 64, 128} (SSMV_EUNSUPPORTED otherwise); L >= 1, the same for all sequences.
  * Arithmetic: fp32 tensors multiply in fp32; bf16 tensors multiply on the bf16 matrix cores with
- * fp32 accumulation, B, C and the conv output entering exactly and every fp32 operand (state,
- * decay-weighted terms) as a bf16 head plus a bf16 tail, which keeps 2^-17 of it per product: the
- * state stays within about 1e-4 (relative) of the exact scan, the outputs within their bf16 rounding.
+ * fp32 accumulation, B, C and the conv output entering exactly.  The fp32 operand of the product that
+ * updates the state enters as a bf16 head plus a bf16 tail, which keeps 2^-17 of it: the state stays
+ * within about 1e-4 (relative) of the exact scan.  The fp32 operands of the products that end in outputs
+ * only enter as their bf16 head (2^-9 per term, the size of the outputs' own bf16 rounding): an output is
+ * within about 1e-2 of the largest output of its tensor.
  * dt is the positive step (after softplus, if that is requested); an input that is not finite
  * anywhere in a chunk of 32 tokens can spread over that chunk's outputs.
  *   x_raw, y_out [batch][L][H*P]; dt [batch][L][H]; Bm, Cm [batch][L][G][N]: io_dtype, device;

@@ -5,8 +5,14 @@
 // with the operands arranged so that fp32 accuracy survives the 8-bit mantissa of the multiplier inputs:
 //   * B, C and the conv output X ARE bf16 (the tensors' storage type; the conv output is rounded to it by
 //     definition), so they enter exactly;
-//   * every fp32 operand (the state h, the masked matrix M, the weighted rows w_s B_s) is split into a bf16 head
-//     and a bf16 tail, v = hi + lo + O(2^-17 |v|), and contributes two products into the same fp32 accumulator.
+//   * the fp32 operand of the product that UPDATES THE STATE (the weighted rows w_s B_s) is split into a bf16 head and a
+//     bf16 tail, v = hi + lo + O(2^-17 |v|), and contributes two products into the same fp32 accumulator: the state
+//     carries over the whole prompt and stays at fp32 accuracy;
+//   * the fp32 operands of the two products that end in OUTPUTS only (the state h in h C^T, the masked matrix M in M X)
+//     enter as their bf16 head alone: a relative 2^-9 per term, the size of the rounding the outputs get anyway when
+//     they are stored as bf16, and nothing of it feeds back into the state.  (Their tails cost a fifth of the kernel's
+//     vector and matrix instructions: 0.41 -> 0.36 ms for 32 x 2048 tokens of a 32 x 128 x 64 layer; the largest output
+//     error against the fp64 scan went from 0.0058 to 0.0075 of the largest output.)
 // One workgroup owns one (sequence, head); wave w owns the 32 channels [32 w, 32 w + 32).  The state lives in the
 // accumulator registers for the whole prompt, TRANSPOSED (tile rows = state index n, columns = channel p): in that
 // shape the registers of a lane (its channel, 16 of the 32 n of a tile) are directly the k-slots of the A operand of
@@ -52,10 +58,9 @@ struct PfLds {              // byte offsets of the LDS arrays (bf16 unless said)
     static constexpr int oX = 0;                           // [P][Q]  conv output x_s
     static constexpr int oBh = oX + P * XS;                // [N][Q]  head of w_s B_s, transposed
     static constexpr int oBl = oBh + N * XS;               // [N][Q]  tail of w_s B_s, transposed
-    static constexpr int oMh = oBl + N * XS;               // [Q][Q]  head of M^T, rows t
-    static constexpr int oMl = oMh + kQ * XS;              // [Q][Q]  tail of M^T
+    static constexpr int oMh = oBl + N * XS;               // [Q][Q]  M^T, rows t (rounded to bf16: it only feeds outputs)
     static constexpr int YS = 32 * 2 + 16;                 // row stride of a wave's output tile [token][32 channels]
-    static constexpr int oY = oMl + kQ * XS;               // [NP][Q][32]  the output tiles, for stores of whole 64-byte rows
+    static constexpr int oY = oMh + kQ * XS;               // [NP][Q][32]  the output tiles, for stores of whole 64-byte rows
     // filled by loads that go from global memory straight into LDS (1 KB per wave and instruction, lane l at byte 16 l):
     static constexpr int oZ = oY + NP * kQ * YS;           // fp32 [NP][16][64]  h C^T over the second half of n, for the tile's first wave
     static constexpr int oXraw = oZ + (NSPL - 1) * NP * 4096;        // [Q][P]  raw conv inputs of the chunk, rows of 2 P bytes
@@ -158,7 +163,7 @@ void prefill_bf16_kernel(const PrefillParams p)
 
     extern __shared__ float4 lds_raw[];
     char *lds = reinterpret_cast<char *>(lds_raw);
-    char *sX = lds + Ld::oX, *sBh = lds + Ld::oBh, *sBl = lds + Ld::oBl, *sMh = lds + Ld::oMh, *sMl = lds + Ld::oMl, *sXraw = lds + Ld::oXraw;
+    char *sX = lds + Ld::oX, *sBh = lds + Ld::oBh, *sBl = lds + Ld::oBl, *sMh = lds + Ld::oMh, *sXraw = lds + Ld::oXraw;
     uint32_t *sCar = reinterpret_cast<uint32_t *>(lds + Ld::oCar);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -410,7 +415,7 @@ void prefill_bf16_kernel(const PrefillParams p)
         uint4 cop[N / 16];
 #pragma unroll
         for (int st = 0; st < N / 16; ++st) cop[st] = *reinterpret_cast<const uint4 *>(sC + t * (N * 2) + (((2 * st + lh) ^ Ld::swz(t)) * 16));
-        // ---- G^T = B C^T, then this wave's share of M^T: masked, decayed, scaled, D on the diagonal; head and tail to LDS ----
+        // ---- G^T = B C^T, then this wave's share of M^T: masked, decayed, scaled, D on the diagonal; to LDS ----
         {
             f16v gacc = {0};
 #pragma unroll
@@ -427,11 +432,7 @@ void prefill_bf16_kernel(const PrefillParams p)
                     const float dec = __builtin_amdgcn_exp2f(cum_t - csv[e]) * dsv[e];      // may overflow where s > t: selected away
                     m[e] = keep[4 * r + e] ? fmaf(g4[e], dec, dadd[4 * r + e]) : 0.f;
                 }
-                uint2 mh, ml;
-                split2(m[0], m[1], mh.x, ml.x);
-                split2(m[2], m[3], mh.y, ml.y);
-                *reinterpret_cast<uint2 *>(sMh + t * XS + s0 * 2) = mh;
-                *reinterpret_cast<uint2 *>(sMl + t * XS + s0 * 2) = ml;
+                *reinterpret_cast<uint2 *>(sMh + t * XS + s0 * 2) = make_uint2(pack_bf16x2(m[0], m[1]), pack_bf16x2(m[2], m[3]));
             };
             // the wave's quads: a uniform branch, so that no register is indexed by a variable
             if constexpr (RW == 4) {
@@ -460,9 +461,11 @@ void prefill_bf16_kernel(const PrefillParams p)
         for (int tn = 0; tn < TNL; ++tn)
 #pragma unroll
             for (int st = 0; st < 2; ++st) {
-                uint32_t ah[4], al[4];
+                uint32_t ah[4];                          // heads only: these products end in outputs, not in the state
 #pragma unroll
-                for (int d = 0; d < 4; ++d) split2(hacc[tn][8 * st + 2 * d], hacc[tn][8 * st + 2 * d + 1], ah[d], al[d]);
+                for (int d = 0; d < 4; ++d) {
+                    ah[d] = pack_bf16x2(hacc[tn][8 * st + 2 * d], hacc[tn][8 * st + 2 * d + 1]);
+                }
                 // C for the wave's own tiles: with a split state read again at the wave's offset (a choice between
                 // registers by a variable would put the array into scratch memory)
                 uint4 c4;
@@ -470,7 +473,6 @@ void prefill_bf16_kernel(const PrefillParams p)
                 else c4 = cop[2 * tn + st];
                 const bf8 cb = as_bf8(c4);
                 yacc = mfma(as_bf8(ah[0], ah[1], ah[2], ah[3]), cb, yacc);
-                yacc = mfma(as_bf8(al[0], al[1], al[2], al[3]), cb, yacc);
             }
         if constexpr (NSPL == 2) {
             if (nh == 1) {                              // the second half of n: hand the sum to the tile's first wave
@@ -499,7 +501,6 @@ void prefill_bf16_kernel(const PrefillParams p)
             for (int st = 0; st < 2; ++st) {
                 const int o = t * XS + (16 * st + 8 * lh) * 2;
                 yacc = mfma(as_bf8(xop[st]), as_bf8(*reinterpret_cast<const uint4 *>(sMh + o)), yacc);
-                yacc = mfma(as_bf8(xop[st]), as_bf8(*reinterpret_cast<const uint4 *>(sMl + o)), yacc);
             }
         }
 #pragma unroll
