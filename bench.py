@@ -220,9 +220,9 @@ def bench_prefill(args):
     tflops = flops / (ms * 1e-3) / 1e12
     gbps = nbytes / (ms * 1e-3) / 1e9
     if wl.io == "bf16":
-        # executed matrix work per chunk and wave, in products of 32x32x16: N/16 (G^T, every wave its own) + 2 N/16 (h C^T, head
-        # and tail) + 4 (M X, head and tail) + 2 N/16 (update, head and tail)
-        mfma_flops = (4 + 5 * (N // 16)) * 32768.0 * (P // 32) * math.ceil(L / Q) * B_ * H
+        # executed matrix work per chunk and wave, in products of 32x32x16: N/16 (G^T, every wave its own) + N/16 (h C^T, head
+        # only) + 2 (M X, head only) + 2 N/16 (update, head and tail)
+        mfma_flops = (2 + 4 * (N // 16)) * 32768.0 * (P // 32) * math.ceil(L / Q) * B_ * H
         traffic = None                                  # the counters were read on this shape only
         tpath = os.path.join(ROOT, "profiles", "prefill_bf16_kernel_%s_L%d_pmc.txt" % (wl.name, L))
         if not args.prefill_io and os.path.exists(tpath):
@@ -230,11 +230,11 @@ def bench_prefill(args):
                 if line.startswith("traffic_bytes_per_launch:"):
                     traffic = float(line.split(":")[1])
         roof = {"bound": "hbm", "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(gbps / PEAK_HBM_GBPS, 4),
-                "traffic": traffic, "kernel": "prefill_bf16_kernel (bf16 MFMA, split operands)", "avg_launch_us": round(ms * 1e3, 1),
+                "traffic": traffic, "kernel": "prefill_bf16_kernel (bf16 MFMA, split operand in the state update)", "avg_launch_us": round(ms * 1e3, 1),
                 "algorithmic_bytes_per_launch": int(nbytes), "algorithmic_flops_per_launch": int(flops),
                 "mfma_executed_tflops": round(mfma_flops / (ms * 1e-3) / 1e12, 1),
                 "mfma_frac_of_bf16_peak": round(mfma_flops / (ms * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4)}
-        dtype = "bf16 products of split fp32 operands, f32 accumulation"
+        dtype = "bf16 products (fp32 operand of the state update split into head and tail), f32 accumulation"
     else:
         roof = {"bound": "mfma", "achieved": round(tflops, 2), "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(tflops / PEAK_MFMA_F32_TFLOPS, 4), "traffic": None, "kernel": "prefill_kernel (fp32 MFMA)",

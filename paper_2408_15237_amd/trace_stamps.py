@@ -1,7 +1,7 @@
 """Timeline of the matrix-core verify kernel from inside: builds the library with -DSSMV_TRACE (libssmv_trace.so), runs a
 workload's fused conv+verify launches back to back (one HIP graph, rotating caches, pending counts as the workload leaves
 them) and prints, for the LAST launch of the graph, the distribution over its workgroups of eight wall-clock stamps
-(microseconds since the launch's first workgroup started).  A profiling aid: the stamps and two extra waits change the
+(microseconds since the launch's first workgroup started).  A profiling aid: the stamps and one extra wait change the
 kernel slightly, so its timings are not the library's.
 
   python -m paper_2408_15237_amd.trace_stamps [--workload cfg3] [--launches 64] [--snapshot-mode both|hj_only|defer] [--prime 3]
