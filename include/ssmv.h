@@ -62,8 +62,8 @@ enum { SSMV_ACT_NONE = 0, SSMV_ACT_SILU = 1 };  /* conv_act                     
  * fully accepted round makes h_k the live state.  HJ_ONLY never stores h_k: every accepted token, also those of
  * a fully accepted round, stays pending and is replayed by the next verify.  Same outputs and same logical
  * state; about a third fewer bytes per round for up to k more replay steps.
- * DEFER goes one step further along Section 4.2's lazy advance ("maintains only one hidden state in the cache and
- * advances it lazily"): h_k is never stored, and h_j only when it has to be.  A verify recomputes up to SSMV_WINDOW
+ * DEFER goes one step further along the lazily advanced single cached state of Section 4.2: h_k is never stored,
+ * and h_j only when it has to be.  A verify recomputes up to SSMV_WINDOW
  * tokens from the cached state, so the live slot stays put and the accepted tokens collect behind it for as long as the
  * next round is sure to fit: a verify stores h_j (and its commit moves the live slot there) only if it meets
  * pend > SSMV_WINDOW - 2*kmax.  kmax <= SSMV_WINDOW/2; with kmax = SSMV_WINDOW/2 this is HJ_ONLY.  Same outputs and same

@@ -42,6 +42,9 @@ CASES = {
     "f32_groups": CONFIGS["cfg0"].scaled(io="f32", ngroups=2, nheads=4, batch=5, k=3, kmax=5, rounds=10),
     "ragged_rows": CONFIGS["cfg0"].scaled(headdim=24, dstate=32, batch=3, rounds=8),
     "cfg1_full": CONFIGS["cfg1"].scaled(rounds=8),              # the 8B-shaped layer at its full size, every element
+    # the deferred advance: window ring, states stored only when it fills up (matrix-core engine; vector engine, fp32)
+    "cfg1_small_defer": CONFIGS["cfg1"].scaled(nheads=4, batch=3, rounds=24, snapshot_mode="defer"),
+    "f32_groups_defer": CONFIGS["cfg0"].scaled(io="f32", ngroups=2, nheads=4, batch=5, k=3, kmax=5, rounds=20, snapshot_mode="defer"),
 }
 
 
@@ -56,7 +59,7 @@ def test_step_size_transform_and_gate(name, gate, fused):
     tol = TOL[wl.io]
     hip = HipLayer(wl, lp)
     ora = _block_oracle(wl, lp, bias, True)
-    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width, mode=wl.snapshot_mode, kmax=wl.kmax_eff)
     d_bias = torch.from_numpy(bias).to("cuda")
     for i, rd in enumerate(data.rounds):
         k = rd.x_raw.shape[1]
@@ -116,7 +119,7 @@ def test_round_fed_by_several_calls_equals_one_call(name, split):
     tol = TOL[wl.io]
     one, many = HipLayer(wl, lp), HipLayer(wl, lp)
     ora = oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.conv_act, wl.ngroups)
-    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width, mode=wl.snapshot_mode, kmax=wl.kmax_eff)
     for i, rd in enumerate(data.rounds):
         k = rd.x_raw.shape[1]
         parts = SPLITS[split] if SPLITS[split] is not None and sum(SPLITS[split]) == k else [1] * k
@@ -257,7 +260,7 @@ def test_draft_model_round_trip_with_rejections():
 
 
 @pytest.mark.parametrize("fused", [False, True], ids=["split", "fused"])
-@pytest.mark.parametrize("name", ["cfg0", "cfg1_small", "cfg2_small", "f32_groups"])
+@pytest.mark.parametrize("name", ["cfg0", "cfg1_small", "cfg2_small", "f32_groups", "cfg1_small_defer", "f32_groups_defer"])
 def test_ragged_draft_counts(name, fused):
     """Per-sequence draft counts k_seq[b] <= k.  The recurrence is causal, so the oracle's outputs and states for
     the first kb tokens of a sequence do not depend on the tokens behind them: the oracle verifies all k tokens
@@ -270,7 +273,7 @@ def test_ragged_draft_counts(name, fused):
     rng = np.random.default_rng(77)
     hip = HipLayer(wl, lp)
     ora = oracle.EagerOracle(wl.a_mode, lp.A, lp.D, lp.conv_w, lp.conv_b, lp.h0, wl.io, wl.conv_act, wl.ngroups)
-    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width, mode=wl.snapshot_mode, kmax=wl.kmax_eff)
     for i, rd in enumerate(data.rounds):
         k = rd.x_raw.shape[1]
         kseq = rng.integers(1, k + 1, size=wl.batch).astype(np.int32)

@@ -34,6 +34,14 @@ def test_cfg3_full_size_every_element(engine):
     print("cfg3 full size, engine %s: worst errors %s" % (engine, {k: "%.3g" % v for k, v in worst.items()}))
 
 
+def test_cfg3_full_size_deferred_advance_every_element():
+    """The same with SSMV_SNAP_DEFER, the configuration `bench.py --deferred-advance` times: all 64 rounds, every y and
+    conv output, the logical state every 8 rounds, the integers of all 32 sequences every round."""
+    wl = CONFIGS["cfg3"].scaled(snapshot_mode="defer")
+    worst = run_parity(wl, generate(wl), check_state_every=8, fused=True)
+    print("cfg3 full size, deferred advance: worst errors %s" % {k: "%.3g" % v for k, v in worst.items()})
+
+
 def test_cfg1_full_size_every_element():
     wl = CONFIGS["cfg1"]
     for fused in (False, True):
@@ -64,7 +72,7 @@ def test_cfg4_stack_every_layer_every_sequence():
     forced = [HipLayer(wl, lp) for lp in data.layers]
     free = [HipLayer(wl, lp) for lp in data.layers]
     oras = [eager_oracle(wl, lp) for lp in data.layers]
-    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width, mode=wl.snapshot_mode, kmax=wl.kmax_eff)
     worst, worst_free = 0.0, 0.0
     for i, rd in enumerate(data.rounds):
         x_ora = rd.x_raw.astype(np.float64)                   # the oracle chain's input to layer 0

@@ -310,9 +310,10 @@ def test_fused_launch_equals_the_two_separate_launches_bit_for_bit():
                 assert torch.equal(a.cache.buffers[name], bb.cache.buffers[name]), name
 
 
-def test_commit_multi_matches_single_commits():
-    wl = Workload("cm", "scalar", batch=5, nheads=1, headdim=16, dstate=16, k=3, rounds=6, io="f32",
-                  accept="uniform", seed=17)
+@pytest.mark.parametrize("snap", ["both", "hj_only", "defer"])
+def test_commit_multi_matches_single_commits(snap):
+    wl = Workload("cm", "scalar", batch=5, nheads=1, headdim=16, dstate=16, k=3, rounds=6 if snap != "defer" else 18, io="f32",
+                  accept="uniform", seed=17, snapshot_mode=snap)
     data = generate(wl)
     lp = data.layers[0]
     n_layers = 40                                        # more than one launch covers
@@ -397,7 +398,7 @@ def test_device_error_flag_paths():
     hip.verify(xc, to_dev(rd.dt[0], wl.io), to_dev(rd.B[0], wl.io), to_dev(rd.C[0], wl.io))
     bad = np.array([7, -2, 1], dtype=np.int32)
     hip.commit(torch.from_numpy(bad).to("cuda"))
-    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
+    bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width, mode=wl.snapshot_mode, kmax=wl.kmax_eff)
     bk.verify(wl.k)
     bk.commit(bad)
     ints = hip.cache.ints()
@@ -419,7 +420,7 @@ def test_commit_is_per_sequence_when_some_have_no_verify_pending():
         lk[:wl.batch] = lk[:wl.batch] * torch.tensor(mask, dtype=torch.int32, device="cuda")
         acc = np.array([3, 1, 2, 0], dtype=np.int32)
         hip.commit(torch.from_numpy(acc).to("cuda"))
-        bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width)
+        bk = oracle.BookkeepingModel(wl.batch, wl.ring_len, wl.conv_width, mode=wl.snapshot_mode, kmax=wl.kmax_eff)
         bk.verify(wl.k)
         bk.last_k = [wl.k * m for m in mask]
         bk.commit(acc)

@@ -34,12 +34,23 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+# the same with the deferred advance: the prompt leaves pos = L, so the window ring starts at entry L % 16, and the decode
+# runs long enough to reach the rounds that store a state (matrix-core engine, vector engine with bf16 and with fp32 tensors)
+DEFER_CASES = [
+    ("defer_p128n64_bf16", 128, 64, 2, 1, 3, "bf16", "none", 77, "defer", "auto"),
+    ("defer_p64n32_bf16_groups", 64, 32, 4, 2, 3, "bf16", "silu", 45, "defer", "auto"),
+    ("defer_p64n64_bf16_vector", 64, 64, 2, 1, 2, "bf16", "none", 50, "defer", "vector"),
+    ("defer_p32n32_f32", 32, 32, 3, 1, 2, "f32", "none", 70, "defer", "auto"),
+]
+
+
+@pytest.mark.parametrize("case", CASES + DEFER_CASES, ids=[c[0] for c in CASES + DEFER_CASES])
 def test_prefill_then_speculative_decoding(case):
-    name, P, N, H, G, batch, io, act, L = case
+    name, P, N, H, G, batch, io, act, L = case[:9]
+    snap, engine = (case[9], case[10]) if len(case) > 9 else ("both", "auto")
     tol = TOL[io]
-    dec = Workload(name, "scalar", batch=batch, nheads=H, headdim=P, dstate=N, k=4, rounds=6, io=io, accept="uniform",
-                   ngroups=G, conv_act=act, seed=31)
+    dec = Workload(name, "scalar", batch=batch, nheads=H, headdim=P, dstate=N, k=4, rounds=6 if snap == "both" else 24, io=io,
+                   accept="uniform", ngroups=G, conv_act=act, seed=31, snapshot_mode=snap, engine=engine)
     prompt = generate(dec.scaled(k=L, kmax=L, rounds=1, seed=32))       # only its draws are used: one "round" of L tokens
     data = generate(dec)
     lp = data.layers[0]
@@ -69,7 +80,7 @@ def test_prefill_then_speculative_decoding(case):
     assert e_h <= tol, "state after the prompt: %.3g" % e_h
 
     # decode from there: the ring must continue the prompt, the slots and integers must be consistent
-    bk = oracle.BookkeepingModel(batch, dec.ring_len, dec.conv_width)
+    bk = oracle.BookkeepingModel(batch, dec.ring_len, dec.conv_width, mode=dec.snapshot_mode, kmax=dec.kmax_eff)
     bk.pos = [L] * batch
     bk.conv_head = ints["conv_head"].tolist()
     for i, rd in enumerate(data.rounds):
