@@ -20,6 +20,12 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+# verify_mfma.hip: the first 14 dwords of kernel arguments (seven pointers its first scalar loads go through) are handed to
+# the waves in scalar registers at their start (gfx950 kernel-argument preload; where the firmware does not do it the
+# compiler's prologue loads them)
+EXTRA_FLAGS = {"verify_mfma.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=14"]}
+
+
 def _hipcc() -> str:
     for c in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
         if c and (os.path.sep not in c or os.path.exists(c)):
@@ -47,7 +53,7 @@ def build(force: bool = False, verbose: bool = False, trace: bool = False) -> st
         src = os.path.join(CSRC, s)
         obj = os.path.join(obj_dir, s.replace(".hip", ".o"))
         if force or _stale(obj, [src] + HEADERS):
-            jobs.append([hipcc] + flags + ["-c", src, "-o", obj])
+            jobs.append([hipcc] + flags + EXTRA_FLAGS.get(s, []) + ["-c", src, "-o", obj])
 
     def run(cmd):
         r = subprocess.run(cmd, capture_output=True, text=True)

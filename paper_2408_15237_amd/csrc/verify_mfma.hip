@@ -84,7 +84,13 @@ __device__ long long *trace_buf_ = nullptr;
 #endif
 
 template <int N, int NT, bool CONV, bool EXTRA>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void verify_mfma_kernel(const VerifyParams p)
+// The seven pointers that the first scalar loads go through are kernel arguments of their own, ahead of the parameter
+// block: this file is compiled with kernel-argument preload, which hands the first arguments to a wave in scalar registers
+// when it starts, so those loads leave at once instead of behind a first round trip for the parameter block (where the
+// firmware does not preload, the compiler's own prologue loads them, as before).
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4)))
+void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32_t *a_par, const int32_t *a_pos, const int32_t *a_head,
+                        const float *a_A, const float *a_D, const VerifyParams p)
 {
     constexpr int NQ = N / 16;                           // 16-wide tiles along n
     constexpr int NH = N / 32;                           // 32-deep steps of a contraction over n
@@ -127,11 +133,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void v
     // (readfirstlane: free for a value that already sits in a scalar register, and it keeps the constraint below legal in
     // builds where a store ahead of these loads turns them into vector loads)
     auto uni = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
-    int cur_raw = uni(p.cur_slot[b]), pd_raw = uni(p.pend[b]), par_raw = uni(p.win_par[0]);
-    int pos_raw = uni(reinterpret_cast<const int *>(p.pos)[2 * b]);       // the low half: only pos % 16 is needed
-    int A_bits = uni(__float_as_int(p.A[hd])), D_bits = uni(__float_as_int(p.D[hd]));
+    int cur_raw = uni(a_cur[b]), pd_raw = uni(a_pend[b]), par_raw = uni(a_par[0]);
+    int pos_raw = uni(a_pos[2 * b]);                                      // the low half: only pos % 16 is needed
+    int A_bits = uni(__float_as_int(a_A[hd])), D_bits = uni(__float_as_int(a_D[hd]));
     int ch_raw = 0, ks_raw = k, dtb_bits = 0;
-    if constexpr (CONV) ch_raw = uni(p.conv_head[b]);
+    if constexpr (CONV) ch_raw = uni(a_head[b]);
     if constexpr (EXTRA) {
         if (p.k_seq) ks_raw = uni(p.k_seq[b]);
         if (p.dt_bias) dtb_bits = uni(__float_as_int(p.dt_bias[hd]));
@@ -512,14 +518,16 @@ int launch_shape(const VerifyParams &p, hipStream_t stream)
 {
     const dim3 grid(p.P / (64 * NT), p.H, p.batch), block(256);
     const bool conv = p.x_raw != nullptr;
+#define PRE p.cur_slot, p.pend, p.win_par, reinterpret_cast<const int32_t *>(p.pos), p.conv_head, p.A, p.D
     const bool extra = p.tok0 > 0 || p.dt_softplus || p.dt_bias || p.z || p.k_seq || !p.store_state;
     if (conv) {
-        if (extra) hipLaunchKernelGGL((verify_mfma_kernel<N, NT, true, true>), grid, block, 0, stream, p);
-        else hipLaunchKernelGGL((verify_mfma_kernel<N, NT, true, false>), grid, block, 0, stream, p);
+        if (extra) hipLaunchKernelGGL((verify_mfma_kernel<N, NT, true, true>), grid, block, 0, stream, PRE, p);
+        else hipLaunchKernelGGL((verify_mfma_kernel<N, NT, true, false>), grid, block, 0, stream, PRE, p);
     } else {
-        if (extra) hipLaunchKernelGGL((verify_mfma_kernel<N, NT, false, true>), grid, block, 0, stream, p);
-        else hipLaunchKernelGGL((verify_mfma_kernel<N, NT, false, false>), grid, block, 0, stream, p);
+        if (extra) hipLaunchKernelGGL((verify_mfma_kernel<N, NT, false, true>), grid, block, 0, stream, PRE, p);
+        else hipLaunchKernelGGL((verify_mfma_kernel<N, NT, false, false>), grid, block, 0, stream, PRE, p);
     }
+#undef PRE
     return (int)hipGetLastError();
 }
 
