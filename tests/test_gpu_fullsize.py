@@ -108,10 +108,12 @@ def test_cfg4_stack_every_layer_every_sequence():
     print("cfg4 stack: worst y error, teacher-forced %.3g; free-running last layer max|g-r|/max|r| %.3g" % (worst, worst_free))
 
 
-def test_one_round_as_a_hip_graph_replayed_with_eager_work_in_between():
+@pytest.mark.parametrize("snap", ["both", "defer"])
+def test_one_round_as_a_hip_graph_replayed_with_eager_work_in_between(snap):
     """A verify round captured once (kernel nodes only) and replayed for several rounds, with eager work and
-    synchronisation between the replays; every replay must equal the eager path bit for bit."""
-    wl = CONFIGS["cfg1"].scaled(nheads=4, batch=3, rounds=8)
+    synchronisation between the replays; every replay must equal the eager path bit for bit.  With the deferred advance
+    the window entries a replay reads and writes follow from pos and pend on the device, round after round."""
+    wl = CONFIGS["cfg1"].scaled(nheads=4, batch=3, rounds=8 if snap == "both" else 20, snapshot_mode=snap)
     data = generate(wl)
     lp = data.layers[0]
     eager, graphed = HipLayer(wl, lp), HipLayer(wl, lp)
