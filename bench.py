@@ -360,7 +360,9 @@ def main():
     sizes = ssmv.ssmv_cache_sizes(dims)
     matrix_engine = ssmv.ssmv_engine_of(dims) == 1
     cache_bytes = sum(sizes)
-    n_inst = args.instances or max(1, math.ceil(args.footprint_gib * 2 ** 30 / cache_bytes))
+    # (at most 1024 caches: a tiny workload such as cfg0 would otherwise ask for 10^5 of them and a graph of 10^6 launches,
+    # which the runtime does not survive; its footprint is then below --footprint-gib and `config.instances` says so)
+    n_inst = args.instances or min(1024, max(1, math.ceil(args.footprint_gib * 2 ** 30 / cache_bytes)))
     caches = [ssmv.LayerCache.allocate(dims) for _ in range(n_inst)]
     A = torch.from_numpy(lp.A).to(dev)
     D = torch.from_numpy(lp.D).to(dev)
@@ -447,6 +449,9 @@ def main():
             ssmv.ssm_commit_rollback_multi(dims, part, rounds[(s_end // n_inst) % n_rounds]["acc"])
 
     K = args.steps if args.steps > 0 else n_inst * n_rounds
+    if K > 65536:
+        print("bench.py: %d timed steps would be one graph of that many launches; at most 65536" % K, file=sys.stderr)
+        sys.exit(2)
     W = args.warmup if args.warmup >= 0 else max(3, n_inst)
     plan = step_plan(wl, [r.accepted for r in data.rounds], k, n_inst, W, K, fused, gate=args.block, calls=k if args.draft else 1, replay=replay)
     PRIME, workload_bytes = plan["prime"], plan["workload_bytes"]
