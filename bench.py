@@ -462,9 +462,9 @@ def main():
     # 20 us, which K = 20 steps of 17 us would otherwise carry as 6 %).
     filler_buf = torch.empty(2 * 256 * 2 ** 20, dtype=torch.uint8, device=dev)
 
-    def filler(n=1):
+    def filler(n=1):                                  # (the stream probe, not the copy probe: that one calibrates the byte counters)
         for _ in range(n):
-            ssmv.ssmv_copy_probe(filler_buf.data_ptr(), filler_buf.data_ptr() + 256 * 2 ** 20, None, 256 * 2 ** 20)
+            ssmv.ssmv_stream_probe("r1w1", filler_buf.data_ptr(), filler_buf.data_ptr() + 256 * 2 ** 20, None, 256 * 2 ** 20)
 
     result = {}
     for s in range(PRIME):
