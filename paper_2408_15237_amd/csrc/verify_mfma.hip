@@ -513,21 +513,27 @@ void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32
 #endif
 }
 
+template <int N, int NT, bool CONV, bool EXTRA>
+void launch_one(const VerifyParams &p, hipStream_t stream)
+{
+    const dim3 grid(p.P / (64 * NT), p.H, p.batch), block(256);
+    // the pointers of the first scalar loads ahead of the parameter block (kernel-argument preload)
+    hipLaunchKernelGGL((verify_mfma_kernel<N, NT, CONV, EXTRA>), grid, block, 0, stream, p.cur_slot, p.pend, p.win_par,
+                       reinterpret_cast<const int32_t *>(p.pos), p.conv_head, p.A, p.D, p);
+}
+
 template <int N, int NT>
 int launch_shape(const VerifyParams &p, hipStream_t stream)
 {
-    const dim3 grid(p.P / (64 * NT), p.H, p.batch), block(256);
     const bool conv = p.x_raw != nullptr;
-#define PRE p.cur_slot, p.pend, p.win_par, reinterpret_cast<const int32_t *>(p.pos), p.conv_head, p.A, p.D
     const bool extra = p.tok0 > 0 || p.dt_softplus || p.dt_bias || p.z || p.k_seq || !p.store_state;
     if (conv) {
-        if (extra) hipLaunchKernelGGL((verify_mfma_kernel<N, NT, true, true>), grid, block, 0, stream, PRE, p);
-        else hipLaunchKernelGGL((verify_mfma_kernel<N, NT, true, false>), grid, block, 0, stream, PRE, p);
+        if (extra) launch_one<N, NT, true, true>(p, stream);
+        else launch_one<N, NT, true, false>(p, stream);
     } else {
-        if (extra) hipLaunchKernelGGL((verify_mfma_kernel<N, NT, false, true>), grid, block, 0, stream, PRE, p);
-        else hipLaunchKernelGGL((verify_mfma_kernel<N, NT, false, false>), grid, block, 0, stream, PRE, p);
+        if (extra) launch_one<N, NT, false, true>(p, stream);
+        else launch_one<N, NT, false, false>(p, stream);
     }
-#undef PRE
     return (int)hipGetLastError();
 }
 
