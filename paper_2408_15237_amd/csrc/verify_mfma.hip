@@ -385,8 +385,11 @@ void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32
         }
     }
 
-    // ---- weighted, transposed B rows: head and tail, for the snapshot h_j (pending tokens) and for h_k (drafts) -------------
-    if ((int)tid >= BT0) {
+    // ---- weighted, transposed B rows: head and tail, for the snapshot h_j (pending tokens) and for h_k (drafts).  Only if
+    // this launch forms a snapshot for this sequence: with a deferred advance, and in a call of a replayed round that is not
+    // its last, most launches form none ---------------------------------------------------------------------------------
+    const bool forms_state = (!EXTRA || p.store_state) && (adv || p.write_hk);
+    if (forms_state && (int)tid >= BT0) {
         const unsigned bi = tid - BT0, bn = bi % N, bt0 = 8 * (bi / N);
         uint32_t hj[4], lj[4], hk[4], lk[4];
 #pragma unroll
@@ -468,7 +471,7 @@ void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32
             Y1 = mfma16(as_bf8(a), as_bf8(u4v{c2.x, c2.y, c2.x, c2.y}), Y1);
         }
         // (a call of a replayed round that is not its last needs the outputs only: no snapshot is formed)
-        if (!EXTRA || p.store_state) {
+        if (forms_state) {
             // (i) + (ii): fold the pending tokens in and store the snapshot h_j (a deferred advance stores it only when the
             // window is about to fill up; until then it is needed, unstored, as the start of h_k or not at all)
             if (adv || (pd > 0 && p.write_hk)) {
