@@ -390,15 +390,19 @@ void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32
     // its last, most launches form none ---------------------------------------------------------------------------------
     const bool forms_state = (!EXTRA || p.store_state) && (adv || p.write_hk);
     if (forms_state && (int)tid >= BT0) {
-        const unsigned bi = tid - BT0, bn = bi % N, bt0 = 8 * (bi / N);
+        const unsigned bi = tid - BT0, bn = bi % N;
+        // the eight tokens of this thread's unit: the same for the whole wave when a wave covers one n range (N >= 64), and
+        // then a weight comes out of its lane with a scalar read instead of a trip through the LDS crossbar
+        const unsigned bt0 = N >= 64 ? 8 * __builtin_amdgcn_readfirstlane(bi / N) : 8 * (bi / N);
+        auto weight = [&](float v, int lane) { return N >= 64 ? uniform_lane(v, lane) : lane_get(v, lane); };
         uint32_t hj[4], lj[4], hk[4], lk[4];
 #pragma unroll
         for (int ii = 0; ii < 4; ++ii) {
             const int ta = bt0 + 2 * ii;
             // rows past the last token hold whatever LDS held: select, do not multiply
             const float b0 = ta < T ? bf16lo(sBr[ta * CS + bn]) : 0.f, b1 = ta + 1 < T ? bf16lo(sBr[(ta + 1) * CS + bn]) : 0.f;
-            split2(lane_get(wk, ta) * b0, lane_get(wk, ta + 1) * b1, hk[ii], lk[ii]);
-            split2(lane_get(wj, ta) * b0, lane_get(wj, ta + 1) * b1, hj[ii], lj[ii]);
+            split2(weight(wk, ta) * b0, weight(wk, ta + 1) * b1, hk[ii], lk[ii]);
+            split2(weight(wj, ta) * b0, weight(wj, ta + 1) * b1, hj[ii], lj[ii]);
         }
         u2v *dk = reinterpret_cast<u2v *>(sWk + bn * XS + bt0), *dkl = reinterpret_cast<u2v *>(sWk + (N + bn) * XS + bt0);
         dk[0] = u2v{hk[0], hk[1]}; dk[1] = u2v{hk[2], hk[3]};
