@@ -449,7 +449,10 @@ void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32
     SSMV_TP(5);
     __builtin_amdgcn_s_barrier();
 
-    // ---- the products, tile by tile ------------------------------------------------------------------------------------------
+    // ---- the products: the outputs of every tile of the wave, then h_j of every tile, then h_k of every tile.  The order of
+    // the stores is worth 3 % of the launch: the outputs (32-byte pieces that the L2 puts together into lines) leave ahead of
+    // the state stores, not between or behind them (small cached stores as the last thing a wave does cost a microsecond),
+    // and a wave writes its 8 KB of one snapshot in one run instead of changing slots every 4 KB -----------------------------
     float *dstJ = p.state + (size_t)((cur + 1) % 3) * p.slot_stride + head_base + st_off;
     float *dstK = p.state + (size_t)((cur + 2) % 3) * p.slot_stride + head_base + st_off;
     uint16_t *yp = static_cast<uint16_t *>(p.y);
@@ -458,10 +461,11 @@ void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32
         const u2v a = reinterpret_cast<const u2v *>(row)[0], c = reinterpret_cast<const u2v *>(row)[1];
         return as_bf8(u4v{a.x, a.y, c.x, c.y});
     };
+    bf8 Xop[NT];
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
         const unsigned ptl = w * NT + i;                 // row tile inside the workgroup
-        const bf8 Xop = row16(sX + (ptl * 16 + li) * XS + 8 * (g & 1));
+        Xop[i] = row16(sX + (ptl * 16 + li) * XS + 8 * (g & 1));
         // Y1^T = h_0 C^T : rows p, columns t, contraction over n; head and tail of h_0 stacked along the contraction
         v4f Y1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -474,31 +478,9 @@ void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32
             const u2v c2 = *reinterpret_cast<const u2v *>(sC + li * CS + 16 * q + 4 * g);
             Y1 = mfma16(as_bf8(a), as_bf8(u4v{c2.x, c2.y, c2.x, c2.y}), Y1);
         }
-        // (a call of a replayed round that is not its last needs the outputs only: no snapshot is formed)
-        if (forms_state) {
-            // (i) + (ii): fold the pending tokens in and store the snapshot h_j (a deferred advance stores it only when the
-            // window is about to fill up; until then it is needed, unstored, as the start of h_k or not at all)
-            if (adv || (pd > 0 && p.write_hk)) {
-#pragma unroll
-                for (int q = 0; q < NQ; ++q) {
-                    const bf8 Aw = row16(sWj + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1));
-                    st[i][q] = mfma16(Aw, Xop, st[i][q] * alphaJ);
-                    if (adv) __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstJ + ((i * NQ + q) << 8)));
-                }
-            }
-            // (iii) + (iv): the drafts, and the snapshot h_k (Algorithm 2), unless every accepted token is to stay pending
-            if (p.write_hk) {
-#pragma unroll
-                for (int q = 0; q < NQ; ++q) {
-                    const bf8 Aw = row16(sWk + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1));
-                    st[i][q] = mfma16(Aw, Xop, st[i][q] * beta);
-                    __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstK + ((i * NQ + q) << 8)));
-                }
-            }
-        }
         // Y2^T = X^T M^T : the drafts' outputs from the tokens of this launch (D x_t on the diagonal of M)
         const bf8 Mop = row16(sM + ((g >> 1) * 16 + li) * XS + 8 * (g & 1));
-        const v4f Y2 = mfma16(Xop, Mop, v4f{0.f, 0.f, 0.f, 0.f});
+        const v4f Y2 = mfma16(Xop[i], Mop, v4f{0.f, 0.f, 0.f, 0.f});
         // lane: draft t = li, channels ptl*16 + 4 g .. + 3
         if ((int)li < k) {
             float yv[4];
@@ -511,6 +493,32 @@ void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32
                 }
             }
             *reinterpret_cast<u2v *>(yp + oX_in + (size_t)li * HP + ptl * 16 + 4 * g) = u2v{pack_bf16x2(yv[0], yv[1]), pack_bf16x2(yv[2], yv[3])};
+        }
+    }
+    // (a call of a replayed round that is not its last needs the outputs only: no snapshot is formed)
+    if (forms_state) {
+        // (i) + (ii): fold the pending tokens in and store the snapshot h_j (a deferred advance stores it only when the
+        // window is about to fill up; until then it is needed, unstored, as the start of h_k or not at all)
+        if (adv || (pd > 0 && p.write_hk)) {
+#pragma unroll
+            for (int i = 0; i < NT; ++i)
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    const bf8 Aw = row16(sWj + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1));
+                    st[i][q] = mfma16(Aw, Xop[i], st[i][q] * alphaJ);
+                    if (adv) __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstJ + ((i * NQ + q) << 8)));
+                }
+        }
+        // (iii) + (iv): the drafts, and the snapshot h_k (Algorithm 2), unless every accepted token is to stay pending
+        if (p.write_hk) {
+#pragma unroll
+            for (int i = 0; i < NT; ++i)
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    const bf8 Aw = row16(sWk + ((g >> 1) * N + 16 * q + li) * XS + 8 * (g & 1));
+                    st[i][q] = mfma16(Aw, Xop[i], st[i][q] * beta);
+                    __builtin_nontemporal_store(st[i][q], reinterpret_cast<v4f *>(dstK + ((i * NQ + q) << 8)));
+                }
         }
     }
     SSMV_TP(6);
