@@ -114,6 +114,7 @@ void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32
     __shared__ __attribute__((aligned(16))) uint16_t sWj[2 * N * XS];      // w^j_s B_s   [head|tail][n][token]
     __shared__ __attribute__((aligned(16))) uint16_t sWk[2 * N * XS];      // w^k_s B_s
     __shared__ __attribute__((aligned(16))) uint16_t sM[2 * 16 * XS];      // M           [head|tail][draft][token]
+    __shared__ uint16_t sDtRaw[16];                                        // dt of the launch's tokens, raw
 
     const unsigned tid = threadIdx.x, l = tid & 63u, w = __builtin_amdgcn_readfirstlane(tid >> 6), li = l & 15u, g = l >> 4;
     const int tile = blockIdx.x, hd = blockIdx.y, b = blockIdx.z;
@@ -196,7 +197,7 @@ void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32
 
     // ---- token loads: whole rows in 16-byte pieces, a few instructions per wave, all issued before the state loads -------
     // wave 0: the raw x rows (history out of the ring, pending tokens out of the stash, this call's tokens); wave 1: the B
-    // rows; wave 2: the C rows; wave 3: conv taps and bias.  Every wave: dt of token li in lane li.
+    // rows; wave 2: the C rows; wave 3: conv taps and bias, and dt of token li in lane li.
     // Loads are unconditional inside a role (rows past the last one read the last one again and are dropped at the use):
     // a load under a lane mask, or one merged with a constant, makes the compiler wait for it on the spot.
     u4v xk[XIT], bk[BIT], ck[3];                         // one set per role: no value is merged across the roles
@@ -231,9 +232,11 @@ void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32
         if constexpr (RW / 2 > 64) ck[1] = wsrc[64 + l];
         ck[2] = (p.bias ? reinterpret_cast<const u4v *>(static_cast<const uint16_t *>(p.bias) + ch0) : wsrc)[l % CX];
     }
-    // every wave: dt of token li in lane li (lanes past the last token read the last one)
-    uint32_t dt_raw;
-    {
+    // dt of token li in lane li (lanes past the last token read the last one).  One wave fetches it for the workgroup (it
+    // goes round through LDS with the rows): sixteen 2-byte reads out of sixteen cache lines per wave were half of the
+    // line requests of the token phase when every wave made them
+    uint32_t dt_raw = 0;
+    if (w == 3) {
         const int tt = min((int)li, T - 1);
         dt_raw = tt < pq ? *stashed(winDt, winDt_out, oDt_win, tt, H) : (dtp + oDt_in)[(tt - pq) * H];
     }
@@ -311,6 +314,9 @@ void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32
         if ((int)l < CX) reinterpret_cast<u4v *>(sBias)[l] = p.bias ? ck[2] : u4v{0u, 0u, 0u, 0u};
     }
     SSMV_TP(3);
+    if (w == 3 && l < 16) sDtRaw[l] = (uint16_t)dt_raw;
+    __syncthreads();
+    dt_raw = sDtRaw[li];
 
     // ---- decay factors and weights: every wave, lane li = token li ---------------------------------------------------------
     float dtv = bf16lo(dt_raw);
@@ -331,7 +337,6 @@ void verify_mfma_kernel(const int32_t *a_cur, const int32_t *a_pend, const int32
         if (g == 0 && (int)li >= pq && (int)li < T) winDt_out[oDt_win + (size_t)out_entry(li - pq) * H] = (uint16_t)dt_raw;   // the raw dt: replay transforms it again
         if (hd == 0 && tid == 0) p.last_k[b] = t0 + kb;
     }
-    __syncthreads();
 
     // ---- x: conv roll, stash, and the [row][token] operand.  An item is two adjacent channels x two adjacent token slots ----
     {
